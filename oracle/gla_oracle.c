@@ -1,0 +1,209 @@
+/*
+ * CPU oracle for decode attention over a paged latent / tied-state cache.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  It shares no code with the GPU path and is
+ * only ever loaded by the tests, the smoke check and the benchmark's CPU
+ * baseline leg.
+ *
+ * What it computes (written from the paper, in its notation):
+ *
+ *   GLA, absorbed decode (Section 3.3.2; the score with the decoupled RoPE
+ *   term is the sum form given for MLA in Section 2.1): the query heads are
+ *   split into h_c groups of g_q = h_q / h_c consecutive heads; head h of group
+ *   g = h / g_q attends to latent head c_g only,
+ *        s_j  = scale * ( q_nope . c_g[j]  +  q_rope . k_rope[j] )
+ *        p    = softmax_j(s)
+ *        out  = sum_j p_j * c_g[j]                       (latent-space output)
+ *   The RoPE key k_rope[j] is ONE vector per token shared by every head.
+ *
+ *   GTA (Section 3.3.1): the tied state of group g is the value V; the key is
+ *   concat(first d_n = d_h/2 dims of the tied state, shared RoPE key); so the
+ *   same formula applies with the dot product q_nope . c_g[j] running over the
+ *   first d_n dims only while the output uses all d_v dims.
+ *
+ *   Visible keys: key j of sequence b is visible to query row t (0-based, of T
+ *   rows that are the LAST T cached positions) iff j < L_b - T + 1 + t when
+ *   causal, j < L_b otherwise.  A row with no visible key yields out = 0 and
+ *   lse = -infinity.
+ *
+ *   lse = m + ln( sum_j exp(s_j - m) ),  m = max_j s_j   (natural log).
+ *
+ * Everything is two-pass and accumulated in fp64; bf16 inputs are widened
+ * exactly.  No blocking, no online softmax, no fusion.
+ *
+ * Pins (tests/test_oracle_pins.py): equality with explicit up-projected
+ * attention, with an assembled-K GQA for GTA, closed forms, paging invariance,
+ * split/merge identity.  No function here is unpinned.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static inline double bf16_to_f64(uint16_t v) {
+  uint32_t u = ((uint32_t)v) << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return (double)f;
+}
+
+/* Number of threads the parallel loops will use. */
+int gla_oracle_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/*
+ * One decode call.
+ *
+ *  q_nope      [B, T, h_q, d_n]   bf16 bits
+ *  q_rope      [B, T, h_q, d_r]   bf16 bits (ignored when d_r == 0)
+ *  state       [n_pages, h_c, P, d_v] bf16 bits
+ *  rope        [n_pages, P, d_r]  bf16 bits
+ *  page_table  [B, max_pages]     int32; entries past ceil(L_b / P) never read
+ *  seq_lens    [B]                int32
+ *  key_begin, key_end             only keys j in [key_begin, key_end) take part
+ *                                 (pass 0 and INT64_MAX for the whole context);
+ *                                 used to produce the partial results of a
+ *                                 split over the key axis
+ *  sel, n_sel                     optional list of (b, t, h) int32 triples; when
+ *                                 given only those rows are computed and the
+ *                                 outputs are indexed by list position
+ *  out         [rows, d_v] fp64, lse [rows] fp64
+ *  weights     optional [rows, w_stride] fp64 softmax weights (0 beyond the
+ *              visible range), for the row-sum pin
+ *
+ *  returns 0, or -1 on a bad argument.
+ */
+int gla_oracle_decode(const uint16_t* q_nope, const uint16_t* q_rope, const uint16_t* state,
+                      const uint16_t* rope, const int32_t* page_table, const int32_t* seq_lens,
+                      int B, int T, int h_q, int h_c, int d_v, int d_n, int d_r, int P,
+                      int max_pages, double scale, int causal, int64_t key_begin,
+                      int64_t key_end, const int32_t* sel, int64_t n_sel, double* out,
+                      double* lse, double* weights, int64_t w_stride) {
+  if (B < 0 || T < 1 || h_q < 1 || h_c < 1 || h_q % h_c != 0 || d_v < 1 || d_n < 0 ||
+      d_n > d_v || d_r < 0 || P < 1)
+    return -1;
+  const int g_q = h_q / h_c;
+  const int64_t rows = sel ? n_sel : (int64_t)B * T * h_q;
+  int64_t max_len = 0;
+  for (int b = 0; b < B; ++b)
+    if (seq_lens[b] > max_len) max_len = seq_lens[b];
+  int failed = 0;
+
+#pragma omp parallel
+  {
+    double* s = (double*)malloc(sizeof(double) * (size_t)(max_len > 0 ? max_len : 1));
+    if (!s) {
+#pragma omp atomic write
+      failed = 1;
+    }
+#pragma omp for schedule(dynamic, 1)
+    for (int64_t r = 0; r < rows; ++r) {
+      if (!s) continue;
+      int b, t, h;
+      if (sel) {
+        b = sel[3 * r + 0];
+        t = sel[3 * r + 1];
+        h = sel[3 * r + 2];
+      } else {
+        b = (int)(r / ((int64_t)T * h_q));
+        t = (int)((r / h_q) % T);
+        h = (int)(r % h_q);
+      }
+      const int g = h / g_q;
+      const int64_t L = seq_lens[b];
+      int64_t n_vis = causal ? L - T + 1 + t : L;
+      int64_t j0 = key_begin > 0 ? key_begin : 0;
+      int64_t j1 = key_end < n_vis ? key_end : n_vis;
+      double* o = out + r * d_v;
+      for (int d = 0; d < d_v; ++d) o[d] = 0.0;
+      if (weights)
+        for (int64_t j = 0; j < w_stride; ++j) weights[r * w_stride + j] = 0.0;
+      if (j1 <= j0) {
+        lse[r] = -INFINITY;
+        continue;
+      }
+      const uint16_t* qn = q_nope + (((int64_t)b * T + t) * h_q + h) * d_n;
+      const uint16_t* qr = q_rope ? q_rope + (((int64_t)b * T + t) * h_q + h) * d_r : NULL;
+
+      /* pass 1: scores and their maximum */
+      double m = -INFINITY;
+      for (int64_t j = j0; j < j1; ++j) {
+        const int64_t page = page_table[(int64_t)b * max_pages + j / P];
+        const int64_t off = j % P;
+        const uint16_t* c = state + ((page * h_c + g) * P + off) * d_v;
+        double acc = 0.0;
+        for (int d = 0; d < d_n; ++d) acc += bf16_to_f64(qn[d]) * bf16_to_f64(c[d]);
+        if (d_r > 0) {
+          const uint16_t* k = rope + (page * P + off) * d_r;
+          for (int d = 0; d < d_r; ++d) acc += bf16_to_f64(qr[d]) * bf16_to_f64(k[d]);
+        }
+        const double sj = scale * acc;
+        s[j - j0] = sj;
+        if (sj > m) m = sj;
+      }
+      /* pass 2: normaliser */
+      double l = 0.0;
+      for (int64_t j = j0; j < j1; ++j) l += exp(s[j - j0] - m);
+      lse[r] = m + log(l);
+      /* pass 3: weighted sum of the SAME cached vectors (all d_v dims) */
+      for (int64_t j = j0; j < j1; ++j) {
+        const double p = exp(s[j - j0] - m) / l;
+        if (weights && j < w_stride) weights[r * w_stride + j] = p;
+        const int64_t page = page_table[(int64_t)b * max_pages + j / P];
+        const int64_t off = j % P;
+        const uint16_t* c = state + ((page * h_c + g) * P + off) * d_v;
+        for (int d = 0; d < d_v; ++d) o[d] += p * bf16_to_f64(c[d]);
+      }
+    }
+    free(s);
+  }
+  return failed ? -1 : 0;
+}
+
+/*
+ * Merge of partial results taken over disjoint key ranges.  Softmax over a
+ * union of ranges, written in terms of each range's own normalised output O_s
+ * and log-sum-exp lse_s:
+ *      lse = ln sum_s exp(lse_s)
+ *      out = sum_s exp(lse_s - lse) * O_s
+ * A part with lse_s = -inf (no keys) contributes nothing; if every part is
+ * empty the result is out = 0, lse = -inf.
+ *
+ *  part_out [n_parts, rows, d_v], part_lse [n_parts, rows]
+ */
+int gla_oracle_merge(const double* part_out, const double* part_lse, int n_parts, int64_t rows,
+                     int d_v, double* out, double* lse) {
+  if (n_parts < 1 || rows < 0 || d_v < 1) return -1;
+  for (int64_t r = 0; r < rows; ++r) {
+    double m = -INFINITY;
+    for (int s = 0; s < n_parts; ++s)
+      if (part_lse[(int64_t)s * rows + r] > m) m = part_lse[(int64_t)s * rows + r];
+    double* o = out + r * d_v;
+    for (int d = 0; d < d_v; ++d) o[d] = 0.0;
+    if (m == -INFINITY) {
+      lse[r] = -INFINITY;
+      continue;
+    }
+    double z = 0.0;
+    for (int s = 0; s < n_parts; ++s) z += exp(part_lse[(int64_t)s * rows + r] - m);
+    const double total = m + log(z);
+    lse[r] = total;
+    for (int s = 0; s < n_parts; ++s) {
+      const double ls = part_lse[(int64_t)s * rows + r];
+      if (ls == -INFINITY) continue;
+      const double w = exp(ls - total);
+      const double* po = part_out + ((int64_t)s * rows + r) * d_v;
+      for (int d = 0; d < d_v; ++d) o[d] += w * po[d];
+    }
+  }
+  return 0;
+}

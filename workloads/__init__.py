@@ -1,0 +1,203 @@
+"""Seeded synthetic decode workloads (inputs only).
+
+This module builds the INPUTS of a decode-attention call over a paged cache:
+absorbed queries, paged latent / tied states, the shared RoPE-key pages, a page
+table and per-sequence lengths.  It holds none of the attention arithmetic and
+is imported by both the CPU oracle's tests and the GPU path's tests/bench, which
+otherwise share nothing.
+
+Shapes follow the paper's kernel benchmarks (GLA: 2 latent heads of 256 plus a
+RoPE key of 64, MLA: one latent head of 512 plus 64, page size 64; Section 5.3
+and Appendix B.5) and its tied-state definition for GTA (Section 3.3.1).  All
+values are bf16 draws from N(0, 1) from a seeded CPU generator.
+
+Storage is "compact": only the pages a batch really uses are materialised
+(`state_pages[i]`, `rope_pages[i]`), together with `page_ids[i]`, the physical
+slot that page occupies in a much larger pool.  The CPU side consumes the
+compact arrays through `table_compact`; the GPU side scatters them into a pool
+of `num_pages` slots and uses `table_pool`.  Both describe the same logical
+cache.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+BASE_SEED = 250521487
+
+
+@dataclasses.dataclass
+class DecodeProblem:
+    name: str
+    kind: str            # "gla" (d_n == d_v) or "gta" (d_n == d_v // 2)
+    B: int
+    T: int               # query length, 1..4
+    h_q: int
+    h_c: int             # latent heads (GLA) / tied KV heads (GTA)
+    d_v: int
+    d_n: int
+    d_r: int
+    page_size: int
+    max_pages: int       # row length of the page tables
+    num_pages: int       # physical pool size
+    scale: float
+    causal: int
+    seq_lens: np.ndarray          # int32 [B]
+    q_nope: torch.Tensor          # bf16 [B, T, h_q, d_n]
+    q_rope: torch.Tensor          # bf16 [B, T, h_q, d_r]
+    state_pages: torch.Tensor     # bf16 [n_used, h_c, page_size, d_v]
+    rope_pages: torch.Tensor      # bf16 [n_used, page_size, d_r]
+    page_ids: np.ndarray          # int64 [n_used] physical slot of compact page i
+    table_compact: np.ndarray     # int32 [B, max_pages] -> compact index, -1 unused
+    table_pool: np.ndarray        # int32 [B, max_pages] -> physical slot, -1 unused
+
+    @property
+    def g_q(self) -> int:
+        return self.h_q // self.h_c
+
+    @property
+    def total_tokens(self) -> int:
+        return int(np.maximum(self.seq_lens, 0).astype(np.int64).sum())
+
+    @property
+    def cache_bytes_per_token(self) -> int:
+        return 2 * (self.h_c * self.d_v + self.d_r)
+
+
+def _bits(t: torch.Tensor) -> np.ndarray:
+    """bf16 tensor -> uint16 bit patterns (numpy has no bf16)."""
+    return t.contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def bf16_bits(t: torch.Tensor) -> np.ndarray:
+    return _bits(t)
+
+
+def make_problem(
+    name: str,
+    *,
+    kind: str = "gla",
+    seq_lens: Sequence[int],
+    T: int = 1,
+    h_q: int,
+    h_c: int,
+    d_v: int,
+    d_r: int = 64,
+    page_size: int = 64,
+    num_pages: Optional[int] = None,
+    identity_table: bool = False,
+    scale: Optional[float] = None,
+    causal: int = 1,
+    seed: int = BASE_SEED,
+    q_gain: float = 1.0,
+    poison_tail: bool = False,
+    extra_table_cols: int = 0,
+) -> DecodeProblem:
+    """Draw one decode problem.
+
+    q_gain > 1 makes the softmax peaky (large outputs, heavy rescaling).
+    poison_tail writes NaN into every cached slot at or beyond a sequence's
+    length inside its last page: no correct implementation may read them into
+    a result.
+    """
+    assert kind in ("gla", "gta")
+    d_n = d_v if kind == "gla" else d_v // 2
+    if scale is None:
+        scale = 1.0 / math.sqrt(d_n + d_r)
+    seq = np.asarray(seq_lens, dtype=np.int32)
+    B = int(seq.shape[0])
+    pages_per_seq = (np.maximum(seq, 0).astype(np.int64) + page_size - 1) // page_size
+    n_used = int(pages_per_seq.sum())
+    max_pages = int(max(1, pages_per_seq.max() if B else 1)) + int(extra_table_cols)
+    if num_pages is None:
+        num_pages = max(n_used, 1)
+    assert num_pages >= n_used
+
+    g = torch.Generator(device="cpu")
+    g.manual_seed(int(seed))
+    q_nope = (torch.randn(B, T, h_q, d_n, generator=g) * q_gain).to(torch.bfloat16)
+    q_rope = (torch.randn(B, T, h_q, d_r, generator=g) * q_gain).to(torch.bfloat16)
+    state_pages = torch.randn(max(n_used, 1), h_c, page_size, d_v, generator=g).to(torch.bfloat16)
+    rope_pages = torch.randn(max(n_used, 1), page_size, d_r, generator=g).to(torch.bfloat16)
+
+    if identity_table:
+        page_ids = np.arange(n_used, dtype=np.int64)
+    else:
+        perm = torch.randperm(int(num_pages), generator=g).numpy().astype(np.int64)
+        page_ids = perm[:n_used].copy()
+
+    table_compact = np.full((B, max_pages), -1, dtype=np.int32)
+    table_pool = np.full((B, max_pages), -1, dtype=np.int32)
+    cur = 0
+    for b in range(B):
+        n = int(pages_per_seq[b])
+        table_compact[b, :n] = np.arange(cur, cur + n, dtype=np.int32)
+        table_pool[b, :n] = page_ids[cur:cur + n].astype(np.int32)
+        if poison_tail and n > 0:
+            used = int(seq[b]) - (n - 1) * page_size
+            if used < page_size:
+                state_pages[cur + n - 1, :, used:, :] = float("nan")
+                rope_pages[cur + n - 1, used:, :] = float("nan")
+        cur += n
+
+    return DecodeProblem(
+        name=name, kind=kind, B=B, T=T, h_q=h_q, h_c=h_c, d_v=d_v, d_n=d_n, d_r=d_r,
+        page_size=page_size, max_pages=max_pages, num_pages=int(num_pages),
+        scale=float(scale), causal=int(causal), seq_lens=seq,
+        q_nope=q_nope, q_rope=q_rope, state_pages=state_pages[:max(n_used, 1)],
+        rope_pages=rope_pages[:max(n_used, 1)], page_ids=page_ids,
+        table_compact=table_compact, table_pool=table_pool,
+    )
+
+
+# --------------------------------------------------------------------------
+# The five benchmark configurations (index = position in the config list).
+# --------------------------------------------------------------------------
+
+POOL_PAGES = 600_000
+
+
+def log_uniform_lengths(n: int, lo: int, hi: int, seed: int) -> np.ndarray:
+    g = torch.Generator(device="cpu")
+    g.manual_seed(int(seed))
+    u = torch.rand(n, generator=g, dtype=torch.float64).numpy()
+    return np.floor(np.exp(math.log(lo) + u * (math.log(hi) - math.log(lo)))).astype(np.int32)
+
+
+def uniform_lengths(n: int, lo: int, hi: int, seed: int) -> np.ndarray:
+    g = torch.Generator(device="cpu")
+    g.manual_seed(int(seed))
+    return torch.randint(lo, hi + 1, (n,), generator=g).numpy().astype(np.int32)
+
+
+def config(index: int, *, T: Optional[int] = None, draw: int = 0, batch: Optional[int] = None,
+           max_len: Optional[int] = None) -> DecodeProblem:
+    """BASELINE configuration `index` (0-based).  `draw` selects a disjoint
+    re-draw of values and page ids (seed offset); `batch` / `max_len` shrink the
+    problem for quick tests while keeping its head and cache shape."""
+    seed = BASE_SEED + index + 1000 * draw
+    if index == 0:
+        return make_problem("tiny_gla2", seq_lens=[256] * (batch or 1), T=T or 1, h_q=16, h_c=2,
+                            d_v=256, identity_table=True, seed=seed)
+    if index == 1:
+        L = min(8192, max_len or 8192)
+        return make_problem("gla2_b64_l8192", seq_lens=[L] * (batch or 64), T=T or 1, h_q=128,
+                            h_c=2, d_v=256, num_pages=POOL_PAGES, seed=seed)
+    if index == 2:
+        L = min(16384, max_len or 16384)
+        return make_problem("gla2_spec_b32_l16384", seq_lens=[L] * (batch or 32), T=T or 2,
+                            h_q=128, h_c=2, d_v=256, num_pages=POOL_PAGES, seed=seed)
+    if index == 3:
+        lens = log_uniform_lengths(batch or 128, 512, max_len or 32768, seed + 7)
+        return make_problem("mla_ragged_b128", seq_lens=lens, T=T or 1, h_q=128, h_c=1,
+                            d_v=512, num_pages=POOL_PAGES, seed=seed)
+    if index == 4:
+        hi = max_len or 32768
+        lens = uniform_lengths(batch or 128, min(4096, hi), hi, seed + 7)
+        return make_problem("gta4_b128", kind="gta", seq_lens=lens, T=T or 1, h_q=32, h_c=4,
+                            d_v=128, num_pages=POOL_PAGES, seed=seed)
+    raise ValueError(f"no config {index}")
