@@ -1,0 +1,136 @@
+/*
+ * gla_decode.h — C ABI of the MI355X (gfx950) decode-attention library for
+ * Grouped Latent Attention (GLA) and Grouped-Tied Attention (GTA).
+ *
+ * Operation (paper Sections 2.1, 3.3.1, 3.3.2).  For every sequence b, query
+ * row t in [0, q_len) and query head h (group g = h / (num_q_heads/num_groups),
+ * heads of a group are a contiguous block):
+ *
+ *     s_j  = softmax_scale * ( q_nope[b,t,h,:d_nope] . state[b,j,g,:d_nope]
+ *                            + q_rope[b,t,h,:]       . rope[b,j,:] )
+ *     lse  = ln sum_j exp(s_j)                          over the visible keys j
+ *     out  = sum_j exp(s_j - lse) * state[b,j,g,:d_v]
+ *
+ * i.e. attention in the weight-absorbed form: each group's queries score
+ * directly against that group's cached state (latent head c_g for GLA, tied KV
+ * head for GTA) plus ONE decoupled-RoPE key per token shared by all heads, and
+ * the same cached state is the value, so the output stays in the state's space.
+ *   gla_decode: d_nope == d_v (GLA; num_groups == 1 is the MLA shape).
+ *   gta_decode: d_nope == d_v / 2 (the key reuses only the first half of the
+ *               tied state; the RoPE half comes from the shared key).
+ * Visible keys: j < L_b - q_len + 1 + t when causal (the q_len queries are the
+ * last q_len cached positions, as in linear-chain speculative decoding), else
+ * j < L_b, with L_b = seq_lens[b].  A row with no visible key gets out = 0 and
+ * lse = -inf.
+ *
+ * The cache is paged: token j of sequence b lives in physical page
+ * page_table[b][j / page_size] at slot j % page_size.  Slots at or beyond L_b
+ * and table entries at or beyond ceil(L_b / page_size) are never read.
+ *
+ * Ownership and execution.  Every pointer in the struct is a DEVICE pointer
+ * owned by the caller unless stated otherwise; the library allocates no device
+ * memory, never synchronises the device and never blocks: it enqueues a few
+ * kernels on `stream` and returns.  Intermediate results (partial outputs of
+ * the split over the key axis) go to the caller's `workspace`.  All functions
+ * are thread-safe for distinct streams and workspaces.
+ *
+ * Errors.  Functions return GLA_OK (0) or a negative GLA_ERR_* code; nothing
+ * is enqueued when an error is returned.  Only host-visible fields can be
+ * validated; device contents (page ids, lengths) are trusted.
+ */
+#ifndef GLA_DECODE_H_
+#define GLA_DECODE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  GLA_OK = 0,
+  GLA_ERR_INVALID_ARG = -1,        /* null pointer, bad count, h_q % h_c != 0, q_len outside 1..4 ... */
+  GLA_ERR_UNSUPPORTED_SHAPE = -2,  /* valid problem, but no kernel for it (see `impl`)               */
+  GLA_ERR_WORKSPACE_TOO_SMALL = -3,
+  GLA_ERR_LAUNCH = -4              /* the HIP runtime refused a launch                                */
+};
+
+enum {
+  GLA_IMPL_AUTO = 0,     /* tuned MFMA kernel when the shape has one, else the generic kernel */
+  GLA_IMPL_GENERIC = 1,  /* shape-agnostic scalar kernel (any dims, any page size)            */
+  GLA_IMPL_TUNED = 2     /* tuned kernel or GLA_ERR_UNSUPPORTED_SHAPE                          */
+};
+
+enum { GLA_OUT_BF16 = 0, GLA_OUT_FP32 = 1 };
+
+typedef struct gla_decode_params {
+  int32_t batch;              /* B >= 0                                                        */
+  int32_t q_len;              /* T in 1..4                                                     */
+  int32_t num_q_heads;        /* h_q                                                           */
+  int32_t num_groups;         /* h_c (GLA latent heads / GTA tied KV heads); divides h_q       */
+  int32_t d_v;                /* state dim used as value (GLA: d_c, GTA: d_h)                  */
+  int32_t d_nope;             /* leading state dims used in the score                          */
+  int32_t d_rope;             /* shared RoPE key dim (0 allowed on the generic kernel)         */
+  int32_t page_size;          /* tokens per page                                               */
+  int32_t max_pages_per_seq;  /* row length of page_table                                      */
+  int32_t causal;             /* 1: row t sees j <= L_b - q_len + t ; 0: every j < L_b         */
+  int64_t num_pages;          /* pool size (used for argument checks only)                     */
+
+  /* Strides are in ELEMENTS; the last dimension is always contiguous. */
+  const void* q_nope;         /* bf16 [B, T, h_q, d_nope]                                      */
+  int64_t q_nope_stride[3];   /* strides of (b, t, h)                                          */
+  const void* q_rope;         /* bf16 [B, T, h_q, d_rope]                                      */
+  int64_t q_rope_stride[3];
+  const void* state_cache;    /* bf16 [num_pages, h_c, page_size, d_v]                         */
+  int64_t state_stride[3];    /* strides of (page, group, token)                               */
+  const void* rope_cache;     /* bf16 [num_pages, page_size, d_rope]                           */
+  int64_t rope_stride[2];     /* strides of (page, token)                                      */
+  const int32_t* page_table;  /* int32 [B, max_pages_per_seq], row-major                       */
+  const int32_t* seq_lens;    /* int32 [B]; cached tokens INCLUDING the q_len newest ones      */
+
+  float softmax_scale;        /* multiplies the summed (nope + rope) score                     */
+  int32_t out_dtype;          /* GLA_OUT_BF16 or GLA_OUT_FP32                                  */
+  void* out;                  /* [B, T, h_q, d_v] of out_dtype                                 */
+  int64_t out_stride[3];      /* strides of (b, t, h)                                          */
+  float* lse;                 /* fp32 [B, T, h_q] contiguous; natural log                      */
+
+  void* workspace;            /* >= gla_decode_workspace_size() bytes, 256-byte aligned        */
+  size_t workspace_bytes;
+  int32_t num_splits;         /* 0 = automatic.  n > 0: cut the key axis so that a sequence of
+                                 max_pages_per_seq pages falls into about n chunks            */
+  int32_t impl;               /* GLA_IMPL_*                                                    */
+  void* stream;               /* hipStream_t (0 = the null stream)                             */
+} gla_decode_params;
+
+/* GLA / MLA-shape decode (Section 3.3.2).  Requires d_nope == d_v. */
+int gla_decode(const gla_decode_params* p);
+
+/* GTA decode (Section 3.3.1).  Requires d_nope == d_v / 2 (d_v even). */
+int gta_decode(const gla_decode_params* p);
+
+/* Bytes of workspace a call with these parameters needs (host only; pointer
+ * fields are ignored).  Returns 0 for an invalid parameter set. */
+size_t gla_decode_workspace_size(const gla_decode_params* p, int is_gta);
+
+/* Which implementation a call would run: GLA_IMPL_GENERIC or GLA_IMPL_TUNED,
+ * or a negative error code.  Host only; pointer fields are ignored. */
+int gla_decode_select_impl(const gla_decode_params* p, int is_gta);
+
+/* Benchmark helper: enqueue `iters` calls (1..256) bracketed by HIP events on
+ * p->stream, wait for them, and report the mean duration in microseconds of
+ * the main (split-KV attention) kernel and of the combine kernel.  This call
+ * DOES synchronise the stream.  Host pointers for the two results. */
+int gla_decode_profile(const gla_decode_params* p, int is_gta, int iters, float* main_us,
+                       float* combine_us);
+
+/* Static, NUL-terminated description of a status code. */
+const char* gla_status_string(int status);
+
+/* ABI version (major * 100 + minor). */
+int gla_decode_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GLA_DECODE_H_ */

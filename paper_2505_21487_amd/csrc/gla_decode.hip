@@ -1,0 +1,217 @@
+// Host side of the decode-attention library: argument checks, kernel choice,
+// workspace sizing and launches.  The exported functions and their contracts
+// are declared in include/gla_decode.h.
+#include "../../include/gla_decode.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+
+#include "common.hpp"
+#include "generic_kernels.hpp"
+#include "tuned_kernels.hpp"
+
+namespace gla {
+namespace {
+
+constexpr int kVersion = 100;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int check_shape(const gla_decode_params* p, int is_gta) {
+  if (!p) return GLA_ERR_INVALID_ARG;
+  if (p->batch < 0 || p->q_len < 1 || p->q_len > 4) return GLA_ERR_INVALID_ARG;
+  if (p->num_q_heads < 1 || p->num_groups < 1 || p->num_q_heads % p->num_groups != 0)
+    return GLA_ERR_INVALID_ARG;
+  if (p->d_v < 1 || p->d_nope < 1 || p->d_rope < 0) return GLA_ERR_INVALID_ARG;
+  if (is_gta) {
+    if (p->d_v % 2 != 0 || p->d_nope != p->d_v / 2) return GLA_ERR_INVALID_ARG;
+  } else {
+    if (p->d_nope != p->d_v) return GLA_ERR_INVALID_ARG;
+  }
+  if (p->page_size < 1 || p->max_pages_per_seq < 1 || p->num_pages < 0) return GLA_ERR_INVALID_ARG;
+  if (p->num_splits < 0) return GLA_ERR_INVALID_ARG;
+  if (p->out_dtype != GLA_OUT_BF16 && p->out_dtype != GLA_OUT_FP32) return GLA_ERR_INVALID_ARG;
+  if (p->impl != GLA_IMPL_AUTO && p->impl != GLA_IMPL_GENERIC && p->impl != GLA_IMPL_TUNED)
+    return GLA_ERR_INVALID_ARG;
+  if ((int64_t)p->batch * p->q_len * p->num_q_heads > (int64_t)0x7fffffff) return GLA_ERR_INVALID_ARG;
+  return GLA_OK;
+}
+
+bool generic_supported(const gla_decode_params* p) { return p->d_v <= 1024 && p->d_rope <= 128; }
+
+int generic_splits(const gla_decode_params* p) {
+  const int64_t rows = std::max<int64_t>(1, (int64_t)p->batch * p->q_len * p->num_q_heads);
+  int64_t s = p->num_splits > 0 ? p->num_splits : (4096 + rows - 1) / rows;
+  s = std::min<int64_t>(s, p->max_pages_per_seq);
+  s = std::min<int64_t>(s, 65535);
+  return (int)std::max<int64_t>(s, 1);
+}
+
+int select_impl(const gla_decode_params* p, int is_gta) {
+  int rc = check_shape(p, is_gta);
+  if (rc != GLA_OK) return rc;
+  const bool tuned_ok = tuned_supported(p, is_gta);
+  if (p->impl == GLA_IMPL_TUNED) return tuned_ok ? GLA_IMPL_TUNED : GLA_ERR_UNSUPPORTED_SHAPE;
+  if (p->impl == GLA_IMPL_AUTO && tuned_ok) return GLA_IMPL_TUNED;
+  return generic_supported(p) ? GLA_IMPL_GENERIC : GLA_ERR_UNSUPPORTED_SHAPE;
+}
+
+size_t generic_workspace(const gla_decode_params* p) {
+  const int s = generic_splits(p);
+  if (s == 1) return 0;
+  const size_t rows = (size_t)p->batch * p->q_len * p->num_q_heads;
+  return align_up((size_t)s * rows * p->d_v * sizeof(float), 256) +
+         align_up((size_t)s * rows * sizeof(float), 256);
+}
+
+int check_pointers(const gla_decode_params* p) {
+  if (p->batch == 0) return GLA_OK;
+  if (!p->q_nope || !p->state_cache || !p->page_table || !p->seq_lens || !p->out || !p->lse)
+    return GLA_ERR_INVALID_ARG;
+  if (p->d_rope > 0 && (!p->q_rope || !p->rope_cache)) return GLA_ERR_INVALID_ARG;
+  return GLA_OK;
+}
+
+void fill_dev(const gla_decode_params* p, DevParams* d) {
+  std::memset(d, 0, sizeof(*d));
+  d->q_nope = (const uint16_t*)p->q_nope;
+  d->q_rope = (const uint16_t*)p->q_rope;
+  d->state = (const uint16_t*)p->state_cache;
+  d->rope = (const uint16_t*)p->rope_cache;
+  d->page_table = p->page_table;
+  d->seq_lens = p->seq_lens;
+  d->out = p->out;
+  d->lse = p->lse;
+  for (int i = 0; i < 3; ++i) {
+    d->qn_s[i] = p->q_nope_stride[i];
+    d->qr_s[i] = p->q_rope_stride[i];
+    d->st_s[i] = p->state_stride[i];
+    d->out_s[i] = p->out_stride[i];
+  }
+  d->rp_s[0] = p->rope_stride[0];
+  d->rp_s[1] = p->rope_stride[1];
+  d->B = p->batch;
+  d->T = p->q_len;
+  d->h_q = p->num_q_heads;
+  d->h_c = p->num_groups;
+  d->g_q = p->num_q_heads / p->num_groups;
+  d->d_v = p->d_v;
+  d->d_n = p->d_nope;
+  d->d_r = p->d_rope;
+  d->P = p->page_size;
+  d->max_pages = p->max_pages_per_seq;
+  d->causal = p->causal ? 1 : 0;
+  d->out_fp32 = p->out_dtype == GLA_OUT_FP32;
+  d->scale = p->softmax_scale;
+}
+
+int launch_generic(const gla_decode_params* p, DevParams& d, hipStream_t st, hipEvent_t* ev) {
+  const int s = generic_splits(p);
+  d.splits = s;
+  d.pages_per_split = (p->max_pages_per_seq + s - 1) / s;
+  const size_t rows = (size_t)p->batch * p->q_len * p->num_q_heads;
+  if (s > 1) {
+    d.ws_out = (float*)p->workspace;
+    d.ws_lse = (float*)((char*)p->workspace + align_up((size_t)s * rows * p->d_v * sizeof(float), 256));
+  }
+  dim3 grid((unsigned)rows, (unsigned)s), block(64);
+  const int nv = (p->d_v + 63) / 64;
+  if (ev) (void)hipEventRecord(ev[0], st);
+  if (nv <= 2) hipLaunchKernelGGL(generic_main_kernel<2>, grid, block, 0, st, d);
+  else if (nv <= 4) hipLaunchKernelGGL(generic_main_kernel<4>, grid, block, 0, st, d);
+  else if (nv <= 8) hipLaunchKernelGGL(generic_main_kernel<8>, grid, block, 0, st, d);
+  else hipLaunchKernelGGL(generic_main_kernel<16>, grid, block, 0, st, d);
+  if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
+  if (ev) (void)hipEventRecord(ev[1], st);
+  if (s > 1) {
+    hipLaunchKernelGGL(generic_combine_kernel, dim3((unsigned)rows), block, 0, st, d);
+    if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
+  }
+  if (ev) (void)hipEventRecord(ev[2], st);
+  return GLA_OK;
+}
+
+int run(const gla_decode_params* p, int is_gta, hipEvent_t* ev) {
+  const int impl = select_impl(p, is_gta);
+  if (impl < 0) return impl;
+  int rc = check_pointers(p);
+  if (rc != GLA_OK) return rc;
+  if (p->batch == 0) return GLA_OK;
+  const size_t need = impl == GLA_IMPL_TUNED ? tuned_workspace(p, is_gta) : generic_workspace(p);
+  if (need > 0 && (!p->workspace || p->workspace_bytes < need)) return GLA_ERR_WORKSPACE_TOO_SMALL;
+  if (need > 0 && ((uintptr_t)p->workspace & 255u)) return GLA_ERR_INVALID_ARG;
+  DevParams d;
+  fill_dev(p, &d);
+  hipStream_t st = (hipStream_t)p->stream;
+  if (impl == GLA_IMPL_TUNED) return tuned_launch(p, is_gta, d, st, ev);
+  return launch_generic(p, d, st, ev);
+}
+
+}  // namespace
+}  // namespace gla
+
+extern "C" {
+
+int gla_decode(const gla_decode_params* p) { return gla::run(p, 0, nullptr); }
+
+int gta_decode(const gla_decode_params* p) { return gla::run(p, 1, nullptr); }
+
+size_t gla_decode_workspace_size(const gla_decode_params* p, int is_gta) {
+  const int impl = gla::select_impl(p, is_gta);
+  if (impl < 0) return 0;
+  // A little more than nothing, so callers can always pass a real buffer.
+  const size_t need = impl == GLA_IMPL_TUNED ? gla::tuned_workspace(p, is_gta) : gla::generic_workspace(p);
+  return std::max<size_t>(need, 256);
+}
+
+int gla_decode_select_impl(const gla_decode_params* p, int is_gta) {
+  return gla::select_impl(p, is_gta);
+}
+
+int gla_decode_profile(const gla_decode_params* p, int is_gta, int iters, float* main_us,
+                       float* combine_us) {
+  if (!p || !main_us || !combine_us || iters < 1 || iters > 256) return GLA_ERR_INVALID_ARG;
+  hipEvent_t ev[3 * 256];
+  int made = 0;
+  int rc = GLA_OK;
+  for (; made < 3 * iters; ++made)
+    if (hipEventCreate(&ev[made]) != hipSuccess) { rc = GLA_ERR_LAUNCH; break; }
+  for (int i = 0; rc == GLA_OK && i < iters; ++i) rc = gla::run(p, is_gta, &ev[3 * i]);
+  if (hipStreamSynchronize((hipStream_t)p->stream) != hipSuccess && rc == GLA_OK) rc = GLA_ERR_LAUNCH;
+  if (rc == GLA_OK && p->batch > 0) {
+    double a = 0, b = 0;
+    for (int i = 0; i < iters; ++i) {
+      float t0 = 0, t1 = 0;
+      if (hipEventElapsedTime(&t0, ev[3 * i], ev[3 * i + 1]) != hipSuccess ||
+          hipEventElapsedTime(&t1, ev[3 * i + 1], ev[3 * i + 2]) != hipSuccess) {
+        rc = GLA_ERR_LAUNCH;
+        break;
+      }
+      a += t0;
+      b += t1;
+    }
+    *main_us = (float)(a * 1000.0 / iters);
+    *combine_us = (float)(b * 1000.0 / iters);
+  } else {
+    *main_us = *combine_us = 0.f;
+  }
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+  return rc;
+}
+
+const char* gla_status_string(int status) {
+  switch (status) {
+    case GLA_OK: return "ok";
+    case GLA_ERR_INVALID_ARG: return "invalid argument";
+    case GLA_ERR_UNSUPPORTED_SHAPE: return "no kernel for this shape with the requested implementation";
+    case GLA_ERR_WORKSPACE_TOO_SMALL: return "workspace missing or too small";
+    case GLA_ERR_LAUNCH: return "HIP launch or event call failed";
+    default: return "unknown status";
+  }
+}
+
+int gla_decode_version(void) { return gla::kVersion; }
+
+}  // extern "C"

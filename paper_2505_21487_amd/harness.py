@@ -1,0 +1,36 @@
+"""Upload of a synthetic decode problem to GPU memory (plumbing for tests,
+smoke and bench; no arithmetic of the method)."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+
+class DeviceProblem:
+    """Device tensors of one problem: the paged pool holds `num_pages` slots of
+    which only the used ones are written."""
+
+    def __init__(self, p, device="cuda:0", pool=None):
+        dev = torch.device(device)
+        self.p = p
+        self.q_nope = p.q_nope.to(dev)
+        self.q_rope = p.q_rope.to(dev)
+        if pool is None:
+            state = torch.empty(p.num_pages, p.h_c, p.page_size, p.d_v, dtype=torch.bfloat16, device=dev)
+            rope = torch.empty(p.num_pages, p.page_size, p.d_r, dtype=torch.bfloat16, device=dev)
+        else:
+            state, rope = pool
+        n_used = len(p.page_ids)
+        if n_used:
+            ids = torch.from_numpy(np.asarray(p.page_ids, dtype=np.int64)).to(dev)
+            step = 4096
+            for i in range(0, n_used, step):      # bounded staging copies
+                state[ids[i:i + step]] = p.state_pages[i:i + step].to(dev)
+                rope[ids[i:i + step]] = p.rope_pages[i:i + step].to(dev)
+        self.state_cache, self.rope_cache = state, rope
+        self.page_table = torch.from_numpy(p.table_pool).to(dev)
+        self.seq_lens = torch.from_numpy(np.asarray(p.seq_lens, dtype=np.int32)).to(dev)
+
+    def args(self):
+        return (self.q_nope, self.q_rope, self.state_cache, self.rope_cache, self.page_table,
+                self.seq_lens, self.p.scale)

@@ -1,0 +1,153 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on
+the same seeded inputs, element by element."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_21487_amd as gla
+from paper_2505_21487_amd.harness import DeviceProblem
+from workloads import config, make_problem
+
+from gpu_util import check_problem, compare, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+GENERIC, TUNED, AUTO = gla.GLA_IMPL_GENERIC, gla.GLA_IMPL_TUNED, gla.GLA_IMPL_AUTO
+
+# lengths spanning empty, one token, tile edges (63/64/65), several tiles, ragged tails
+RAGGED = [0, 1, 63, 64, 65, 130, 700, 1500, 2, 4]
+
+
+def tuned_available(p):
+    sp = gla.shape_params(batch=p.B, q_len=p.T, num_q_heads=p.h_q, num_groups=p.h_c, d_v=p.d_v,
+                          d_nope=p.d_n, d_rope=p.d_r, page_size=p.page_size,
+                          max_pages_per_seq=p.max_pages, impl=TUNED)
+    return gla.gla_decode_select_impl(sp, p.kind == "gta") == TUNED
+
+
+def impls_for(p):
+    return [GENERIC, TUNED] if tuned_available(p) else [GENERIC]
+
+
+def test_config0_tiny_all_rows():
+    p = config(0)
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, what=f"cfg0 impl={impl}")
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 4])
+def test_gla2_ragged_small(T):
+    p = make_problem("gla2_ragged", seq_lens=RAGGED, T=T, h_q=128, h_c=2, d_v=256, seed=100 + T,
+                     num_pages=4096, poison_tail=True, extra_table_cols=3)
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, what=f"T={T} impl={impl}")
+
+
+@pytest.mark.parametrize("T", [1, 2])
+def test_gla2_few_heads(T):
+    """g_q smaller than a row block: 16 heads in 2 groups."""
+    p = make_problem("gla2_h16", seq_lens=[300, 64, 17], T=T, h_q=16, h_c=2, d_v=256, seed=110 + T,
+                     num_pages=512, poison_tail=True)
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, what=f"T={T} impl={impl}")
+
+
+@pytest.mark.parametrize("splits", [1, 2, 3, 7])
+def test_split_count_does_not_change_the_result(splits):
+    p = make_problem("gla2_splits", seq_lens=[1000, 129, 64, 5], T=2, h_q=128, h_c=2, d_v=256,
+                     seed=120, num_pages=2048, poison_tail=True)
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, num_splits=splits, what=f"splits={splits} impl={impl}")
+
+
+def test_mla_shape_small():
+    p = make_problem("mla_small", seq_lens=[513, 64, 1, 200], h_q=128, h_c=1, d_v=512, seed=130,
+                     num_pages=1024, poison_tail=True)
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, what=f"mla impl={impl}")
+
+
+@pytest.mark.parametrize("T", [1, 3])
+def test_gta_small(T):
+    p = make_problem("gta_small", kind="gta", seq_lens=[700, 65, 1, 0, 128], T=T, h_q=32, h_c=4,
+                     d_v=128, seed=140 + T, num_pages=1024, poison_tail=True, extra_table_cols=1)
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, what=f"gta T={T} impl={impl}")
+
+
+def test_peaky_softmax_fp32_and_bf16_out():
+    """Queries scaled x6: the softmax concentrates on a few keys, outputs are
+    O(1) and the running-max rescaling is exercised."""
+    p = make_problem("peaky", seq_lens=[900, 77], T=2, h_q=128, h_c=2, d_v=256, seed=150,
+                     num_pages=1024, q_gain=6.0, poison_tail=True)
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, out_dtype=torch.float32, what=f"peaky fp32 impl={impl}")
+        check_problem(p, impl=impl, what=f"peaky bf16 impl={impl}", bf16_out_allowance=True)
+
+
+def test_generic_kernel_odd_shapes_and_strides():
+    """Dims, page size and strides with no tuned kernel."""
+    p = make_problem("odd", seq_lens=[37, 5, 0, 90], T=3, h_q=6, h_c=3, d_v=96, d_r=32, page_size=16,
+                     seed=160, num_pages=64, poison_tail=True)
+    check_problem(p, what="odd shapes")
+    dp = DeviceProblem(p)
+    # queries as a slice of a wider buffer, output into a strided view
+    wide = torch.zeros(p.B, p.T, p.h_q, p.d_n + 40, dtype=torch.bfloat16, device="cuda")
+    wide[..., 8:8 + p.d_n] = dp.q_nope
+    dp.q_nope = wide[..., 8:8 + p.d_n]
+    out_wide = torch.zeros(p.B, p.T, p.h_q, p.d_v * 2, dtype=torch.float32, device="cuda")
+    out, lse = gla.gla_decode(*dp.args(), out=out_wide[..., :p.d_v])
+    torch.cuda.synchronize()
+    ref_out, ref_lse = oracle.decode_problem(p)
+    compare(out.double().cpu().numpy(), lse.double().cpu().numpy(), ref_out, ref_lse, what="strided")
+    assert (out_wide[..., p.d_v:] == 0).all()
+
+
+def test_non_causal():
+    p = make_problem("noncausal", seq_lens=[200, 3], T=4, h_q=128, h_c=2, d_v=256, seed=170,
+                     num_pages=256, causal=0)
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, what=f"noncausal impl={impl}")
+
+
+def test_repeat_calls_are_bit_identical():
+    p = make_problem("determinism", seq_lens=[3000, 1000, 64], h_q=128, h_c=2, d_v=256, seed=180,
+                     num_pages=4096)
+    dp = DeviceProblem(p)
+    for impl in impls_for(p):
+        a = run_gpu(p, dp=dp, impl=impl)
+        b = run_gpu(p, dp=dp, impl=impl)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_workspace_too_small_is_reported():
+    p = make_problem("ws", seq_lens=[500], h_q=128, h_c=2, d_v=256, seed=190, num_pages=64)
+    dp = DeviceProblem(p)
+    ws = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(gla.GlaError) as e:
+        gla.gla_decode(*dp.args(), workspace=ws, num_splits=4, impl=GENERIC)
+    assert e.value.status == gla.GLA_ERR_WORKSPACE_TOO_SMALL
+
+
+# ---------------------------------------------------------------- full sizes
+def sample_rows(p, n, seed):
+    rng = np.random.default_rng(seed)
+    rows = set()
+    while len(rows) < n:
+        rows.add((int(rng.integers(p.B)), int(rng.integers(p.T)), int(rng.integers(p.h_q))))
+    return sorted(rows)
+
+
+@pytest.mark.parametrize("index,T", [(1, 1), (2, 2), (2, 4), (3, 1), (4, 1)])
+def test_full_size_configs_on_sampled_rows(index, T):
+    """The launch configuration the benchmark times, at the full size of each
+    configuration; the oracle computes a seeded sample of output rows."""
+    p = config(index, T=T)
+    sel = sample_rows(p, 96, 1000 + index)
+    # always include the rows that end each sequence's causal window for the longest sequence
+    b_long = int(np.argmax(p.seq_lens))
+    sel += [(b_long, t, h) for t in range(p.T) for h in (0, p.h_q - 1)]
+    check_problem(p, sel=sel, what=f"cfg{index} T={T}")
