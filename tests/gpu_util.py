@@ -21,11 +21,13 @@ def run_gpu(p, dp=None, **kw):
     return out.to(torch.float64).cpu().numpy(), lse.to(torch.float64).cpu().numpy()
 
 
-def compare(out, lse, ref_out, ref_lse, *, what="", bf16_out_allowance=False):
-    """Element-wise comparison at the benchmark spec's tolerances.  With
-    bf16_out_allowance, half a bf16 ulp of the reference magnitude (2^-9 |ref|)
-    is added to the absolute bound: needed only where outputs exceed ~1, since
-    rounding the result to bf16 alone then costs more than 5e-3."""
+def compare(out, lse, ref_out, ref_lse, *, what="", bf16_out_allowance=True):
+    """Element-wise comparison at the benchmark spec's tolerances.  When the library
+    writes bf16 (bf16_out_allowance), the rounding of the result itself, up to
+    half a bf16 ulp <= 2^-9 |ref|, is added to the absolute bound: for |ref| >= 2
+    that rounding alone is 7.8e-3 and would exceed 5e-3 however exact the
+    arithmetic.  For the benchmark shapes (|out| << 1) the term is < 2e-4; fp32
+    output is held to 5e-3 flat."""
     assert out.shape == ref_out.shape and lse.shape == ref_lse.shape, what
     assert not np.isnan(out).any(), f"{what}: NaN in out"
     neg = np.isneginf(ref_lse)
@@ -52,7 +54,8 @@ def compare(out, lse, ref_out, ref_lse, *, what="", bf16_out_allowance=False):
         assert worst_row <= 3 * OUT_REL_L2, f"{what}: worst row rel-L2 {worst_row:.3e}"
 
 
-def check_problem(p, *, sel=None, what="", bf16_out_allowance=False, dp=None, **kw):
+def check_problem(p, *, sel=None, what="", dp=None, **kw):
+    bf16_out_allowance = kw.get("out_dtype", torch.bfloat16) == torch.bfloat16
     out, lse = run_gpu(p, dp=dp, **kw)
     if sel is None:
         ref_out, ref_lse = oracle.decode_problem(p)
