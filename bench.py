@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-attention hot path on ONE MI355X.
+
+A "step" is one whole decode call (split-KV attention kernel + combine kernel)
+over one batch of synthetic paged cache that is already resident in HBM.  Two
+disjoint draws of the workload alternate so that no call re-reads the pages of
+the previous one.  Prints one JSON line.
+
+    python bench.py [--steps K] [--warmup W] [--config 1] [--q-len T]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "GLA decode µs/call + achieved HBM GB/s (fraction of peak), q_len 1–4"
+HBM_PEAK_GBPS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def cpu_baseline(p, budget_s: float = 15.0):
+    """Time the fp64 CPU oracle, as it stands, on a bounded sample of the same
+    workload's output rows and extrapolate to the whole call."""
+    import numpy as np
+    import oracle
+    rng = np.random.default_rng(7)
+    total_rows = p.B * p.T * p.h_q
+
+    def draw(n):
+        n = min(n, total_rows)
+        flat = rng.choice(total_rows, size=n, replace=False)
+        return [(int(r // (p.T * p.h_q)), int((r // p.h_q) % p.T), int(r % p.h_q)) for r in flat]
+
+    threads = oracle.threads()
+    probe = draw(4 * threads)
+    t0 = time.perf_counter()
+    oracle.decode_problem(p, sel=probe)
+    dt = time.perf_counter() - t0
+    per_row = dt / len(probe)
+    n = int(max(len(probe), min(total_rows, budget_s / max(per_row, 1e-9))))
+    n = max(threads, (n // threads) * threads)
+    sel = draw(n)
+    t0 = time.perf_counter()
+    oracle.decode_problem(p, sel=sel)
+    dt = time.perf_counter() - t0
+    return {
+        "value": dt / len(sel) * total_rows * 1e6,
+        "unit": "us/call",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": f"{len(sel)} of {total_rows} output rows (b,t,h) drawn uniformly, "
+                  f"{dt:.1f} s wall, extrapolated linearly to the whole call",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="index into the configuration list")
+    ap.add_argument("--q-len", type=int, default=0, help="override query length (1..4)")
+    ap.add_argument("--num-splits", type=int, default=0)
+    ap.add_argument("--impl", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-iters", type=int, default=50)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); nothing here uses a second "
+              "GPU, see DESIGN.md for how the path would shard", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2505_21487_amd as gla
+    from paper_2505_21487_amd import accounting
+    from paper_2505_21487_amd.harness import DeviceProblem
+    from workloads import config
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    T = args.q_len or None
+    p0 = config(args.config, T=T, draw=0, page_offset=0)
+    n_used = len(p0.page_ids)
+    p1 = config(args.config, T=T, draw=1, page_offset=n_used)
+    d0 = DeviceProblem(p0, dev)
+    d1 = DeviceProblem(p1, dev, pool=(d0.state_cache, d0.rope_cache))
+    is_gta = p0.kind == "gta"
+    fn = gla.gta_decode if is_gta else gla.gla_decode
+
+    out = torch.empty(p0.B, p0.T, p0.h_q, p0.d_v, dtype=torch.bfloat16, device=dev)
+    lse = torch.empty(p0.B, p0.T, p0.h_q, dtype=torch.float32, device=dev)
+    prm = [gla.make_params(*d.args()[:6], d.p.scale, out=out, lse=lse, workspace=None,
+                           causal=bool(d.p.causal), num_splits=args.num_splits, impl=args.impl)
+           for d in (d0, d1)]
+    need = gla.gla_decode_workspace_size(prm[0], is_gta)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    impl = gla.gla_decode_select_impl(prm[0], is_gta)
+    for q in prm:
+        q.workspace, q.workspace_bytes = ws.data_ptr(), ws.numel()
+    kw = dict(causal=bool(p0.causal), out=out, lse=lse, workspace=ws, num_splits=args.num_splits,
+              impl=args.impl)
+    probs = (d0, d1)
+
+    for i in range(args.warmup):
+        fn(*probs[i & 1].args(), **kw)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        fn(*probs[i & 1].args(), **kw)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    us_per_call = dt / args.steps * 1e6
+
+    # per-kernel durations from HIP events recorded by the library on its launch stream
+    main_us = comb_us = 0.0
+    for i in range(2):
+        a, b = gla.gla_decode_profile(prm[i], is_gta, args.profile_iters)
+        main_us += a / 2
+        comb_us += b / 2
+
+    cache_b = accounting.cache_bytes(p0.seq_lens, p0.h_c, p0.d_v, p0.d_r)
+    fl = accounting.flops(p0.seq_lens, p0.T, p0.h_q, p0.d_n, p0.d_r, p0.d_v, bool(p0.causal))
+    ai = fl / cache_b
+    ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9)
+    if ai <= ridge:
+        roof = {"bound": "hbm", "achieved": cache_b / (main_us * 1e-6) / 1e9,
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": fl / (main_us * 1e-6) / 1e12,
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = "main (split-KV attention)"
+    roof["kernel_us"] = main_us
+    roof["combine_us"] = comb_us
+
+    rec = {
+        "metric": METRIC,
+        "value": us_per_call,
+        "unit": "us/call",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": us_per_call / 1e3,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {p0.name}: B={p0.B} q_len={p0.T} "
+                               f"h_q={p0.h_q} h_c={p0.h_c} d_v={p0.d_v} d_rope={p0.d_r} "
+                               f"page={p0.page_size} tokens={p0.total_tokens} "
+                               f"pool_pages={p0.num_pages}",
+                   "kind": p0.kind,
+                   "impl": {1: "generic", 2: "tuned"}.get(impl, str(impl)),
+                   "num_splits": args.num_splits},
+        "cache_bytes": cache_b,
+        "cache_GBps": cache_b / (us_per_call * 1e-6) / 1e9,
+        "hbm_frac_of_peak": cache_b / (us_per_call * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+        "tflops": fl / (us_per_call * 1e-6) / 1e12,
+        "flops_per_cache_byte": ai,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(p0)
+    print(json.dumps(rec, ensure_ascii=False), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

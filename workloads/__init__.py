@@ -96,13 +96,17 @@ def make_problem(
     q_gain: float = 1.0,
     poison_tail: bool = False,
     extra_table_cols: int = 0,
+    table_seed: Optional[int] = None,
+    page_offset: int = 0,
 ) -> DecodeProblem:
     """Draw one decode problem.
 
     q_gain > 1 makes the softmax peaky (large outputs, heavy rescaling).
     poison_tail writes NaN into every cached slot at or beyond a sequence's
     length inside its last page: no correct implementation may read them into
-    a result.
+    a result.  Page ids are the slice [page_offset, page_offset + n_used) of a
+    random permutation of the pool drawn from `table_seed` (default: the value
+    seed), so problems sharing a table_seed can occupy disjoint pages of one pool.
     """
     assert kind in ("gla", "gta")
     d_n = d_v if kind == "gla" else d_v // 2
@@ -127,8 +131,13 @@ def make_problem(
     if identity_table:
         page_ids = np.arange(n_used, dtype=np.int64)
     else:
-        perm = torch.randperm(int(num_pages), generator=g).numpy().astype(np.int64)
-        page_ids = perm[:n_used].copy()
+        gt = g
+        if table_seed is not None:
+            gt = torch.Generator(device="cpu")
+            gt.manual_seed(int(table_seed))
+        perm = torch.randperm(int(num_pages), generator=gt).numpy().astype(np.int64)
+        assert page_offset + n_used <= num_pages
+        page_ids = perm[page_offset:page_offset + n_used].copy()
 
     table_compact = np.full((B, max_pages), -1, dtype=np.int32)
     table_pool = np.full((B, max_pages), -1, dtype=np.int32)
@@ -175,29 +184,31 @@ def uniform_lengths(n: int, lo: int, hi: int, seed: int) -> np.ndarray:
 
 
 def config(index: int, *, T: Optional[int] = None, draw: int = 0, batch: Optional[int] = None,
-           max_len: Optional[int] = None) -> DecodeProblem:
-    """BASELINE configuration `index` (0-based).  `draw` selects a disjoint
-    re-draw of values and page ids (seed offset); `batch` / `max_len` shrink the
-    problem for quick tests while keeping its head and cache shape."""
+           max_len: Optional[int] = None, page_offset: int = 0) -> DecodeProblem:
+    """BASELINE configuration `index` (0-based).  `draw` re-draws the values
+    (seed offset) while the pool permutation stays that of draw 0, so draws
+    placed at disjoint `page_offset`s share one pool; `batch` / `max_len` shrink
+    the problem for quick tests while keeping its head and cache shape."""
     seed = BASE_SEED + index + 1000 * draw
+    tbl = dict(table_seed=BASE_SEED + index + 500, page_offset=page_offset)
     if index == 0:
         return make_problem("tiny_gla2", seq_lens=[256] * (batch or 1), T=T or 1, h_q=16, h_c=2,
                             d_v=256, identity_table=True, seed=seed)
     if index == 1:
         L = min(8192, max_len or 8192)
         return make_problem("gla2_b64_l8192", seq_lens=[L] * (batch or 64), T=T or 1, h_q=128,
-                            h_c=2, d_v=256, num_pages=POOL_PAGES, seed=seed)
+                            h_c=2, d_v=256, num_pages=POOL_PAGES, seed=seed, **tbl)
     if index == 2:
         L = min(16384, max_len or 16384)
         return make_problem("gla2_spec_b32_l16384", seq_lens=[L] * (batch or 32), T=T or 2,
-                            h_q=128, h_c=2, d_v=256, num_pages=POOL_PAGES, seed=seed)
+                            h_q=128, h_c=2, d_v=256, num_pages=POOL_PAGES, seed=seed, **tbl)
     if index == 3:
         lens = log_uniform_lengths(batch or 128, 512, max_len or 32768, seed + 7)
         return make_problem("mla_ragged_b128", seq_lens=lens, T=T or 1, h_q=128, h_c=1,
-                            d_v=512, num_pages=POOL_PAGES, seed=seed)
+                            d_v=512, num_pages=POOL_PAGES, seed=seed, **tbl)
     if index == 4:
         hi = max_len or 32768
         lens = uniform_lengths(batch or 128, min(4096, hi), hi, seed + 7)
         return make_problem("gta4_b128", kind="gta", seq_lens=lens, T=T or 1, h_q=32, h_c=4,
-                            d_v=128, num_pages=POOL_PAGES, seed=seed)
+                            d_v=128, num_pages=POOL_PAGES, seed=seed, **tbl)
     raise ValueError(f"no config {index}")
