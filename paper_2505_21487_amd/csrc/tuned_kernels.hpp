@@ -3,13 +3,13 @@
 //
 // Work decomposition.  A "unit" is (sequence b, group g, row block mb): the
 // g_q * T query rows of one group (ordered t-major) cut into blocks of
-// ROWS = 32 * NWAVES rows.  A unit owns ceil(L_b / TOK) key tiles of TOK = 64
-// tokens (one page).  All tiles of all units, in unit order, form one flat list
-// that is cut into equal chunks, one workgroup per chunk, so ragged batches
-// balance by construction and at most two units per chunk are left incomplete.
-// A unit that lies inside one chunk is written straight to the output; one that
-// spans chunks leaves one partial (normalised fp32 output + log-sum-exp) per
-// chunk in the workspace, merged afterwards by tuned_combine_kernel.
+// ROWS = 32 * NWAVES rows.  A unit owns ceil(L_b / TOK) key tiles of TOK tokens
+// (a page of 64 tokens or half of one).  All tiles of all units, in unit order,
+// form one flat list that is cut into equal chunks, one workgroup per chunk, so
+// ragged batches balance by construction and at most two units per chunk are
+// left incomplete.  A unit that lies inside one chunk is written straight to
+// the output; one that spans chunks leaves one partial (normalised fp32 output
+// + log-sum-exp) per chunk in the workspace, merged by tuned_combine_kernel.
 //
 // Inside a workgroup every wave owns 32 query rows and works in the transposed
 // form: S^T = K . Q^T with the key tile as the MFMA A operand (from LDS) and
@@ -20,12 +20,19 @@
 // tile with transposing LDS reads.  Row max / row sum therefore live in one
 // lane plus its partner lane (lane ^ 32): no cross-wave softmax traffic.
 //
+// Tiles travel HBM -> LDS with direct-to-LDS loads through a STAGES-deep ring;
+// the only waits on them are explicit vmcnt counts, and all operand reads from
+// LDS are issued by hand (inline asm) a few MFMAs ahead of their use.
+//
 // The operation itself is the absorbed-form attention of the paper (Sections
 // 2.1, 3.3.1, 3.3.2): score = scale * (q_nope . state[:DN] + q_rope . rope_key),
 // softmax over the visible keys, output = weights . state[:DV].
 #pragma once
 
 #include "../../include/gla_decode.h"
+
+#include <cstdio>
+#include <cstdlib>
 #include <type_traits>
 
 #include "common.hpp"
@@ -33,16 +40,24 @@
 namespace gla {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_cvoid_t;
 
-constexpr int kTok = 64;  // tokens per key tile == page size of the tuned path
+constexpr int kPage = 64;  // page size of the tuned path
 
 // ---- small device helpers -------------------------------------------------
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -58,6 +73,75 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Hand-issued LDS reads.  The result registers are valid only after a matching
+// lds_wait on them; LDS returns data in issue order, so "at most N reads still
+// outstanding" identifies which reads have completed.
+template <int OFF>
+__device__ __forceinline__ void lds_read_b128(u32x4_t& dst, unsigned addr) {
+  static_assert(OFF >= 0 && OFF < 65536, "ds offset field");
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+// Transposing read: within each block of 16 lanes, lanes 4r..4r+3 address row r
+// (4 x b16 each) of a 4 x 16 matrix; lane i receives column i (4 x b16).
+template <int OFF>
+__device__ __forceinline__ void lds_read_tr16_b64(u32x2_t& dst, unsigned addr) {
+  static_assert(OFF >= 0 && OFF < 65536, "ds offset field");
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x4_t& x) {
+  static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void lds_wait2(u32x2_t& x, u32x2_t& y) {
+  static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x), "+v"(y) : "n"(N));
+}
+
+// A 32-bit global load that is complete when the statement ends.  Used for the
+// rare bookkeeping reads inside the tile loop (page ids, next sequence length):
+// being opaque to the compiler's memory-counter tracking, it cannot make the
+// compiler place a "wait for every outstanding load" in the steady-state path,
+// which would drain the tile prefetch ring on every iteration.
+__device__ __forceinline__ int load_i32_sync(const int32_t* ptr) {
+  int v;
+  asm volatile("global_load_dword %0, %1, off\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(ptr) : "memory");
+  return v;
+}
+
+// Register-class pins (no instruction is emitted).  MFMA accumulators and the
+// query fragments, which are only ever MFMA operands inside the tile loop, are
+// kept in the accumulation half of the unified register file; everything the
+// vector ALU touches stays in the architectural half.  Without the pins the
+// allocator shuttles the output accumulators between the halves every tile.
+template <class V>
+__device__ __forceinline__ void pin_acc(V& x) { asm volatile("" : "+a"(x)); }
+template <class V>
+__device__ __forceinline__ void pin_arch(V& x) { asm volatile("" : "+v"(x)); }
+
+// max / sum over the two half-waves (lane and lane ^ 32).  v_permlane32_swap
+// exchanges the upper half of its first register with the lower half of its
+// second, so afterwards the pair holds (lower, lower) and (upper, upper).
+// Issued as inline asm: the compiler's builtin folds the two results of a swap
+// of a value with itself into one.  The s_nop covers the wait states this
+// instruction needs after a vector-ALU write of its operands.
+__device__ __forceinline__ void half_swap(float x, float& a, float& b) {
+  a = x;
+  b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float half_swap_max(float x) {
+  float a, b;
+  half_swap(x, a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float half_swap_sum(float x) {
+  float a, b;
+  half_swap(x, a, b);
+  return a + b;
+}
+
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -67,9 +151,12 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
   return v;
 }
 
-__device__ __forceinline__ int tiles_of(int L) { return L > 0 ? (L + kTok - 1) / kTok : 0; }
+template <int TOK>
+__device__ __forceinline__ int tiles_of(int L) {
+  return L > 0 ? (L + TOK - 1) / TOK : 0;
+}
 
-// Position of a chunk's first tile in the flat tile list.
+// Position in the flat tile list.
 struct TileCursor {
   int b;        // sequence
   int ub;       // unit within the sequence: g * MB + mb
@@ -79,11 +166,12 @@ struct TileCursor {
 };
 
 // Total number of tiles of the batch (every wave computes the same value).
+template <int TOK>
 __device__ __forceinline__ int total_tiles(const DevParams& p, int UPB, int lane) {
   int acc = 0;
   for (int base = 0; base < p.B; base += 64) {
     const int idx = base + lane;
-    acc += idx < p.B ? tiles_of(p.seq_lens[idx]) * UPB : 0;
+    acc += idx < p.B ? tiles_of<TOK>(p.seq_lens[idx]) * UPB : 0;
   }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
@@ -91,13 +179,14 @@ __device__ __forceinline__ int total_tiles(const DevParams& p, int UPB, int lane
 }
 
 // Locate flat tile index `pos` (< total): which sequence / unit / tile.
+template <int TOK>
 __device__ __forceinline__ TileCursor locate_tile(const DevParams& p, int UPB, int pos, int lane) {
   TileCursor c = {0, 0, 0, 0, 0};
   int before = 0;
   for (int base = 0; base < p.B; base += 64) {
     const int idx = base + lane;
     const int L = idx < p.B ? p.seq_lens[idx] : 0;
-    const int tl = tiles_of(L);
+    const int tl = tiles_of<TOK>(L);
     const int w = tl * UPB;
     const int incl = wave_incl_scan(w, lane) + before;
     const int excl = incl - w;
@@ -119,17 +208,19 @@ __device__ __forceinline__ TileCursor locate_tile(const DevParams& p, int UPB, i
 }
 
 // Flat index of the first tile of sequence b (sum over earlier sequences).
+template <int TOK>
 __device__ __forceinline__ int tiles_before(const DevParams& p, int UPB, int b, int lane) {
   int acc = 0;
   for (int base = 0; base < b; base += 64) {
     const int idx = base + lane;
-    acc += idx < b ? tiles_of(p.seq_lens[idx]) * UPB : 0;
+    acc += idx < b ? tiles_of<TOK>(p.seq_lens[idx]) * UPB : 0;
   }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
   return uniform(acc);
 }
 
+template <int TOK>
 __device__ __forceinline__ void advance(const DevParams& p, int UPB, TileCursor& c) {
   if (++c.j < c.tiles_b) return;
   c.j = 0;
@@ -137,8 +228,8 @@ __device__ __forceinline__ void advance(const DevParams& p, int UPB, TileCursor&
   c.ub = 0;
   do {
     ++c.b;
-    c.L = c.b < p.B ? p.seq_lens[c.b] : 0;
-    c.tiles_b = tiles_of(c.L);
+    c.L = c.b < p.B ? uniform(load_i32_sync(p.seq_lens + c.b)) : 0;
+    c.tiles_b = tiles_of<TOK>(c.L);
   } while (c.b < p.B && c.tiles_b == 0);
 }
 
@@ -146,45 +237,46 @@ __device__ __forceinline__ void advance(const DevParams& p, int UPB, TileCursor&
 // every aligned run of 16 chunks the chunk index is XORed with a 4-bit key of
 // the token so that (a) 16 consecutive tokens reading the same logical chunk
 // (score MFMA operand reads) and (b) 4 consecutive tokens reading the same 64
-// bytes (transposing value reads) both spread over all LDS banks.
-__device__ __forceinline__ int swz16(int t) { return ((t & 3) << 2) | ((t >> 2) & 3); }
+// bytes (transposing value reads) both spread over all LDS banks.  The key is
+// a bit permutation, hence XOR-linear in the token index.
+__host__ __device__ constexpr int swz16(int t) { return ((t & 3) << 2) | ((t >> 2) & 3); }
 // RoPE rows are 128 bytes (8 chunks): two tokens share a 256-byte bank row.
-__device__ __forceinline__ int swz8(int t) { return (t >> 1) & 7; }
+__host__ __device__ constexpr int swz8(int t) { return (t >> 1) & 7; }
 
-template <int DV, int DN, int DR, int NWAVES, int STAGES>
+template <int DV, int DN, int DR, int NWAVES, int TOK, int STAGES>
 struct TunedTraits {
   static constexpr int kRows = 32 * NWAVES;
-  static constexpr int kStateBytes = kTok * DV * 2;
-  static constexpr int kRopeBytes = kTok * DR * 2;
+  static constexpr int kRowBytes = DV * 2;
+  static constexpr int kStateBytes = TOK * kRowBytes;
+  static constexpr int kRopeBytes = TOK * DR * 2;
   static constexpr int kStageBytes = kStateBytes + kRopeBytes;
   static constexpr int kSmemBytes = STAGES * kStageBytes;
   static constexpr int kStateLoads = kStateBytes / 1024;  // wave-wide 16 B/lane loads
   static constexpr int kRopeLoads = kRopeBytes / 1024;
   static constexpr int kLoadsPerWave = (kStateLoads + kRopeLoads) / NWAVES;
+  static constexpr int kAhead = STAGES >= 2 ? STAGES - 2 : 0;  // tiles in flight past the awaited one
   static constexpr int kThreads = 64 * NWAVES;
+  static constexpr int kTilesPerPage = kPage / TOK;
   static constexpr size_t kSlotFloats = (size_t)kRows * DV + kRows;  // partial out + lse
+  static_assert(TOK == 32 || TOK == 64, "a tile is a page or half a page");
+  static_assert(STAGES >= 2, "need one stage loading while one computes");
   static_assert(kStateLoads % NWAVES == 0 && kRopeLoads % NWAVES == 0, "tile loads must split evenly over waves");
-  static_assert(kLoadsPerWave * (STAGES - 2 > 0 ? STAGES - 2 : 0) <= 63, "vmcnt range");
+  static_assert(kLoadsPerWave * kAhead <= 63, "vmcnt range");
   static_assert(DR == 64, "RoPE key tile layout assumes 64 dims");
+  static_assert(kRowBytes >= 256 && (kRowBytes & (kRowBytes - 1)) == 0 && kRowBytes <= 1024, "state row bytes");
+  static_assert(kSmemBytes <= 160 * 1024, "LDS capacity");
 };
 
-template <int DV, int DN, int DR, int NWAVES, int STAGES>
+template <int DV, int DN, int DR, int NWAVES, int TOK, int STAGES>
 __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
-  using TT = TunedTraits<DV, DN, DR, NWAVES, STAGES>;
-  // One LDS array per pipeline stage, always addressed with a compile-time
-  // stage index: the compiler can then tell that a tile load into one stage
-  // does not alias operand reads from another and keeps the loads in flight.
-  __shared__ __attribute__((aligned(1024))) unsigned char smem0[TT::kStageBytes];
-  __shared__ __attribute__((aligned(1024))) unsigned char smem1[STAGES > 1 ? TT::kStageBytes : 16];
-  __shared__ __attribute__((aligned(1024))) unsigned char smem2[STAGES > 2 ? TT::kStageBytes : 16];
-  __shared__ __attribute__((aligned(1024))) unsigned char smem3[STAGES > 3 ? TT::kStageBytes : 16];
-  auto stage_ptr = [&](auto sc) -> unsigned char* {
-    constexpr int S = decltype(sc)::value;
-    if constexpr (S == 0) return smem0;
-    else if constexpr (S == 1) return smem1;
-    else if constexpr (S == 2) return smem2;
-    else return smem3;
-  };
+  using TT = TunedTraits<DV, DN, DR, NWAVES, TOK, STAGES>;
+  constexpr int ROWB = TT::kRowBytes;
+  constexpr int NTB = TOK / 32;        // 32-token blocks per tile
+  constexpr int NKN = DN / 16;         // contraction steps over the state dims
+  constexpr int NKR = DR / 16;         // ... over the RoPE dims
+  constexpr int NDB = DV / 32;         // 32-dim output blocks
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[TT::kSmemBytes];
+  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -197,7 +289,7 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   const int UPB = p.h_c * MB;
 
   // ---- plan: this workgroup's chunk [c0, c1) of the flat tile list
-  const int n_total = total_tiles(p, UPB, lane);
+  const int n_total = total_tiles<TOK>(p, UPB, lane);
   const int chunk = p.chunk_tiles > 0 ? p.chunk_tiles
                                       : (n_total + (int)gridDim.x - 1) / (int)gridDim.x;
   if (chunk <= 0) return;
@@ -206,95 +298,110 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   const int c1 = min(n_total, c0 + chunk);
   const int n_tiles = c1 - c0;
 
-  TileCursor cur = locate_tile(p, UPB, c0, lane);  // compute position
-  TileCursor pre = cur;                             // prefetch position
+  TileCursor cur = locate_tile<TOK>(p, UPB, c0, lane);  // compute position
+  TileCursor pre = cur;                                  // prefetch position
 
-  // ---- lane-constant pieces of the tile-load addressing (global -> LDS, 16 B per lane)
-  // A wave-wide load fills 1 KiB of LDS linearly; the lane picks the global
-  // chunk whose swizzled home is its LDS slot.
-  auto issue_tile_loads = [&](const TileCursor& c, auto sc) {
+  // ---- tile loads, global -> LDS, 16 B per lane, 1 KiB per wave instruction.
+  // The LDS side is linear in the lane index, so each lane fetches the global
+  // chunk whose swizzled home is its LDS slot.  With inst = ii * NWAVES + wave
+  // the global byte offset of lane's chunk is  inst * 1024 + (lane_part ^ key(inst) << 4):
+  // one XOR per load.  Page ids are fetched 64 at a time, one per lane, and
+  // broadcast from the owning lane when a tile is issued.
+  constexpr int RPL = 1024 / ROWB;  // state rows per wave load
+  constexpr int CPR = ROWB / 16;    // 16 B chunks per state row
+  const int s_rl = lane / CPR, s_pc = lane % CPR;
+  const unsigned s_lane_part =
+      (unsigned)(s_rl * ROWB + ((s_pc & ~15) << 4) + (((s_pc & 15) ^ swz16(s_rl)) << 4));
+  const int r_rl = lane >> 3, r_pc = lane & 7;
+  const unsigned r_lane_part = (unsigned)(r_rl * 128 + ((r_pc ^ (r_rl >> 1)) << 4));
+
+  int pt_b = -1, pt_base = 0;
+  int pt_vec = 0;
+  auto issue_tile_loads = [&](const TileCursor& c, int stage) {
+    const int page_idx = c.j / TT::kTilesPerPage;
+    const int tip = c.j - page_idx * TT::kTilesPerPage;  // tile within the page
+    if (c.b != pt_b || page_idx < pt_base || page_idx >= pt_base + 64) {
+      pt_b = c.b;
+      pt_base = page_idx;
+      const int idx = min(page_idx + lane, p.max_pages - 1);
+      pt_vec = load_i32_sync(p.page_table + (int64_t)c.b * p.max_pages + idx);
+    }
     const int g = c.ub / MB;
-    const int64_t page = p.page_table[(int64_t)c.b * p.max_pages + c.j];
-    const unsigned char* sbase =
-        (const unsigned char*)(p.state + page * p.st_s[0] + (int64_t)g * p.st_s[1]);
-    const unsigned char* rbase = (const unsigned char*)(p.rope + page * p.rp_s[0]);
-    unsigned char* stage_base = stage_ptr(sc);
+    const int64_t page = __builtin_amdgcn_readlane(pt_vec, page_idx - pt_base);
+    const unsigned char* sbase = (const unsigned char*)(p.state + page * p.st_s[0] + (int64_t)g * p.st_s[1]) +
+                                 tip * TT::kStateBytes;
+    const unsigned char* rbase = (const unsigned char*)(p.rope + page * p.rp_s[0]) + tip * TT::kRopeBytes;
+    unsigned char* stage_base = smem + stage * TT::kStageBytes;
 #pragma unroll
     for (int ii = 0; ii < TT::kStateLoads / NWAVES; ++ii) {
       const int inst = ii * NWAVES + wave;  // 1 KiB slice index within the state tile
-      const int off = inst * 1024 + lane * 16;
-      const int t = off / (DV * 2);
-      const int pc = (off % (DV * 2)) >> 4;
-      const int lc = (pc & ~15) | ((pc & 15) ^ swz16(t));
-      const unsigned goff = (unsigned)(t * (DV * 2) + (lc << 4));
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(sbase + goff),
+      const unsigned voff = s_lane_part ^ ((unsigned)swz16(inst * RPL) << 4);
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(sbase + inst * 1024 + voff),
                                        (lds_void_t*)(stage_base + inst * 1024), 16, 0, 0);
     }
 #pragma unroll
     for (int ii = 0; ii < TT::kRopeLoads / NWAVES; ++ii) {
       const int rinst = ii * NWAVES + wave;
-      const int off = rinst * 1024 + lane * 16;
-      const int t = off >> 7;
-      const int pc = (off >> 4) & 7;
-      const int lc = pc ^ swz8(t);
-      const unsigned goff = (unsigned)(t * 128 + (lc << 4));
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(rbase + goff),
+      const unsigned voff = r_lane_part ^ ((unsigned)(rinst & 1) << 6);
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(rbase + rinst * 1024 + voff),
                                        (lds_void_t*)(stage_base + TT::kStateBytes + rinst * 1024), 16, 0, 0);
     }
   };
 
   // ---- prologue: fill STAGES-1 stages
   int issued = 0;
-  auto prologue_stage = [&](auto sc) {
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s) {
     if (issued < n_tiles) {
-      issue_tile_loads(pre, sc);
-      advance(p, UPB, pre);
+      issue_tile_loads(pre, s);
+      advance<TOK>(p, UPB, pre);
       ++issued;
     }
-  };
-  if constexpr (STAGES > 1) prologue_stage(std::integral_constant<int, 0>{});
-  if constexpr (STAGES > 2) prologue_stage(std::integral_constant<int, 1>{});
-  if constexpr (STAGES > 3) prologue_stage(std::integral_constant<int, 2>{});
+  }
 
-  // ---- lane-constant LDS read addresses
+  // ---- lane-constant LDS read offsets (relative to the stage base)
   // score operand (K rows, 16 B): token = 32*tb + col, logical chunk = 2*ks + hi
   const int sw_col = swz16(col);
-  int k_addr[8];  // index: (2*ks) & 15 >> 1
+  unsigned k_off[8];  // index: ks & 7
 #pragma unroll
-  for (int e = 0; e < 8; ++e) k_addr[e] = col * (DV * 2) + ((((2 * e) | hi) ^ sw_col) << 4);
-  int r_addr[4];
+  for (int e = 0; e < 8; ++e) k_off[e] = (unsigned)(col * ROWB + ((((2 * e) | hi) ^ sw_col) << 4));
+  unsigned r_off[NKR];
 #pragma unroll
-  for (int e = 0; e < 4; ++e) r_addr[e] = TT::kStateBytes + col * 128 + ((((2 * e) | hi) ^ swz8(col)) << 4);
+  for (int e = 0; e < NKR; ++e)
+    r_off[e] = (unsigned)(TT::kStateBytes + col * 128 + ((((2 * e) | hi) ^ swz8(col)) << 4));
   // value operand (transposing 8 B reads): 16-lane block bk = lane / 16 covers
   // 4 tokens x 16 dims; lane 4r+q of the block addresses token r, dims 4q..4q+3.
   const int i16 = lane & 15;
   const int tr_r = i16 >> 2, tr_q = i16 & 3;
   const int dh = (lane >> 4) & 1;
-  int v_addr[4][2];  // [db & 3][a]
+  unsigned v_off[4][2];  // [db & 3][a]
 #pragma unroll
   for (int d4 = 0; d4 < 4; ++d4)
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
       const int key = (tr_r << 2) | (2 * a + hi);           // swz16 of token 8a + 4hi + r
       const int lc = (4 * d4 + 2 * dh + (tr_q >> 1)) ^ key;  // chunk within the 16-chunk run
-      v_addr[d4][a] = (4 * hi + tr_r) * (DV * 2) + (lc << 4) + (tr_q & 1) * 8;
+      v_off[d4][a] = (unsigned)((4 * hi + tr_r) * ROWB + (lc << 4) + (tr_q & 1) * 8);
     }
 
   const float sc2 = p.scale * 1.4426950408889634f;  // scores in base-2 units
 
   // ---- per-unit state
-  bf16x8_t qn[DN / 16];
-  bf16x8_t qr[DR / 16];
-  f32x16_t o[DV / 32];
-  float m_ref = -INFINITY, l_run = 0.f;
+  u32x4_t qn[NKN];  // raw bf16 bits: kept as integer vectors so the register pins see plain 128-bit tuples
+  u32x4_t qr[NKR];
+  f32x16_t o[NDB];
+  // l_run: exact fp32 row sum (for the log-sum-exp); l_rnd: sum of the weights
+  // as rounded to bf16 for the PV product, which is what the output must be
+  // divided by for the rounded weights to still sum to one.
+  float m_ref = -INFINITY, l_run = 0.f, l_rnd = 0.f;
   int n_vis = 0, n_vis_min = 0;
   bool row_valid = false;
   int row_b = 0, row_t = 0, row_h = 0;
   bool unit_start = true;
 
-  auto tile_step = [&](auto sc, int k) {
-    constexpr int S = decltype(sc)::value;
-    unsigned char* sb = stage_ptr(sc);
+  for (int k = 0; k < n_tiles; ++k) {
+    const int stage = k % STAGES;
+    const unsigned sa = lds_base + (unsigned)(stage * TT::kStageBytes);
 
     if (unit_start) {
       // query fragments of this wave's 32 rows: B operand, lane holds 8 dims of row `col`
@@ -302,28 +409,38 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       const int mb = cur.ub - g * MB;
       const int R = mb * TT::kRows + wave * 32 + col;
       row_valid = R < rows_group;
-      row_t = row_valid ? R / p.g_q : 0;
-      row_h = g * p.g_q + (row_valid ? R - row_t * p.g_q : 0);
+      const int Rc = row_valid ? R : rows_group - 1;
+      row_t = Rc / p.g_q;
+      row_h = g * p.g_q + (Rc - row_t * p.g_q);
       row_b = cur.b;
       const uint16_t* qn_ptr = p.q_nope + row_b * p.qn_s[0] + row_t * p.qn_s[1] + row_h * p.qn_s[2] + 8 * hi;
       const uint16_t* qr_ptr = p.q_rope + row_b * p.qr_s[0] + row_t * p.qr_s[1] + row_h * p.qr_s[2] + 8 * hi;
-      const u32x4_t zero4 = {0, 0, 0, 0};
+      const uint32_t keep = row_valid ? 0xffffffffu : 0u;  // padding rows get a zero query
 #pragma unroll
-      for (int ks = 0; ks < DN / 16; ++ks) {
-        u32x4_t v = row_valid ? *(const u32x4_t*)(qn_ptr + 16 * ks) : zero4;
-        qn[ks] = __builtin_bit_cast(bf16x8_t, v);
+      for (int ks = 0; ks < NKN; ++ks) {
+        u32x4_t v = *(const u32x4_t*)(qn_ptr + 16 * ks);
+        v &= keep;
+        qn[ks] = v;
       }
 #pragma unroll
-      for (int ks = 0; ks < DR / 16; ++ks) {
-        u32x4_t v = row_valid ? *(const u32x4_t*)(qr_ptr + 16 * ks) : zero4;
-        qr[ks] = __builtin_bit_cast(bf16x8_t, v);
+      for (int ks = 0; ks < NKR; ++ks) {
+        u32x4_t v = *(const u32x4_t*)(qr_ptr + 16 * ks);
+        v &= keep;
+        qr[ks] = v;
       }
 #pragma unroll
-      for (int db = 0; db < DV / 32; ++db)
+      for (int ks = 0; ks < NKN; ++ks) pin_acc(qn[ks]);
+#pragma unroll
+      for (int ks = 0; ks < NKR; ++ks) pin_acc(qr[ks]);
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+        pin_acc(o[db]);
+      }
       m_ref = -INFINITY;
       l_run = 0.f;
+      l_rnd = 0.f;
       // visible keys of this lane's row; padding rows are left unmasked (never stored)
       n_vis = row_valid ? (p.causal ? cur.L - p.T + 1 + row_t : cur.L) : 0x7fffffff;
       int mn = n_vis;
@@ -334,69 +451,114 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     }
 
     // ---- wait for tile k, make it visible to all waves, free stage (k-1) % STAGES
-    if (k + (STAGES - 2) < n_tiles) wait_vmcnt<TT::kLoadsPerWave*(STAGES - 2 > 0 ? STAGES - 2 : 0)>();
+    if (k + TT::kAhead < n_tiles) wait_vmcnt<TT::kLoadsPerWave * TT::kAhead>();
     else wait_vmcnt<0>();
     lds_barrier();
 
-    const int tile_tok0 = cur.j * kTok;
-    if (tile_tok0 + kTok > cur.L) {
+    const int tile_tok0 = cur.j * TOK;
+    if (tile_tok0 + TOK > cur.L) {
       // last tile of the sequence: slots at or beyond L may hold anything (NaN
       // included); zero those value rows so that 0-weight x garbage cannot leak.
       const int valid = cur.L - tile_tok0;
-      for (int off = valid * (DV * 2) + tid * 16; off < TT::kStateBytes; off += TT::kThreads * 16)
+      unsigned char* sb = smem + stage * TT::kStageBytes;
+      for (int off = valid * ROWB + tid * 16; off < TT::kStateBytes; off += TT::kThreads * 16)
         *(u32x4_t*)(sb + off) = u32x4_t{0, 0, 0, 0};
       lds_barrier();
     }
 
     // ---- prefetch tile k + STAGES - 1 into the stage just released
     if (issued < n_tiles) {
-      issue_tile_loads(pre, std::integral_constant<int, (S + STAGES - 1) % STAGES>{});
-      advance(p, UPB, pre);
+      issue_tile_loads(pre, (k + STAGES - 1) % STAGES);
+      advance<TOK>(p, UPB, pre);
       ++issued;
     }
 
-    // ---- S^T = K . Q^T  (two 32-token blocks)
-    f32x16_t s[2];
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
+    for (int db = 0; db < NDB; ++db) pin_acc(o[db]);
+#pragma unroll
+    for (int ks = 0; ks < NKN; ++ks) pin_acc(qn[ks]);
+#pragma unroll
+    for (int ks = 0; ks < NKR; ++ks) pin_acc(qr[ks]);
+
+    // ---- S^T = K . Q^T, NTB blocks of 32 tokens; operand reads run PD ahead
+    f32x16_t s[NTB];
+#pragma unroll
+    for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[tb][i] = 0.f;
+    {
+      constexpr int NS = (NKN + NKR) * NTB, RS = 6, PD = 5;
+      unsigned ka[8], ra[NKR];
 #pragma unroll
-    for (int ks = 0; ks < DN / 16; ++ks) {
+      for (int e = 0; e < 8; ++e) ka[e] = k_off[e] + sa;
 #pragma unroll
-      for (int tb = 0; tb < 2; ++tb) {
-        const int addr = k_addr[ks & 7] + tb * 32 * (DV * 2) + ((2 * ks) & ~15) * 16;
-        const bf16x8_t a = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(sb + addr));
-        s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qn[ks], s[tb], 0, 0, 0);
-      }
-    }
-#pragma unroll
-    for (int ks = 0; ks < DR / 16; ++ks) {
-#pragma unroll
-      for (int tb = 0; tb < 2; ++tb) {
-        const int addr = r_addr[ks] + tb * 32 * 128;
-        const bf16x8_t a = __builtin_bit_cast(bf16x8_t, *(const u32x4_t*)(sb + addr));
-        s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qr[ks], s[tb], 0, 0, 0);
-      }
+      for (int e = 0; e < NKR; ++e) ra[e] = r_off[e] + sa;
+      u32x4_t frag[RS];
+      auto issue = [&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        constexpr int ks = i / NTB, tb = i % NTB;
+        if constexpr (ks < NKN) lds_read_b128<tb * 32 * ROWB + ((2 * ks) & ~15) * 16>(frag[i % RS], ka[ks & 7]);
+        else lds_read_b128<tb * 32 * 128>(frag[i % RS], ra[ks - NKN]);
+      };
+      static_for<0, (PD < NS ? PD : NS)>(issue);
+      static_for<0, NS>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        constexpr int ks = i / NTB, tb = i % NTB;
+        constexpr int left = NS - 1 - i;
+        lds_wait<(left < PD - 1 ? left : PD - 1)>(frag[i % RS]);
+        const bf16x8_t a = __builtin_bit_cast(bf16x8_t, frag[i % RS]);
+        if constexpr (ks < NKN) s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8_t, qn[ks]), s[tb], 0, 0, 0);
+        else s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8_t, qr[ks - NKN]), s[tb], 0, 0, 0);
+        if constexpr (i < NTB) pin_arch(s[tb]);  // scores are consumed by the vector ALU
+        if constexpr (i + PD < NS) issue(std::integral_constant<int, i + PD>{});
+      });
     }
 
-    // ---- online softmax in base 2; lane holds 32 scores of row `col`:
+#pragma unroll
+    for (int tb = 0; tb < NTB; ++tb) pin_arch(s[tb]);
+
+    // ---- value operand reads for the first PV steps go out before the softmax
+    constexpr int NP = (TOK / 16) * NDB, VRS = 6, VPD = 5;
+    unsigned va[4][2];
+#pragma unroll
+    for (int d4 = 0; d4 < 4; ++d4)
+#pragma unroll
+      for (int a = 0; a < 2; ++a) va[d4][a] = v_off[d4][a] + sa;
+    u32x2_t vlo[VRS], vhi[VRS];
+    auto v_issue = [&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      constexpr int st = i / NDB, db = i % NDB;
+      constexpr int base = st * 16 * ROWB + (db >> 2) * 256;
+      lds_read_tr16_b64<base>(vlo[i % VRS], va[db & 3][0]);
+      lds_read_tr16_b64<base + 8 * ROWB>(vhi[i % VRS], va[db & 3][1]);
+    };
+    static_for<0, (VPD < NP ? VPD : NP)>(v_issue);
+
+    // ---- online softmax in base 2; lane holds TOK/2 scores of row `col`:
     // token(tb, i) = 32*tb + 8*(i/4) + 4*hi + i%4
-    const bool need_mask = tile_tok0 + kTok > n_vis_min;
+    const bool need_mask = tile_tok0 + TOK > n_vis_min;
     float mx = -INFINITY;
+    if (need_mask) {
+      const int lim = n_vis - tile_tok0 - 4 * hi;  // element (tb, i) is visible iff its constant < lim
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
+      for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float x = s[tb][i] * sc2;
-        if (need_mask) {
-          const int tok = tile_tok0 + 32 * tb + 8 * (i >> 2) + 4 * hi + (i & 3);
-          x = tok < n_vis ? x : -INFINITY;
+        for (int i = 0; i < 16; ++i) {
+          const float x = (32 * tb + 8 * (i >> 2) + (i & 3)) < lim ? s[tb][i] * sc2 : -INFINITY;
+          s[tb][i] = x;
+          mx = fmaxf(mx, x);
         }
-        s[tb][i] = x;
-        mx = fmaxf(mx, x);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    } else {
+#pragma unroll
+      for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float x = s[tb][i] * sc2;
+          s[tb][i] = x;
+          mx = fmaxf(mx, x);
+        }
+    }
+    mx = half_swap_max(mx);
     // lazy reference update: keep the old reference while the row max stays
     // within 2^8 of it (probabilities then stay <= 256, exact enough in fp32/bf16)
     const bool bump = mx > m_ref + 8.0f;
@@ -404,17 +566,20 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       const float m_new = bump ? mx : m_ref;
       const float alpha = bump ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.0f;  // m_ref = -inf -> 0
       l_run *= alpha;
+      l_rnd *= alpha;
 #pragma unroll
-      for (int db = 0; db < DV / 32; ++db)
+      for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) pin_acc(o[db]);
       m_ref = m_new;
     }
     const float m_use = m_ref == -INFINITY ? 0.f : m_ref;
     float lsum = 0.f;
-    bf16x8_t pf[4];  // B operands of the four 16-token contraction steps
+    bf16x8_t pf[TOK / 16];  // B operands of the 16-token contraction steps
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
+    for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const float pv = __builtin_amdgcn_exp2f(s[tb][i] - m_use);
@@ -422,37 +587,46 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
         pf[tb * 2 + (i >> 3)][i & 7] = (__bf16)pv;
       }
     l_run += lsum;
-
-    // ---- O^T += V^T . P^T ; contraction slot (hi, j) of step (tb, s2) is token
-    // 32*tb + 16*s2 + 8*(j/4) + 4*hi + j%4, matching the accumulator layout above
+    float rsum = 0.f;
 #pragma unroll
-    for (int st = 0; st < 4; ++st) {
+    for (int st = 0; st < TOK / 16; ++st) {
+      const u32x4_t w = __builtin_bit_cast(u32x4_t, pf[st]);
 #pragma unroll
-      for (int db = 0; db < DV / 32; ++db) {
-        const int base = st * 16 * (DV * 2) + (db >> 2) * 256;
-        const bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-            (__attribute__((address_space(3))) bf16x4_t*)(sb + v_addr[db & 3][0] + base));
-        const bf16x4_t hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-            (__attribute__((address_space(3))) bf16x4_t*)(sb + v_addr[db & 3][1] + base + 8 * (DV * 2)));
-        const bf16x8_t a = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[st], o[db], 0, 0, 0);
-      }
+      for (int e = 0; e < 4; ++e)
+        rsum += __builtin_bit_cast(float, w[e] << 16) + __builtin_bit_cast(float, w[e] & 0xffff0000u);
     }
+    l_rnd += rsum;
+
+    // ---- O^T += V^T . P^T ; contraction slot (hi, j) of step st is token
+    // 16*st + 8*(j/4) + 4*hi + j%4, matching the accumulator layout above
+    static_for<0, NP>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      constexpr int st = i / NDB, db = i % NDB;
+      constexpr int left = NP - 1 - i;
+      lds_wait2<2 * (left < VPD - 1 ? left : VPD - 1)>(vlo[i % VRS], vhi[i % VRS]);
+      const u32x4_t a4 = {vlo[i % VRS][0], vlo[i % VRS][1], vhi[i % VRS][0], vhi[i % VRS][1]};
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a4), pf[st], o[db], 0, 0, 0);
+      if constexpr (i + VPD < NP) v_issue(std::integral_constant<int, i + VPD>{});
+    });
+
+#pragma unroll
+    for (int db = 0; db < NDB; ++db) pin_acc(o[db]);
 
     // ---- end of unit (or of chunk): write the result
     const bool unit_done = cur.j + 1 == cur.tiles_b;
     if (unit_done || k + 1 == n_tiles) {
       // the unit is complete here iff this chunk also held its first tile
       const bool complete = unit_done && (k >= cur.j);
-      const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-      const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+      const float l_tot = half_swap_sum(l_run);
+      const float r_tot = half_swap_sum(l_rnd);
+      const float inv = r_tot > 0.f ? 1.0f / r_tot : 0.f;
       const float lse = l_tot > 0.f ? (m_ref + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
       if (complete) {
         if (row_valid) {
           const int64_t ob = row_b * p.out_s[0] + row_t * p.out_s[1] + row_h * p.out_s[2];
           if (hi == 0) p.lse[((int64_t)row_b * p.T + row_t) * p.h_q + row_h] = lse;
 #pragma unroll
-          for (int db = 0; db < DV / 32; ++db)
+          for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
               const int dim = 32 * db + 8 * q4 + 4 * hi;
@@ -470,12 +644,12 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
         }
       } else {
         // partial: slot 0 if the unit began before this chunk, slot 1 otherwise
-        const int which = (k < cur.j) ? 0 : 1;  // k < j: first tile of the unit is in an earlier chunk
+        const int which = (k < cur.j) ? 0 : 1;
         float* slot = p.ws_out + ((size_t)blockIdx.x * 2 + which) * TT::kSlotFloats;
         const int lr = wave * 32 + col;
         if (hi == 0) slot[(size_t)TT::kRows * DV + lr] = lse;
 #pragma unroll
-        for (int db = 0; db < DV / 32; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
           for (int q4 = 0; q4 < 4; ++q4) {
             const int dim = 32 * db + 8 * q4 + 4 * hi;
@@ -486,21 +660,14 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       }
       unit_start = true;
     }
-    advance(p, UPB, cur);
-  };
-
-  for (int k = 0; k < n_tiles; k += STAGES) {
-    tile_step(std::integral_constant<int, 0>{}, k);
-    if constexpr (STAGES > 1) if (k + 1 < n_tiles) tile_step(std::integral_constant<int, 1>{}, k + 1);
-    if constexpr (STAGES > 2) if (k + 2 < n_tiles) tile_step(std::integral_constant<int, 2>{}, k + 2);
-    if constexpr (STAGES > 3) if (k + 3 < n_tiles) tile_step(std::integral_constant<int, 3>{}, k + 3);
+    advance<TOK>(p, UPB, cur);
   }
 }
 
 // Merge of the partial results of units that span several chunks, and zero fill
 // of units without any key:  lse = ln sum_s exp(lse_s),
-// out = sum_s exp(lse_s - lse) out_s.  One workgroup per unit.
-template <int DV, int NWAVES>
+// out = sum_s exp(lse_s - lse) out_s.  Grid (units, ROWS / 4): one wave per row.
+template <int DV, int NWAVES, int TOK>
 __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
   constexpr int kRows = 32 * NWAVES;
   constexpr size_t kSlotFloats = (size_t)kRows * DV + kRows;
@@ -512,70 +679,53 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
   const int b = unit / UPB;
   const int ub = unit - b * UPB;
   const int g = ub / MB, mb = ub - g * MB;
+  const int r = blockIdx.y * 4 + wave;  // row within the unit's block
+  const int R = mb * kRows + r;
   const int L = p.seq_lens[b];
-  const int tl = tiles_of(L);
+  const int tl = tiles_of<TOK>(L);
 
-  int k_first = 0, k_last = -1, s_u = 0;
+  int k_first = 0, k_last = -1;
   if (tl > 0) {
-    const int n_total = total_tiles(p, UPB, lane);
+    const int n_total = total_tiles<TOK>(p, UPB, lane);
     const int chunk = p.chunk_tiles > 0 ? p.chunk_tiles : (n_total + p.num_chunks - 1) / p.num_chunks;
-    s_u = tiles_before(p, UPB, b, lane) + ub * tl;
+    const int s_u = tiles_before<TOK>(p, UPB, b, lane) + ub * tl;
     k_first = s_u / chunk;
     k_last = (s_u + tl - 1) / chunk;
     if (k_first == k_last) return;  // written directly by the main kernel
-    // partial slot of chunk k: 0 if the unit began before the chunk, else 1
-    // (only chunk k_first can hold the unit's first tile)
-    for (int r = wave; r < kRows; r += 4) {
-      const int R = mb * kRows + r;
-      if (R >= rows_group) break;
-      const int t = R / p.g_q;
-      const int h = g * p.g_q + (R - t * p.g_q);
-      float m = -INFINITY;
+  }
+  if (R >= rows_group) return;
+  const int t = R / p.g_q;
+  const int h = g * p.g_q + (R - t * p.g_q);
+  // Chunk k_first holds the unit's first tile (partial slot 1); every later
+  // chunk sees a unit that began before it (slot 0).
+  float m = -INFINITY;
+  for (int k = k_first; k <= k_last; ++k)
+    m = fmaxf(m, p.ws_out[((size_t)k * 2 + (k == k_first)) * kSlotFloats + (size_t)kRows * DV + r]);
+  float z = 0.f;
+  if (m != -INFINITY)
+    for (int k = k_first; k <= k_last; ++k)
+      z += expf(p.ws_out[((size_t)k * 2 + (k == k_first)) * kSlotFloats + (size_t)kRows * DV + r] - m);
+  const float lse = m == -INFINITY ? -INFINITY : m + logf(z);
+  if (lane == 0) p.lse[((int64_t)b * p.T + t) * p.h_q + h] = lse;
+  const int64_t ob = b * p.out_s[0] + t * p.out_s[1] + h * p.out_s[2];
+  for (int d = lane * 4; d < DV; d += 256) {
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    if (m != -INFINITY)
       for (int k = k_first; k <= k_last; ++k) {
-        const int which = (k == k_first && s_u >= k * chunk) ? 1 : 0;
-        m = fmaxf(m, p.ws_out[((size_t)k * 2 + which) * kSlotFloats + (size_t)kRows * DV + r]);
+        const float* slot = p.ws_out + ((size_t)k * 2 + (k == k_first)) * kSlotFloats;
+        const float ls = slot[(size_t)kRows * DV + r];
+        if (ls == -INFINITY) continue;
+        const float w = expf(ls - lse);
+        const f32x4_t v = *(const f32x4_t*)(slot + (size_t)r * DV + d);
+        acc += w * v;
       }
-      float z = 0.f;
-      if (m != -INFINITY)
-        for (int k = k_first; k <= k_last; ++k) {
-          const int which = (k == k_first && s_u >= k * chunk) ? 1 : 0;
-          z += expf(p.ws_out[((size_t)k * 2 + which) * kSlotFloats + (size_t)kRows * DV + r] - m);
-        }
-      const float lse = m == -INFINITY ? -INFINITY : m + logf(z);
-      if (lane == 0) p.lse[((int64_t)b * p.T + t) * p.h_q + h] = lse;
-      float acc[DV / 64];
-#pragma unroll
-      for (int i = 0; i < DV / 64; ++i) acc[i] = 0.f;
-      if (m != -INFINITY)
-        for (int k = k_first; k <= k_last; ++k) {
-          const int which = (k == k_first && s_u >= k * chunk) ? 1 : 0;
-          const float* slot = p.ws_out + ((size_t)k * 2 + which) * kSlotFloats;
-          const float ls = slot[(size_t)kRows * DV + r];
-          if (ls == -INFINITY) continue;
-          const float w = expf(ls - lse);
-#pragma unroll
-          for (int i = 0; i < DV / 64; ++i) acc[i] += w * slot[(size_t)r * DV + lane + 64 * i];
-        }
-      const int64_t ob = b * p.out_s[0] + t * p.out_s[1] + h * p.out_s[2];
-#pragma unroll
-      for (int i = 0; i < DV / 64; ++i) {
-        if (p.out_fp32) ((float*)p.out)[ob + lane + 64 * i] = acc[i];
-        else ((uint16_t*)p.out)[ob + lane + 64 * i] = f32_to_bf16_bits(acc[i]);
-      }
-    }
-  } else {
-    // no cached token: zeros and -inf
-    for (int r = wave; r < kRows; r += 4) {
-      const int R = mb * kRows + r;
-      if (R >= rows_group) break;
-      const int t = R / p.g_q;
-      const int h = g * p.g_q + (R - t * p.g_q);
-      if (lane == 0) p.lse[((int64_t)b * p.T + t) * p.h_q + h] = -INFINITY;
-      const int64_t ob = b * p.out_s[0] + t * p.out_s[1] + h * p.out_s[2];
-      for (int d = lane; d < DV; d += 64) {
-        if (p.out_fp32) ((float*)p.out)[ob + d] = 0.f;
-        else ((uint16_t*)p.out)[ob + d] = 0;
-      }
+    if (p.out_fp32) {
+      *(f32x4_t*)((float*)p.out + ob + d) = acc;
+    } else {
+      u32x2_t pk;
+      pk[0] = (uint32_t)f32_to_bf16_bits(acc[0]) | ((uint32_t)f32_to_bf16_bits(acc[1]) << 16);
+      pk[1] = (uint32_t)f32_to_bf16_bits(acc[2]) | ((uint32_t)f32_to_bf16_bits(acc[3]) << 16);
+      *(u32x2_t*)((uint16_t*)p.out + ob + d) = pk;
     }
   }
 }
@@ -583,8 +733,9 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
 // ---- host side ---------------------------------------------------------------
 
 struct TunedPlan {
-  int variant;     // index into the instantiation table below, -1: none
+  int dv, dn;      // state dims (value / score)
   int nwaves;      // waves per workgroup
+  int tok, stages; // tile tokens and pipeline depth of the chosen instantiation
   int rows;        // 32 * nwaves
   int mb;          // row blocks per (sequence, group)
   int num_chunks;  // main-kernel grid
@@ -607,12 +758,23 @@ inline int device_cu_count() {
 
 inline bool aligned16(const void* ptr) { return ((uintptr_t)ptr & 15u) == 0; }
 
+// Tuning knob for experiments: GLA_TUNED_CONFIG="tok,stages,wgs_per_cu" overrides
+// the tile size, pipeline depth and grid density chosen below (only values with
+// a compiled instantiation are honoured).
+inline void tuning_override(int* tok, int* stages, int* per_cu) {
+  const char* e = std::getenv("GLA_TUNED_CONFIG");
+  if (!e) return;
+  int a = 0, b = 0, c = 0;
+  if (std::sscanf(e, "%d,%d,%d", &a, &b, &c) >= 2) {
+    if (a == 32 || a == 64) *tok = a;
+    if (b >= 2 && b <= 8) *stages = b;
+    if (c >= 1 && c <= 8) *per_cu = c;
+  }
+}
+
 inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) {
-  if (p->page_size != kTok || p->d_rope != 64) return false;
-  int variant = -1;
-  if (!is_gta && p->d_v == 256) variant = 0;
-  else if (is_gta && p->d_v == 128) variant = 2;
-  if (variant < 0) return false;
+  if (p->page_size != kPage || p->d_rope != 64) return false;
+  if (!((!is_gta && p->d_v == 256) || (is_gta && p->d_v == 128))) return false;
   // layout the kernels assume: token rows contiguous, everything 16-byte aligned
   if (p->state_stride[2] != p->d_v || p->rope_stride[1] != p->d_rope) return false;
   if (p->state_stride[0] % 8 || p->state_stride[1] % 8 || p->rope_stride[0] % 8) return false;
@@ -623,11 +785,17 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
     return false;
   const int rows_group = (p->num_q_heads / p->num_groups) * p->q_len;
   const int nwaves = rows_group <= 32 ? 1 : (rows_group <= 64 ? 2 : 4);
-  plan->variant = variant;
+  plan->dv = p->d_v;
+  plan->dn = p->d_nope;
   plan->nwaves = nwaves;
   plan->rows = 32 * nwaves;
   plan->mb = (rows_group + plan->rows - 1) / plan->rows;
-  const int64_t max_tiles = p->max_pages_per_seq;
+  int tok = 32, stages = 4, per_cu = nwaves == 4 ? 1 : (nwaves == 2 ? 2 : 4);
+  if (nwaves == 4) { tok = 64; stages = 3; }
+  tuning_override(&tok, &stages, &per_cu);
+  plan->tok = tok;
+  plan->stages = stages;
+  const int64_t max_tiles = (int64_t)p->max_pages_per_seq * (kPage / tok);
   const int64_t bound = (int64_t)p->batch * p->num_groups * plan->mb * max_tiles;
   if (bound > 0x3fffffff) return false;
   if (p->num_splits > 0) {
@@ -635,7 +803,6 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
     plan->num_chunks = (int)std::max<int64_t>(1, (bound + plan->chunk_tiles - 1) / plan->chunk_tiles);
   } else {
     plan->chunk_tiles = 0;
-    const int per_cu = nwaves == 4 ? 1 : (nwaves == 2 ? 2 : 3);
     plan->num_chunks = (int)std::max<int64_t>(1, std::min<int64_t>(bound, (int64_t)device_cu_count() * per_cu));
   }
   plan->slot_floats = (size_t)plan->rows * p->d_v + plan->rows;
@@ -653,18 +820,37 @@ inline size_t tuned_workspace(const gla_decode_params* p, int is_gta) {
   return (size_t)plan.num_chunks * 2 * plan.slot_floats * sizeof(float);
 }
 
-template <int DV, int DN, int NWAVES, int STAGES>
+template <int DV, int DN, int NWAVES, int TOK, int STAGES>
 inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, int units, hipStream_t st,
                                 hipEvent_t* ev) {
   if (ev) (void)hipEventRecord(ev[0], st);
-  hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NWAVES, STAGES>), dim3(plan.num_chunks),
+  hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NWAVES, TOK, STAGES>), dim3(plan.num_chunks),
                      dim3(64 * NWAVES), 0, st, d);
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[1], st);
-  hipLaunchKernelGGL((tuned_combine_kernel<DV, NWAVES>), dim3(units), dim3(256), 0, st, d);
+  hipLaunchKernelGGL((tuned_combine_kernel<DV, NWAVES, TOK>), dim3(units, (32 * NWAVES) / 4), dim3(256),
+                     0, st, d);
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[2], st);
   return GLA_OK;
+}
+
+template <int DV, int DN>
+inline int launch_tuned_shape(const TunedPlan& plan, DevParams& d, int units, hipStream_t st,
+                              hipEvent_t* ev) {
+  const int key = plan.nwaves * 10000 + plan.tok * 100 + plan.stages;
+  switch (key) {
+    case 1 * 10000 + 3200 + 2: return launch_tuned_variant<DV, DN, 1, 32, 2>(plan, d, units, st, ev);
+    case 1 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 1, 32, 4>(plan, d, units, st, ev);
+    case 2 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 2, 32, 4>(plan, d, units, st, ev);
+    case 2 * 10000 + 3200 + 2: return launch_tuned_variant<DV, DN, 2, 32, 2>(plan, d, units, st, ev);
+    case 2 * 10000 + 3200 + 3: return launch_tuned_variant<DV, DN, 2, 32, 3>(plan, d, units, st, ev);
+    case 2 * 10000 + 6400 + 2: return launch_tuned_variant<DV, DN, 2, 64, 2>(plan, d, units, st, ev);
+    case 4 * 10000 + 6400 + 3: return launch_tuned_variant<DV, DN, 4, 64, 3>(plan, d, units, st, ev);
+    case 4 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 4, 32, 4>(plan, d, units, st, ev);
+    case 4 * 10000 + 3200 + 6: return launch_tuned_variant<DV, DN, 4, 32, 6>(plan, d, units, st, ev);
+    default: return GLA_ERR_UNSUPPORTED_SHAPE;
+  }
 }
 
 inline int tuned_launch(const gla_decode_params* p, int is_gta, DevParams& d, hipStream_t st,
@@ -675,16 +861,8 @@ inline int tuned_launch(const gla_decode_params* p, int is_gta, DevParams& d, hi
   d.num_chunks = plan.num_chunks;
   d.chunk_tiles = plan.chunk_tiles;
   const int units = p->batch * p->num_groups * plan.mb;
-  if (plan.variant == 0) {
-    if (plan.nwaves == 1) return launch_tuned_variant<256, 256, 1, 2>(plan, d, units, st, ev);
-    if (plan.nwaves == 2) return launch_tuned_variant<256, 256, 2, 2>(plan, d, units, st, ev);
-    return launch_tuned_variant<256, 256, 4, 3>(plan, d, units, st, ev);
-  }
-  if (plan.variant == 2) {
-    if (plan.nwaves == 1) return launch_tuned_variant<128, 64, 1, 2>(plan, d, units, st, ev);
-    if (plan.nwaves == 2) return launch_tuned_variant<128, 64, 2, 2>(plan, d, units, st, ev);
-    return launch_tuned_variant<128, 64, 4, 3>(plan, d, units, st, ev);
-  }
+  if (plan.dv == 256 && plan.dn == 256) return launch_tuned_shape<256, 256>(plan, d, units, st, ev);
+  if (plan.dv == 128 && plan.dn == 64) return launch_tuned_shape<128, 64>(plan, d, units, st, ev);
   return GLA_ERR_UNSUPPORTED_SHAPE;
 }
 

@@ -22,14 +22,24 @@ RAGGED = [0, 1, 63, 64, 65, 130, 700, 1500, 2, 4]
 
 
 def tuned_available(p):
-    sp = gla.shape_params(batch=p.B, q_len=p.T, num_q_heads=p.h_q, num_groups=p.h_c, d_v=p.d_v,
-                          d_nope=p.d_n, d_rope=p.d_r, page_size=p.page_size,
-                          max_pages_per_seq=p.max_pages, impl=TUNED)
-    return gla.gla_decode_select_impl(sp, p.kind == "gta") == TUNED
+    """Ask the library with the REAL device tensors (strides and alignment take
+    part in the choice) whether the tuned kernel would run."""
+    dp = DeviceProblem(p)
+    out = torch.empty(p.B, p.T, p.h_q, p.d_v, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(p.B, p.T, p.h_q, dtype=torch.float32, device="cuda")
+    prm = gla.make_params(*dp.args()[:6], p.scale, out=out, lse=lse, workspace=None, impl=TUNED)
+    return gla.gla_decode_select_impl(prm, p.kind == "gta") == TUNED
+
+
+TUNED_SHAPES = {("gla", 256), ("gta", 128)}   # (kind, d_v) with an MFMA instantiation
 
 
 def impls_for(p):
-    return [GENERIC, TUNED] if tuned_available(p) else [GENERIC]
+    ok = tuned_available(p)
+    # a shape that has a tuned kernel must really take it: no silent generic-only pass
+    if (p.kind, p.d_v) in TUNED_SHAPES and p.d_r == 64 and p.page_size == 64:
+        assert ok, "tuned kernel unexpectedly unavailable"
+    return [GENERIC, TUNED] if ok else [GENERIC]
 
 
 def test_config0_tiny_all_rows():
