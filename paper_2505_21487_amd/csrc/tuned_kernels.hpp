@@ -99,6 +99,57 @@ __device__ __forceinline__ void lds_wait2(u32x2_t& x, u32x2_t& y) {
   asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x), "+v"(y) : "n"(N));
 }
 
+// MFMA 32x32x16 bf16 issued as inline asm so that every operand's register file
+// is fixed: score accumulators live in architectural VGPRs (the vector ALU
+// reads them), output accumulators and query fragments in accumulation VGPRs.
+// The compiler does not see these as matrix instructions, so the wait states
+// the hardware needs around them are provided by hand where the surrounding
+// code does not already guarantee them:
+//   * a vector-ALU write of an MFMA source needs 2 wait states before the MFMA;
+//   * an MFMA result needs 12 wait states before anything but a dependent MFMA
+//     on the same accumulator reads it (back-to-back accumulation needs none).
+__device__ __forceinline__ void mfma_first_v(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b_acc) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b_acc));
+}
+__device__ __forceinline__ void mfma_acc_v(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b_acc) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b_acc));
+}
+__device__ __forceinline__ void mfma_acc_a(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+template <int N>
+__device__ __forceinline__ void wait_states() {
+  static_assert(N >= 1 && N <= 16, "s_nop covers 1..16 wait states");
+  asm volatile("s_nop %0" ::"n"(N - 1));
+}
+
+// Vector-ALU pieces of the softmax, issued by hand so that they stay exactly
+// where they are written between the MFMAs they overlap with.  v_exp_f32 is a
+// transcendental: its result must not be read by the very next instruction.
+__device__ __forceinline__ float asm_fma(float a, float b, float c) {
+  float d;
+  asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+__device__ __forceinline__ float asm_exp2(float x) {
+  float d;
+  asm volatile("v_exp_f32 %0, %1" : "=v"(d) : "v"(x));
+  return d;
+}
+__device__ __forceinline__ void asm_add(float& acc, float x) {
+  asm volatile("v_add_f32 %0, %0, %1" : "+v"(acc) : "v"(x));
+}
+__device__ __forceinline__ uint32_t asm_cvt_pk_bf16(float lo, float hi) {
+  uint32_t d;
+  asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(d) : "v"(lo), "v"(hi));
+  return d;
+}
+// 16-byte global load straight into an accumulation VGPR tuple (no staging in
+// architectural VGPRs); complete after the next wait_vmcnt<0>().
+__device__ __forceinline__ void load_b128_async(u32x4_t& dst, const void* ptr) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(dst) : "v"(ptr) : "memory");
+}
+
 // A 32-bit global load that is complete when the statement ends.  Used for the
 // rare bookkeeping reads inside the tile loop (page ids, next sequence length):
 // being opaque to the compiler's memory-counter tracking, it cannot make the
@@ -259,7 +310,7 @@ struct TunedTraits {
   static constexpr int kTilesPerPage = kPage / TOK;
   static constexpr size_t kSlotFloats = (size_t)kRows * DV + kRows;  // partial out + lse
   static_assert(TOK == 32 || TOK == 64, "a tile is a page or half a page");
-  static_assert(STAGES >= 2, "need one stage loading while one computes");
+  static_assert(STAGES >= 3, "one stage feeds PV, one the next scores, at least one is loading");
   static_assert(kStateLoads % NWAVES == 0 && kRopeLoads % NWAVES == 0, "tile loads must split evenly over waves");
   static_assert(kLoadsPerWave * kAhead <= 63, "vmcnt range");
   static_assert(DR == 64, "RoPE key tile layout assumes 64 dims");
@@ -275,6 +326,10 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   constexpr int NKN = DN / 16;         // contraction steps over the state dims
   constexpr int NKR = DR / 16;         // ... over the RoPE dims
   constexpr int NDB = DV / 32;         // 32-dim output blocks
+  constexpr int NE = 16 * NTB;         // scores per lane per tile
+  constexpr int NS = (NKN + NKR) * NTB;  // score MFMAs per tile
+  constexpr int NP = (TOK / 16) * NDB;   // value MFMAs per tile
+  constexpr int LPW = TT::kLoadsPerWave;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[TT::kSmemBytes];
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
@@ -317,7 +372,13 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
 
   int pt_b = -1, pt_base = 0;
   int pt_vec = 0;
-  auto issue_tile_loads = [&](const TileCursor& c, int stage) {
+  // Addresses of the next tile to issue (set by dma_prepare, used by dma_load<i>).
+  const unsigned char* dma_sbase = nullptr;
+  const unsigned char* dma_rbase = nullptr;
+  unsigned char* dma_stage = nullptr;
+  int issued = 0;  // tiles whose loads have been issued
+  auto dma_prepare = [&]() {
+    const TileCursor& c = pre;
     const int page_idx = c.j / TT::kTilesPerPage;
     const int tip = c.j - page_idx * TT::kTilesPerPage;  // tile within the page
     if (c.b != pt_b || page_idx < pt_base || page_idx >= pt_base + 64) {
@@ -328,34 +389,37 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     }
     const int g = c.ub / MB;
     const int64_t page = __builtin_amdgcn_readlane(pt_vec, page_idx - pt_base);
-    const unsigned char* sbase = (const unsigned char*)(p.state + page * p.st_s[0] + (int64_t)g * p.st_s[1]) +
-                                 tip * TT::kStateBytes;
-    const unsigned char* rbase = (const unsigned char*)(p.rope + page * p.rp_s[0]) + tip * TT::kRopeBytes;
-    unsigned char* stage_base = smem + stage * TT::kStageBytes;
-#pragma unroll
-    for (int ii = 0; ii < TT::kStateLoads / NWAVES; ++ii) {
-      const int inst = ii * NWAVES + wave;  // 1 KiB slice index within the state tile
+    dma_sbase = (const unsigned char*)(p.state + page * p.st_s[0] + (int64_t)g * p.st_s[1]) +
+                tip * TT::kStateBytes + wave * 1024;
+    dma_rbase = (const unsigned char*)(p.rope + page * p.rp_s[0]) + tip * TT::kRopeBytes + wave * 1024;
+    dma_stage = smem + (issued % STAGES) * TT::kStageBytes + wave * 1024;
+    advance<TOK>(p, UPB, pre);
+    ++issued;
+  };
+  // i-th of this wave's LPW loads of the prepared tile
+  auto dma_load = [&](auto ic) {
+    constexpr int i = decltype(ic)::value;
+    if (p.debug_flags & 1) return;
+    if constexpr (i < TT::kStateLoads / NWAVES) {
+      const int inst = i * NWAVES + wave;  // 1 KiB slice index within the state tile
       const unsigned voff = s_lane_part ^ ((unsigned)swz16(inst * RPL) << 4);
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(sbase + inst * 1024 + voff),
-                                       (lds_void_t*)(stage_base + inst * 1024), 16, 0, 0);
-    }
-#pragma unroll
-    for (int ii = 0; ii < TT::kRopeLoads / NWAVES; ++ii) {
-      const int rinst = ii * NWAVES + wave;
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_sbase + i * NWAVES * 1024 + voff),
+                                       (lds_void_t*)(dma_stage + i * NWAVES * 1024), 16, 0, 0);
+    } else {
+      constexpr int ir = i - TT::kStateLoads / NWAVES;
+      const int rinst = ir * NWAVES + wave;
       const unsigned voff = r_lane_part ^ ((unsigned)(rinst & 1) << 6);
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(rbase + rinst * 1024 + voff),
-                                       (lds_void_t*)(stage_base + TT::kStateBytes + rinst * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_rbase + ir * NWAVES * 1024 + voff),
+                                       (lds_void_t*)(dma_stage + TT::kStateBytes + ir * NWAVES * 1024), 16, 0, 0);
     }
   };
 
   // ---- prologue: fill STAGES-1 stages
-  int issued = 0;
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s) {
     if (issued < n_tiles) {
-      issue_tile_loads(pre, s);
-      advance<TOK>(p, UPB, pre);
-      ++issued;
+      dma_prepare();
+      static_for<0, LPW>(dma_load);
     }
   }
 
@@ -384,26 +448,179 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       v_off[d4][a] = (unsigned)((4 * hi + tr_r) * ROWB + (lc << 4) + (tr_q & 1) * 8);
     }
 
-  const float sc2 = p.scale * 1.4426950408889634f;  // scores in base-2 units
+  const float sc2 = p.scale * 1.4426950408889634f;  // scores in base-2 units (scale > 0)
+  u32x4_t ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 x 8
+  pin_arch(ones_bits);  // a live register, never re-materialised right in front of an MFMA
 
   // ---- per-unit state
-  u32x4_t qn[NKN];  // raw bf16 bits: kept as integer vectors so the register pins see plain 128-bit tuples
+  u32x4_t qn[NKN];  // raw bf16 bits: integer vectors, so the register pins see plain 128-bit tuples
   u32x4_t qr[NKR];
   f32x16_t o[NDB];
-  // l_run: exact fp32 row sum (for the log-sum-exp); l_rnd: sum of the weights
-  // as rounded to bf16 for the PV product, which is what the output must be
-  // divided by for the rounded weights to still sum to one.
-  float m_ref = -INFINITY, l_run = 0.f, l_rnd = 0.f;
+  f32x16_t o_one;   // every row: sum of the bf16-rounded weights (V block of ones)
+  float m_ref = -INFINITY, l_run = 0.f;
   int n_vis = 0, n_vis_min = 0;
   bool row_valid = false;
   int row_b = 0, row_t = 0, row_h = 0;
-  bool unit_start = true;
 
-  for (int k = 0; k < n_tiles; ++k) {
-    const int stage = k % STAGES;
-    const unsigned sa = lds_base + (unsigned)(stage * TT::kStageBytes);
+  // ---- building blocks of the tile pipeline ---------------------------------------
+  auto stage_addr = [&](int kk) { return lds_base + (unsigned)((kk % STAGES) * TT::kStageBytes); };
 
-    if (unit_start) {
+  // zero the value rows at or beyond the sequence end in a freshly landed tile:
+  // those slots may hold anything (NaN included) and 0-weight x garbage must not leak
+  auto zero_tail = [&](int kk, int tile_j, int L) {
+    const int tok0 = tile_j * TOK;
+    if (tok0 + TOK > L) {
+      const int valid = L - tok0;
+      unsigned char* sb = smem + (kk % STAGES) * TT::kStageBytes;
+      for (int off = valid * ROWB + tid * 16; off < TT::kStateBytes; off += TT::kThreads * 16)
+        *(u32x4_t*)(sb + off) = u32x4_t{0, 0, 0, 0};
+    }
+  };
+
+  constexpr int RS = 8, PD = 7;    // operand ring: slots / reads in flight
+  constexpr int VRS = 8, VPD = 7;
+
+  // one score MFMA (step i of NS) with its operand ring bookkeeping
+  u32x4_t kfrag[RS];
+  unsigned ka[8], ra[NKR];
+  auto s_addr = [&](unsigned sa) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ka[e] = k_off[e] + sa;
+#pragma unroll
+    for (int e = 0; e < NKR; ++e) ra[e] = r_off[e] + sa;
+  };
+  auto s_issue = [&](auto ic) {
+    constexpr int i = decltype(ic)::value;
+    constexpr int ks = i / NTB, tb = i % NTB;
+    if constexpr (ks < NKN) lds_read_b128<tb * 32 * ROWB + ((2 * ks) & ~15) * 16>(kfrag[i % RS], ka[ks & 7]);
+    else lds_read_b128<tb * 32 * 128>(kfrag[i % RS], ra[ks - NKN]);
+  };
+  auto s_step = [&](auto ic, f32x16_t (&acc)[NTB]) {
+    constexpr int i = decltype(ic)::value;
+    constexpr int ks = i / NTB, tb = i % NTB;
+    constexpr int left = NS - 1 - i;
+    lds_wait<(left < PD - 1 ? left : PD - 1)>(kfrag[i % RS]);
+    if constexpr (ks == 0) mfma_first_v(acc[tb], kfrag[i % RS], qn[0]);
+    else if constexpr (ks < NKN) mfma_acc_v(acc[tb], kfrag[i % RS], qn[ks]);
+    else mfma_acc_v(acc[tb], kfrag[i % RS], qr[ks - NKN]);
+    if constexpr (i + PD < NS) s_issue(std::integral_constant<int, i + PD>{});
+  };
+
+  // value operand ring
+  u32x2_t vlo[VRS], vhi[VRS];
+  unsigned va[4][2];
+  auto v_addr = [&](unsigned sa) {
+#pragma unroll
+    for (int d4 = 0; d4 < 4; ++d4)
+#pragma unroll
+      for (int a = 0; a < 2; ++a) va[d4][a] = v_off[d4][a] + sa;
+  };
+  auto v_issue = [&](auto ic) {
+    constexpr int i = decltype(ic)::value;
+    constexpr int st = i / NDB, db = i % NDB;
+    constexpr int base = st * 16 * ROWB + (db >> 2) * 256;
+    lds_read_tr16_b64<base>(vlo[i % VRS], va[db & 3][0]);
+    lds_read_tr16_b64<base + 8 * ROWB>(vhi[i % VRS], va[db & 3][1]);
+  };
+  u32x4_t pf[TOK / 16];  // bf16 weights: B operands of the 16-token contraction steps
+  auto v_step = [&](auto ic) {
+    constexpr int i = decltype(ic)::value;
+    constexpr int st = i / NDB, db = i % NDB;
+    constexpr int left = NP - 1 - i;
+    lds_wait2<2 * (left < VPD - 1 ? left : VPD - 1)>(vlo[i % VRS], vhi[i % VRS]);
+    const u32x4_t a4 = {vlo[i % VRS][0], vlo[i % VRS][1], vhi[i % VRS][0], vhi[i % VRS][1]};
+    mfma_acc_a(o[db], a4, pf[st]);
+    if constexpr (i + VPD < NP) v_issue(std::integral_constant<int, i + VPD>{});
+  };
+
+  // softmax of one tile, cut into NE element steps that are interleaved with MFMAs.
+  // Scores are in s_cur (raw dot products); weights go to pf, their exact sum to lsum.
+  f32x16_t s_cur[NTB], s_nxt[NTB];
+  float neg_m = 0.f, lsum = 0.f;
+  float p_prev = 0.f, p_prev2 = 0.f;  // weights of the two preceding elements
+  // element e: x = s * sc2 - m ; p = 2^x ; then, one element later (so that the
+  // transcendental result is never consumed by the next instruction), p is
+  // added to the row sum, and after every odd element a pair is packed to bf16.
+  auto sm_finish = [&](auto ec) {  // consume element e (already exponentiated)
+    constexpr int e = decltype(ec)::value;
+    constexpr int tb = e / 16, i = e % 16;
+    asm_add(lsum, p_prev);
+    if constexpr ((i & 1) == 1) pf[tb * 2 + (i >> 3)][(i & 7) >> 1] = asm_cvt_pk_bf16(p_prev2, p_prev);
+  };
+  auto sm_elem = [&](auto ec) {
+    constexpr int e = decltype(ec)::value;
+    constexpr int tb = e / 16, i = e % 16;
+    const float x = asm_fma(s_cur[tb][i], sc2, neg_m);
+    const float pv = asm_exp2(x);
+    if constexpr (e > 0) sm_finish(std::integral_constant<int, e - 1>{});
+    p_prev2 = p_prev;
+    p_prev = pv;
+    if constexpr (e == NE - 1) {
+      wait_states<1>();
+      sm_finish(std::integral_constant<int, NE - 1>{});
+    }
+  };
+  // elements [lo, hi) of the tile's NE scores
+  auto sm_range = [&](auto loc, auto hic) {
+    constexpr int lo = decltype(loc)::value, hi_ = decltype(hic)::value;
+    static_for<lo, hi_>(sm_elem);
+  };
+
+  // running-max bookkeeping for the tile in s_cur (tile index j of the unit):
+  // masks invisible keys, and moves the reference when the row max has grown by
+  // more than 2^8 (lazy: weights stay <= 256 otherwise), rescaling O and the sums
+  auto sm_begin = [&](int tile_j) {
+    const int tile_tok0 = tile_j * TOK;
+    if (tile_tok0 + TOK > n_vis_min) {
+      const int lim = n_vis - tile_tok0 - 4 * hi;  // element (tb, i) is visible iff its constant < lim
+#pragma unroll
+      for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          s_cur[tb][i] = (32 * tb + 8 * (i >> 2) + (i & 3)) < lim ? s_cur[tb][i] : -INFINITY;
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_cur[tb][i]);
+    mx = half_swap_max(mx) * sc2;
+    const bool bump = mx > m_ref + 8.0f;
+    if (__ballot(bump)) {
+      wait_states<16>();  // output accumulators are about to be read by the vector ALU
+      const float m_new = bump ? mx : m_ref;
+      const float alpha = bump ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.0f;  // m_ref = -inf -> 0
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {  // one 16-register block at a time through the vector ALU
+        f32x16_t t = o[db];
+        pin_arch(t);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) t[i] *= alpha;
+        o[db] = t;
+        pin_acc(o[db]);
+      }
+      {
+        f32x16_t t = o_one;
+        pin_arch(t);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) t[i] *= alpha;
+        o_one = t;
+        pin_acc(o_one);
+      }
+      m_ref = m_new;
+    }
+    neg_m = m_ref == -INFINITY ? 0.f : -m_ref;
+    lsum = 0.f;
+  };
+
+  int k = 0;  // chunk-local index of the tile at `cur`
+  while (k < n_tiles) {
+    // ================= segment: the tiles of cur's unit that lie in this chunk
+    const int seg_n = min(n_tiles - k, cur.tiles_b - cur.j);
+    const int seg_j0 = cur.j;
+    const int seg_L = cur.L;
+    {
       // query fragments of this wave's 32 rows: B operand, lane holds 8 dims of row `col`
       const int g = cur.ub / MB;
       const int mb = cur.ub - g * MB;
@@ -415,19 +632,12 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       row_b = cur.b;
       const uint16_t* qn_ptr = p.q_nope + row_b * p.qn_s[0] + row_t * p.qn_s[1] + row_h * p.qn_s[2] + 8 * hi;
       const uint16_t* qr_ptr = p.q_rope + row_b * p.qr_s[0] + row_t * p.qr_s[1] + row_h * p.qr_s[2] + 8 * hi;
-      const uint32_t keep = row_valid ? 0xffffffffu : 0u;  // padding rows get a zero query
+      // padding rows re-read the last valid row: their columns are computed and never stored
 #pragma unroll
-      for (int ks = 0; ks < NKN; ++ks) {
-        u32x4_t v = *(const u32x4_t*)(qn_ptr + 16 * ks);
-        v &= keep;
-        qn[ks] = v;
-      }
+      for (int ks = 0; ks < NKN; ++ks) load_b128_async(qn[ks], qn_ptr + 16 * ks);
 #pragma unroll
-      for (int ks = 0; ks < NKR; ++ks) {
-        u32x4_t v = *(const u32x4_t*)(qr_ptr + 16 * ks);
-        v &= keep;
-        qr[ks] = v;
-      }
+      for (int ks = 0; ks < NKR; ++ks) load_b128_async(qr[ks], qr_ptr + 16 * ks);
+      wait_vmcnt<0>();
 #pragma unroll
       for (int ks = 0; ks < NKN; ++ks) pin_acc(qn[ks]);
 #pragma unroll
@@ -438,229 +648,119 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
         for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
         pin_acc(o[db]);
       }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o_one[i] = 0.f;
+      pin_acc(o_one);
       m_ref = -INFINITY;
       l_run = 0.f;
-      l_rnd = 0.f;
       // visible keys of this lane's row; padding rows are left unmasked (never stored)
       n_vis = row_valid ? (p.causal ? cur.L - p.T + 1 + row_t : cur.L) : 0x7fffffff;
       int mn = n_vis;
 #pragma unroll
       for (int off = 32; off >= 1; off >>= 1) mn = min(mn, __shfl_xor(mn, off, 64));
       n_vis_min = uniform(mn);
-      unit_start = false;
     }
 
-    // ---- wait for tile k, make it visible to all waves, free stage (k-1) % STAGES
-    if (k + TT::kAhead < n_tiles) wait_vmcnt<TT::kLoadsPerWave * TT::kAhead>();
+    // ---- segment prologue: scores of its first tile
+    if (issued - 1 - k >= STAGES - 2) wait_vmcnt<LPW * (STAGES - 2)>();
     else wait_vmcnt<0>();
     lds_barrier();
+    zero_tail(k, seg_j0, seg_L);
+    s_addr(stage_addr(k));
+    static_for<0, (PD < NS ? PD : NS)>(s_issue);
+    wait_states<2>();  // query fragments were just moved into place by the vector ALU
+    static_for<0, NS>([&](auto ic) { s_step(ic, s_nxt); });
+    wait_states<16>();  // the scores are read by the vector ALU right below
 
-    const int tile_tok0 = cur.j * TOK;
-    if (tile_tok0 + TOK > cur.L) {
-      // last tile of the sequence: slots at or beyond L may hold anything (NaN
-      // included); zero those value rows so that 0-weight x garbage cannot leak.
-      const int valid = cur.L - tile_tok0;
-      unsigned char* sb = smem + stage * TT::kStageBytes;
-      for (int off = valid * ROWB + tid * 16; off < TT::kStateBytes; off += TT::kThreads * 16)
-        *(u32x4_t*)(sb + off) = u32x4_t{0, 0, 0, 0};
+    for (int t = 0; t < seg_n; ++t, ++k) {
+      const bool has_next = t + 1 < seg_n;
+#pragma unroll
+      for (int tb = 0; tb < NTB; ++tb) s_cur[tb] = s_nxt[tb];
+      // ---- tile k+1 landed?  (also: every wave is done with tile k-1, so its stage is free)
+      if (has_next) {
+        if (issued - 2 - k >= STAGES - 3) wait_vmcnt<LPW * (STAGES - 3)>();
+        else wait_vmcnt<0>();
+      }
       lds_barrier();
-    }
+      if (has_next) zero_tail(k + 1, seg_j0 + t + 1, seg_L);
 
-    // ---- prefetch tile k + STAGES - 1 into the stage just released
-    if (issued < n_tiles) {
-      issue_tile_loads(pre, (k + STAGES - 1) % STAGES);
-      advance<TOK>(p, UPB, pre);
-      ++issued;
-    }
-
-#pragma unroll
-    for (int db = 0; db < NDB; ++db) pin_acc(o[db]);
-#pragma unroll
-    for (int ks = 0; ks < NKN; ++ks) pin_acc(qn[ks]);
-#pragma unroll
-    for (int ks = 0; ks < NKR; ++ks) pin_acc(qr[ks]);
-
-    // ---- S^T = K . Q^T, NTB blocks of 32 tokens; operand reads run PD ahead
-    f32x16_t s[NTB];
-#pragma unroll
-    for (int tb = 0; tb < NTB; ++tb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[tb][i] = 0.f;
-    {
-      constexpr int NS = (NKN + NKR) * NTB, RS = 6, PD = 5;
-      unsigned ka[8], ra[NKR];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) ka[e] = k_off[e] + sa;
-#pragma unroll
-      for (int e = 0; e < NKR; ++e) ra[e] = r_off[e] + sa;
-      u32x4_t frag[RS];
-      auto issue = [&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        constexpr int ks = i / NTB, tb = i % NTB;
-        if constexpr (ks < NKN) lds_read_b128<tb * 32 * ROWB + ((2 * ks) & ~15) * 16>(frag[i % RS], ka[ks & 7]);
-        else lds_read_b128<tb * 32 * 128>(frag[i % RS], ra[ks - NKN]);
-      };
-      static_for<0, (PD < NS ? PD : NS)>(issue);
+      // ---- [A] softmax of tile k on the vector ALU, interleaved with the score
+      //          MFMAs of tile k+1.  One code path: without a next tile the MFMAs
+      //          re-run on tile k's stage and their result is simply dropped.
+      s_addr(stage_addr(has_next ? k + 1 : k));
+      static_for<0, (PD < NS ? PD : NS)>(s_issue);
+      sm_begin(seg_j0 + t);
       static_for<0, NS>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
-        constexpr int ks = i / NTB, tb = i % NTB;
-        constexpr int left = NS - 1 - i;
-        lds_wait<(left < PD - 1 ? left : PD - 1)>(frag[i % RS]);
-        const bf16x8_t a = __builtin_bit_cast(bf16x8_t, frag[i % RS]);
-        if constexpr (ks < NKN) s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8_t, qn[ks]), s[tb], 0, 0, 0);
-        else s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8_t, qr[ks - NKN]), s[tb], 0, 0, 0);
-        if constexpr (i < NTB) pin_arch(s[tb]);  // scores are consumed by the vector ALU
-        if constexpr (i + PD < NS) issue(std::integral_constant<int, i + PD>{});
+        s_step(ic, s_nxt);
+        sm_range(std::integral_constant<int, (i * NE) / NS>{}, std::integral_constant<int, ((i + 1) * NE) / NS>{});
+        __builtin_amdgcn_sched_barrier(0);
       });
-    }
+      l_run += lsum;
 
-#pragma unroll
-    for (int tb = 0; tb < NTB; ++tb) pin_arch(s[tb]);
-
-    // ---- value operand reads for the first PV steps go out before the softmax
-    constexpr int NP = (TOK / 16) * NDB, VRS = 6, VPD = 5;
-    unsigned va[4][2];
-#pragma unroll
-    for (int d4 = 0; d4 < 4; ++d4)
-#pragma unroll
-      for (int a = 0; a < 2; ++a) va[d4][a] = v_off[d4][a] + sa;
-    u32x2_t vlo[VRS], vhi[VRS];
-    auto v_issue = [&](auto ic) {
-      constexpr int i = decltype(ic)::value;
-      constexpr int st = i / NDB, db = i % NDB;
-      constexpr int base = st * 16 * ROWB + (db >> 2) * 256;
-      lds_read_tr16_b64<base>(vlo[i % VRS], va[db & 3][0]);
-      lds_read_tr16_b64<base + 8 * ROWB>(vhi[i % VRS], va[db & 3][1]);
-    };
-    static_for<0, (VPD < NP ? VPD : NP)>(v_issue);
-
-    // ---- online softmax in base 2; lane holds TOK/2 scores of row `col`:
-    // token(tb, i) = 32*tb + 8*(i/4) + 4*hi + i%4
-    const bool need_mask = tile_tok0 + TOK > n_vis_min;
-    float mx = -INFINITY;
-    if (need_mask) {
-      const int lim = n_vis - tile_tok0 - 4 * hi;  // element (tb, i) is visible iff its constant < lim
-#pragma unroll
-      for (int tb = 0; tb < NTB; ++tb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float x = (32 * tb + 8 * (i >> 2) + (i & 3)) < lim ? s[tb][i] * sc2 : -INFINITY;
-          s[tb][i] = x;
-          mx = fmaxf(mx, x);
+      // ---- [B] O^T += V^T . P^T for tile k, interleaved with the loads of the
+      //          tile that will reuse the stage of tile k-1.  Contraction slot
+      //          (hi, j) of step st is token 16*st + 8*(j/4) + 4*hi + j%4,
+      //          matching the score accumulator layout.
+      v_addr(stage_addr(k));
+      static_for<0, (VPD < NP ? VPD : NP)>(v_issue);
+      wait_states<2>();  // the last weights were packed by the vector ALU just above
+      const bool do_dma = issued < n_tiles;
+      if (do_dma) dma_prepare();
+      static_for<0, NP>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        v_step(ic);
+        if constexpr (((i + 1) * LPW) / NP > (i * LPW) / NP) {
+          if (do_dma) dma_load(std::integral_constant<int, (i * LPW) / NP>{});
         }
-    } else {
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      wait_states<2>();
 #pragma unroll
-      for (int tb = 0; tb < NTB; ++tb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float x = s[tb][i] * sc2;
-          s[tb][i] = x;
-          mx = fmaxf(mx, x);
-        }
+      for (int st = 0; st < TOK / 16; ++st) mfma_acc_a(o_one, ones_bits, pf[st]);
+      advance<TOK>(p, UPB, cur);
     }
-    mx = half_swap_max(mx);
-    // lazy reference update: keep the old reference while the row max stays
-    // within 2^8 of it (probabilities then stay <= 256, exact enough in fp32/bf16)
-    const bool bump = mx > m_ref + 8.0f;
-    if (__ballot(bump)) {
-      const float m_new = bump ? mx : m_ref;
-      const float alpha = bump ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.0f;  // m_ref = -inf -> 0
-      l_run *= alpha;
-      l_rnd *= alpha;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db) pin_acc(o[db]);
-      m_ref = m_new;
-    }
-    const float m_use = m_ref == -INFINITY ? 0.f : m_ref;
-    float lsum = 0.f;
-    bf16x8_t pf[TOK / 16];  // B operands of the 16-token contraction steps
-#pragma unroll
-    for (int tb = 0; tb < NTB; ++tb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float pv = __builtin_amdgcn_exp2f(s[tb][i] - m_use);
-        lsum += pv;
-        pf[tb * 2 + (i >> 3)][i & 7] = (__bf16)pv;
-      }
-    l_run += lsum;
-    float rsum = 0.f;
-#pragma unroll
-    for (int st = 0; st < TOK / 16; ++st) {
-      const u32x4_t w = __builtin_bit_cast(u32x4_t, pf[st]);
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        rsum += __builtin_bit_cast(float, w[e] << 16) + __builtin_bit_cast(float, w[e] & 0xffff0000u);
-    }
-    l_rnd += rsum;
 
-    // ---- O^T += V^T . P^T ; contraction slot (hi, j) of step st is token
-    // 16*st + 8*(j/4) + 4*hi + j%4, matching the accumulator layout above
-    static_for<0, NP>([&](auto ic) {
-      constexpr int i = decltype(ic)::value;
-      constexpr int st = i / NDB, db = i % NDB;
-      constexpr int left = NP - 1 - i;
-      lds_wait2<2 * (left < VPD - 1 ? left : VPD - 1)>(vlo[i % VRS], vhi[i % VRS]);
-      const u32x4_t a4 = {vlo[i % VRS][0], vlo[i % VRS][1], vhi[i % VRS][0], vhi[i % VRS][1]};
-      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a4), pf[st], o[db], 0, 0, 0);
-      if constexpr (i + VPD < NP) v_issue(std::integral_constant<int, i + VPD>{});
-    });
-
-#pragma unroll
-    for (int db = 0; db < NDB; ++db) pin_acc(o[db]);
-
-    // ---- end of unit (or of chunk): write the result
-    const bool unit_done = cur.j + 1 == cur.tiles_b;
-    if (unit_done || k + 1 == n_tiles) {
-      // the unit is complete here iff this chunk also held its first tile
-      const bool complete = unit_done && (k >= cur.j);
+    // ================= end of segment: write the unit's result or its partial
+    wait_states<16>();  // output accumulators: last MFMA -> vector ALU reads
+    {
+      const bool unit_done = seg_j0 + seg_n == (seg_L + TOK - 1) / TOK;
+      const bool complete = unit_done && seg_j0 == 0;
       const float l_tot = half_swap_sum(l_run);
-      const float r_tot = half_swap_sum(l_rnd);
+      const float r_tot = o_one[0];
       const float inv = r_tot > 0.f ? 1.0f / r_tot : 0.f;
       const float lse = l_tot > 0.f ? (m_ref + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
-      if (complete) {
-        if (row_valid) {
-          const int64_t ob = row_b * p.out_s[0] + row_t * p.out_s[1] + row_h * p.out_s[2];
-          if (hi == 0) p.lse[((int64_t)row_b * p.T + row_t) * p.h_q + row_h] = lse;
-#pragma unroll
-          for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-              const int dim = 32 * db + 8 * q4 + 4 * hi;
-              f32x4_t v = {o[db][4 * q4] * inv, o[db][4 * q4 + 1] * inv, o[db][4 * q4 + 2] * inv,
-                           o[db][4 * q4 + 3] * inv};
-              if (p.out_fp32) {
-                *(f32x4_t*)((float*)p.out + ob + dim) = v;
-              } else {
-                u32x2_t pk;
-                pk[0] = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
-                pk[1] = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
-                *(u32x2_t*)((uint16_t*)p.out + ob + dim) = pk;
-              }
-            }
-        }
-      } else {
-        // partial: slot 0 if the unit began before this chunk, slot 1 otherwise
-        const int which = (k < cur.j) ? 0 : 1;
-        float* slot = p.ws_out + ((size_t)blockIdx.x * 2 + which) * TT::kSlotFloats;
-        const int lr = wave * 32 + col;
-        if (hi == 0) slot[(size_t)TT::kRows * DV + lr] = lse;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            const int dim = 32 * db + 8 * q4 + 4 * hi;
-            f32x4_t v = {o[db][4 * q4] * inv, o[db][4 * q4 + 1] * inv, o[db][4 * q4 + 2] * inv,
-                         o[db][4 * q4 + 3] * inv};
-            *(f32x4_t*)(slot + (size_t)lr * DV + dim) = v;
-          }
+      const int lr = wave * 32 + col;
+      const int64_t ob = row_b * p.out_s[0] + row_t * p.out_s[1] + row_h * p.out_s[2];
+      // partial: slot 1 if the unit's first tile is in this chunk, slot 0 if it began earlier
+      float* slot = p.ws_out + ((size_t)blockIdx.x * 2 + (seg_j0 == 0 ? 1 : 0)) * TT::kSlotFloats;
+      if (hi == 0) {
+        if (!complete) slot[(size_t)TT::kRows * DV + lr] = lse;
+        else if (row_valid) p.lse[((int64_t)row_b * p.T + row_t) * p.h_q + row_h] = lse;
       }
-      unit_start = true;
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {  // one 16-register block at a time
+        f32x16_t t = o[db];
+        pin_arch(t);
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int dim = 32 * db + 8 * q4 + 4 * hi;
+          const f32x4_t v = {t[4 * q4] * inv, t[4 * q4 + 1] * inv, t[4 * q4 + 2] * inv, t[4 * q4 + 3] * inv};
+          if (!complete) {
+            *(f32x4_t*)(slot + (size_t)lr * DV + dim) = v;
+          } else if (row_valid) {
+            if (p.out_fp32) {
+              *(f32x4_t*)((float*)p.out + ob + dim) = v;
+            } else {
+              u32x2_t pk;
+              pk[0] = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
+              pk[1] = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
+              *(u32x2_t*)((uint16_t*)p.out + ob + dim) = pk;
+            }
+          }
+        }
+      }
     }
-    advance<TOK>(p, UPB, cur);
   }
 }
 
@@ -774,6 +874,7 @@ inline void tuning_override(int* tok, int* stages, int* per_cu) {
 
 inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) {
   if (p->page_size != kPage || p->d_rope != 64) return false;
+  if (!(p->softmax_scale > 0.f)) return false;  // row maxima are taken on the raw dot products
   if (!((!is_gta && p->d_v == 256) || (is_gta && p->d_v == 128))) return false;
   // layout the kernels assume: token rows contiguous, everything 16-byte aligned
   if (p->state_stride[2] != p->d_v || p->rope_stride[1] != p->d_rope) return false;
@@ -790,8 +891,8 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
   plan->nwaves = nwaves;
   plan->rows = 32 * nwaves;
   plan->mb = (rows_group + plan->rows - 1) / plan->rows;
-  int tok = 32, stages = 4, per_cu = nwaves == 4 ? 1 : (nwaves == 2 ? 2 : 4);
-  if (nwaves == 4) { tok = 64; stages = 3; }
+  int tok = 32, stages = 4, per_cu = nwaves == 4 ? 1 : 2;
+  if (nwaves == 4) stages = 8;
   tuning_override(&tok, &stages, &per_cu);
   plan->tok = tok;
   plan->stages = stages;
@@ -840,15 +941,16 @@ inline int launch_tuned_shape(const TunedPlan& plan, DevParams& d, int units, hi
                               hipEvent_t* ev) {
   const int key = plan.nwaves * 10000 + plan.tok * 100 + plan.stages;
   switch (key) {
-    case 1 * 10000 + 3200 + 2: return launch_tuned_variant<DV, DN, 1, 32, 2>(plan, d, units, st, ev);
+    case 1 * 10000 + 3200 + 3: return launch_tuned_variant<DV, DN, 1, 32, 3>(plan, d, units, st, ev);
     case 1 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 1, 32, 4>(plan, d, units, st, ev);
-    case 2 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 2, 32, 4>(plan, d, units, st, ev);
-    case 2 * 10000 + 3200 + 2: return launch_tuned_variant<DV, DN, 2, 32, 2>(plan, d, units, st, ev);
     case 2 * 10000 + 3200 + 3: return launch_tuned_variant<DV, DN, 2, 32, 3>(plan, d, units, st, ev);
-    case 2 * 10000 + 6400 + 2: return launch_tuned_variant<DV, DN, 2, 64, 2>(plan, d, units, st, ev);
-    case 4 * 10000 + 6400 + 3: return launch_tuned_variant<DV, DN, 4, 64, 3>(plan, d, units, st, ev);
+    case 2 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 2, 32, 4>(plan, d, units, st, ev);
+    case 2 * 10000 + 3200 + 8: return launch_tuned_variant<DV, DN, 2, 32, 8>(plan, d, units, st, ev);
+    case 2 * 10000 + 6400 + 4: return launch_tuned_variant<DV, DN, 2, 64, 4>(plan, d, units, st, ev);
     case 4 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 4, 32, 4>(plan, d, units, st, ev);
     case 4 * 10000 + 3200 + 6: return launch_tuned_variant<DV, DN, 4, 32, 6>(plan, d, units, st, ev);
+    case 4 * 10000 + 3200 + 8: return launch_tuned_variant<DV, DN, 4, 32, 8>(plan, d, units, st, ev);
+    case 4 * 10000 + 6400 + 4: return launch_tuned_variant<DV, DN, 4, 64, 4>(plan, d, units, st, ev);
     default: return GLA_ERR_UNSUPPORTED_SHAPE;
   }
 }
@@ -860,6 +962,7 @@ inline int tuned_launch(const gla_decode_params* p, int is_gta, DevParams& d, hi
   d.ws_out = (float*)p->workspace;
   d.num_chunks = plan.num_chunks;
   d.chunk_tiles = plan.chunk_tiles;
+  if (const char* e = std::getenv("GLA_DEBUG")) d.debug_flags = std::atoi(e);
   const int units = p->batch * p->num_groups * plan.mb;
   if (plan.dv == 256 && plan.dn == 256) return launch_tuned_shape<256, 256>(plan, d, units, st, ev);
   if (plan.dv == 128 && plan.dn == 64) return launch_tuned_shape<128, 64>(plan, d, units, st, ev);
