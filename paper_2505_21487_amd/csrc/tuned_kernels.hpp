@@ -322,14 +322,19 @@ template <int DV, int DN, int DR, int NWAVES, int TOK, int STAGES>
 __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   using TT = TunedTraits<DV, DN, DR, NWAVES, TOK, STAGES>;
   constexpr int ROWB = TT::kRowBytes;
-  constexpr int NTB = TOK / 32;        // 32-token blocks per tile
-  constexpr int NKN = DN / 16;         // contraction steps over the state dims
-  constexpr int NKR = DR / 16;         // ... over the RoPE dims
-  constexpr int NDB = DV / 32;         // 32-dim output blocks
-  constexpr int NE = 16 * NTB;         // scores per lane per tile
+  constexpr int SB = TT::kStageBytes;
+  constexpr int NTB = TOK / 32;          // 32-token blocks per tile
+  constexpr int NKN = DN / 16;           // contraction steps over the state dims
+  constexpr int NKR = DR / 16;           // ... over the RoPE dims
+  constexpr int NDB = DV / 32;           // 32-dim output blocks
+  constexpr int NE = 16 * NTB;           // scores per lane per tile
   constexpr int NS = (NKN + NKR) * NTB;  // score MFMAs per tile
   constexpr int NP = (TOK / 16) * NDB;   // value MFMAs per tile
+  constexpr int NB = NP + TOK / 16;      // ... plus the row-sum MFMAs
   constexpr int LPW = TT::kLoadsPerWave;
+  constexpr int SLW = TT::kStateLoads / NWAVES;  // 1 KiB state blocks per wave and tile
+  constexpr int RLW = TT::kRopeLoads / NWAVES;   // 1 KiB RoPE blocks per wave and tile
+  constexpr int TPP = TT::kTilesPerPage;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[TT::kSmemBytes];
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
@@ -358,59 +363,87 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
 
   // ---- tile loads, global -> LDS, 16 B per lane, 1 KiB per wave instruction.
   // The LDS side is linear in the lane index, so each lane fetches the global
-  // chunk whose swizzled home is its LDS slot.  With inst = ii * NWAVES + wave
-  // the global byte offset of lane's chunk is  inst * 1024 + (lane_part ^ key(inst) << 4):
-  // one XOR per load.  Page ids are fetched 64 at a time, one per lane, and
-  // broadcast from the owning lane when a tile is issued.
+  // chunk whose swizzled home is its LDS slot.  Wave w moves the contiguous
+  // 1 KiB blocks [w*SLW, (w+1)*SLW) of the state tile and [w*RLW, (w+1)*RLW) of
+  // the RoPE tile; block i of a wave sits at  i*1024 + (lane_part ^ key(i) << 4)
+  // past the wave's start, i.e. one XOR per load, and four loads share one
+  // pair of base addresses through the instruction's immediate offset (which
+  // the hardware adds to the global and to the LDS address alike).  Page ids
+  // are fetched 64 at a time, one per lane, and broadcast from the owning lane.
   constexpr int RPL = 1024 / ROWB;  // state rows per wave load
   constexpr int CPR = ROWB / 16;    // 16 B chunks per state row
   const int s_rl = lane / CPR, s_pc = lane % CPR;
-  const unsigned s_lane_part =
-      (unsigned)(s_rl * ROWB + ((s_pc & ~15) << 4) + (((s_pc & 15) ^ swz16(s_rl)) << 4));
+  const unsigned s_lane_w =
+      (unsigned)(s_rl * ROWB + ((s_pc & ~15) << 4) + (((s_pc & 15) ^ swz16(s_rl) ^ swz16(wave * SLW * RPL)) << 4));
   const int r_rl = lane >> 3, r_pc = lane & 7;
-  const unsigned r_lane_part = (unsigned)(r_rl * 128 + ((r_pc ^ (r_rl >> 1)) << 4));
+  const unsigned r_lane_w = (unsigned)(r_rl * 128 + ((r_pc ^ (r_rl >> 1) ^ (((wave * RLW) & 1) << 2)) << 4));
 
   int pt_b = -1, pt_base = 0;
   int pt_vec = 0;
-  // Addresses of the next tile to issue (set by dma_prepare, used by dma_load<i>).
-  const unsigned char* dma_sbase = nullptr;
-  const unsigned char* dma_rbase = nullptr;
-  unsigned char* dma_stage = nullptr;
+  int pre_g = pre.ub / MB;
+  const unsigned char* pre_sp = nullptr;  // state / RoPE page of the prefetch cursor (group folded in)
+  const unsigned char* pre_rp = nullptr;
+  bool pre_page_valid = false;
+  // addresses of the tile being issued (this wave's share)
+  const unsigned char* dma_s = nullptr;
+  const unsigned char* dma_r = nullptr;
+  unsigned char* dma_l = nullptr;
   int issued = 0;  // tiles whose loads have been issued
-  auto dma_prepare = [&]() {
-    const TileCursor& c = pre;
-    const int page_idx = c.j / TT::kTilesPerPage;
-    const int tip = c.j - page_idx * TT::kTilesPerPage;  // tile within the page
-    if (c.b != pt_b || page_idx < pt_base || page_idx >= pt_base + 64) {
-      pt_b = c.b;
-      pt_base = page_idx;
-      const int idx = min(page_idx + lane, p.max_pages - 1);
-      pt_vec = load_i32_sync(p.page_table + (int64_t)c.b * p.max_pages + idx);
+
+  // Prepare the loads of the next tile into `stage`.  Once every tile of the
+  // chunk has been issued the previous tile's addresses are kept: the loads
+  // then re-read lines that are still in L2 into a stage nobody reads, which
+  // keeps the steady-state loop free of branches around the load instructions.
+  auto dma_prepare = [&](int stage) {
+    dma_l = smem + stage * SB + wave * (SLW * 1024);
+    if (issued >= n_tiles) return;
+    const int page_idx = pre.j / TPP;
+    const int tip = pre.j - page_idx * TPP;  // tile within the page
+    if (tip == 0 || !pre_page_valid) {
+      if (pre.b != pt_b || page_idx < pt_base || page_idx >= pt_base + 64) {
+        pt_b = pre.b;
+        pt_base = page_idx;
+        const int idx = min(page_idx + lane, p.max_pages - 1);
+        pt_vec = load_i32_sync(p.page_table + (int64_t)pre.b * p.max_pages + idx);
+      }
+      const int64_t page = __builtin_amdgcn_readlane(pt_vec, page_idx - pt_base);
+      pre_sp = (const unsigned char*)(p.state + page * p.st_s[0] + (int64_t)pre_g * p.st_s[1]) + wave * (SLW * 1024);
+      pre_rp = (const unsigned char*)(p.rope + page * p.rp_s[0]) + wave * (RLW * 1024);
+      pre_page_valid = true;
     }
-    const int g = c.ub / MB;
-    const int64_t page = __builtin_amdgcn_readlane(pt_vec, page_idx - pt_base);
-    dma_sbase = (const unsigned char*)(p.state + page * p.st_s[0] + (int64_t)g * p.st_s[1]) +
-                tip * TT::kStateBytes + wave * 1024;
-    dma_rbase = (const unsigned char*)(p.rope + page * p.rp_s[0]) + tip * TT::kRopeBytes + wave * 1024;
-    dma_stage = smem + (issued % STAGES) * TT::kStageBytes + wave * 1024;
-    advance<TOK>(p, UPB, pre);
+    dma_s = pre_sp + tip * TT::kStateBytes;
+    dma_r = pre_rp + tip * TT::kRopeBytes;
+    // advance the prefetch cursor
     ++issued;
+    if (++pre.j == pre.tiles_b) {
+      pre.j = 0;
+      pre_page_valid = false;
+      if (++pre.ub == UPB) {
+        pre.ub = 0;
+        do {
+          ++pre.b;
+          pre.L = pre.b < p.B ? uniform(load_i32_sync(p.seq_lens + pre.b)) : 0;
+          pre.tiles_b = tiles_of<TOK>(pre.L);
+        } while (pre.b < p.B && pre.tiles_b == 0);
+      }
+      pre_g = pre.ub / MB;
+    }
   };
   // i-th of this wave's LPW loads of the prepared tile
   auto dma_load = [&](auto ic) {
     constexpr int i = decltype(ic)::value;
     if (p.debug_flags & 1) return;
-    if constexpr (i < TT::kStateLoads / NWAVES) {
-      const int inst = i * NWAVES + wave;  // 1 KiB slice index within the state tile
-      const unsigned voff = s_lane_part ^ ((unsigned)swz16(inst * RPL) << 4);
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_sbase + i * NWAVES * 1024 + voff),
-                                       (lds_void_t*)(dma_stage + i * NWAVES * 1024), 16, 0, 0);
+    if constexpr (i < SLW) {
+      const unsigned voff = s_lane_w ^ ((unsigned)swz16(i * RPL) << 4);
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_s + (i / 4) * 4096 + voff),
+                                       (lds_void_t*)(dma_l + (i / 4) * 4096), 16, (i % 4) * 1024, 0);
     } else {
-      constexpr int ir = i - TT::kStateLoads / NWAVES;
-      const int rinst = ir * NWAVES + wave;
-      const unsigned voff = r_lane_part ^ ((unsigned)(rinst & 1) << 6);
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_rbase + ir * NWAVES * 1024 + voff),
-                                       (lds_void_t*)(dma_stage + TT::kStateBytes + ir * NWAVES * 1024), 16, 0, 0);
+      constexpr int ir = i - SLW;
+      const unsigned voff = r_lane_w ^ ((unsigned)(ir & 1) << 6);
+      __builtin_amdgcn_global_load_lds(
+          (global_cvoid_t*)(dma_r + (ir / 4) * 4096 + voff),
+          (lds_void_t*)(dma_l + (TT::kStateBytes - wave * (SLW * 1024) + wave * (RLW * 1024)) + (ir / 4) * 4096), 16,
+          (ir % 4) * 1024, 0);
     }
   };
 
@@ -418,7 +451,7 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s) {
     if (issued < n_tiles) {
-      dma_prepare();
+      dma_prepare(s);
       static_for<0, LPW>(dma_load);
     }
   }
@@ -448,12 +481,13 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       v_off[d4][a] = (unsigned)((4 * hi + tr_r) * ROWB + (lc << 4) + (tr_q & 1) * 8);
     }
 
-  const float sc2 = p.scale * 1.4426950408889634f;  // scores in base-2 units (scale > 0)
+  float sc2 = p.scale * 1.4426950408889634f;  // scores in base-2 units (scale > 0)
+  pin_arch(sc2);
   u32x4_t ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 x 8
   pin_arch(ones_bits);  // a live register, never re-materialised right in front of an MFMA
 
   // ---- per-unit state
-  u32x4_t qn[NKN];  // raw bf16 bits: integer vectors, so the register pins see plain 128-bit tuples
+  u32x4_t qn[NKN];  // raw bf16 bits of the query fragments (accumulation VGPRs)
   u32x4_t qr[NKR];
   f32x16_t o[NDB];
   f32x16_t o_one;   // every row: sum of the bf16-rounded weights (V block of ones)
@@ -463,7 +497,9 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   int row_b = 0, row_t = 0, row_h = 0;
 
   // ---- building blocks of the tile pipeline ---------------------------------------
-  auto stage_addr = [&](int kk) { return lds_base + (unsigned)((kk % STAGES) * TT::kStageBytes); };
+  auto stage_addr = [&](int kk) { return lds_base + (unsigned)((kk % STAGES) * SB); };
+  // byte step from the stage of tile kk to the stage of tile kk + 1
+  auto stage_step = [&](int kk) { return ((kk + 1) % STAGES == 0) ? -(STAGES - 1) * SB : SB; };
 
   // zero the value rows at or beyond the sequence end in a freshly landed tile:
   // those slots may hold anything (NaN included) and 0-weight x garbage must not leak
@@ -471,50 +507,42 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     const int tok0 = tile_j * TOK;
     if (tok0 + TOK > L) {
       const int valid = L - tok0;
-      unsigned char* sb = smem + (kk % STAGES) * TT::kStageBytes;
+      unsigned char* sb = smem + (kk % STAGES) * SB;
       for (int off = valid * ROWB + tid * 16; off < TT::kStateBytes; off += TT::kThreads * 16)
         *(u32x4_t*)(sb + off) = u32x4_t{0, 0, 0, 0};
     }
   };
 
-  constexpr int RS = 8, PD = 7;    // operand ring: slots / reads in flight
-  constexpr int VRS = 8, VPD = 7;
-
-  // one score MFMA (step i of NS) with its operand ring bookkeeping
+  // score operand ring: RS slots, all RS reads in flight, waited for in groups of 4
+  constexpr int RS = 8;
   u32x4_t kfrag[RS];
-  unsigned ka[8], ra[NKR];
-  auto s_addr = [&](unsigned sa) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) ka[e] = k_off[e] + sa;
-#pragma unroll
-    for (int e = 0; e < NKR; ++e) ra[e] = r_off[e] + sa;
-  };
+  unsigned ka[8], ra[NKR];  // absolute LDS addresses for the stage the next score MFMAs read
   auto s_issue = [&](auto ic) {
     constexpr int i = decltype(ic)::value;
     constexpr int ks = i / NTB, tb = i % NTB;
     if constexpr (ks < NKN) lds_read_b128<tb * 32 * ROWB + ((2 * ks) & ~15) * 16>(kfrag[i % RS], ka[ks & 7]);
     else lds_read_b128<tb * 32 * 128>(kfrag[i % RS], ra[ks - NKN]);
   };
-  auto s_step = [&](auto ic, f32x16_t (&acc)[NTB]) {
+  auto s_wait = [&](auto ic) {  // before step i (i % 4 == 0): fragments i .. i+3 have arrived
+    constexpr int i = decltype(ic)::value;
+    constexpr int issued_r = (i + RS < NS ? i + RS : NS);
+    constexpr int need = (i + 4 < NS ? i + 4 : NS);
+    u32x4_t &f0 = kfrag[i % RS], &f1 = kfrag[(i + 1) % RS], &f2 = kfrag[(i + 2) % RS], &f3 = kfrag[(i + 3) % RS];
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3) : "n"(issued_r - need));
+  };
+  auto s_mfma = [&](auto ic, f32x16_t (&acc)[NTB]) {
     constexpr int i = decltype(ic)::value;
     constexpr int ks = i / NTB, tb = i % NTB;
-    constexpr int left = NS - 1 - i;
-    lds_wait<(left < PD - 1 ? left : PD - 1)>(kfrag[i % RS]);
     if constexpr (ks == 0) mfma_first_v(acc[tb], kfrag[i % RS], qn[0]);
     else if constexpr (ks < NKN) mfma_acc_v(acc[tb], kfrag[i % RS], qn[ks]);
     else mfma_acc_v(acc[tb], kfrag[i % RS], qr[ks - NKN]);
-    if constexpr (i + PD < NS) s_issue(std::integral_constant<int, i + PD>{});
+    if constexpr (i + RS < NS) s_issue(std::integral_constant<int, i + RS>{});
   };
 
-  // value operand ring
+  // value operand ring: VRS fragments of two transposing reads each, waited for in pairs
+  constexpr int VRS = 6;
   u32x2_t vlo[VRS], vhi[VRS];
-  unsigned va[4][2];
-  auto v_addr = [&](unsigned sa) {
-#pragma unroll
-    for (int d4 = 0; d4 < 4; ++d4)
-#pragma unroll
-      for (int a = 0; a < 2; ++a) va[d4][a] = v_off[d4][a] + sa;
-  };
+  unsigned va[4][2];  // absolute LDS addresses for the stage the value MFMAs read
   auto v_issue = [&](auto ic) {
     constexpr int i = decltype(ic)::value;
     constexpr int st = i / NDB, db = i % NDB;
@@ -522,54 +550,61 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     lds_read_tr16_b64<base>(vlo[i % VRS], va[db & 3][0]);
     lds_read_tr16_b64<base + 8 * ROWB>(vhi[i % VRS], va[db & 3][1]);
   };
-  u32x4_t pf[TOK / 16];  // bf16 weights: B operands of the 16-token contraction steps
-  auto v_step = [&](auto ic) {
+  auto v_wait = [&](auto ic) {  // before step i (i even): fragments i, i+1 have arrived
     constexpr int i = decltype(ic)::value;
-    constexpr int st = i / NDB, db = i % NDB;
-    constexpr int left = NP - 1 - i;
-    lds_wait2<2 * (left < VPD - 1 ? left : VPD - 1)>(vlo[i % VRS], vhi[i % VRS]);
-    const u32x4_t a4 = {vlo[i % VRS][0], vlo[i % VRS][1], vhi[i % VRS][0], vhi[i % VRS][1]};
-    mfma_acc_a(o[db], a4, pf[st]);
-    if constexpr (i + VPD < NP) v_issue(std::integral_constant<int, i + VPD>{});
+    constexpr int issued_f = (i + VRS < NP ? i + VRS : NP);
+    constexpr int need = (i + 2 < NP ? i + 2 : NP);
+    u32x2_t &l0 = vlo[i % VRS], &h0 = vhi[i % VRS], &l1 = vlo[(i + 1) % VRS], &h1 = vhi[(i + 1) % VRS];
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(l0), "+v"(h0), "+v"(l1), "+v"(h1) : "n"(2 * (issued_f - need)));
   };
-
-  // softmax of one tile, cut into NE element steps that are interleaved with MFMAs.
-  // Scores are in s_cur (raw dot products); weights go to pf, their exact sum to lsum.
-  f32x16_t s_cur[NTB], s_nxt[NTB];
-  float neg_m = 0.f, lsum = 0.f;
-  float p_prev = 0.f, p_prev2 = 0.f;  // weights of the two preceding elements
-  // element e: x = s * sc2 - m ; p = 2^x ; then, one element later (so that the
-  // transcendental result is never consumed by the next instruction), p is
-  // added to the row sum, and after every odd element a pair is packed to bf16.
-  auto sm_finish = [&](auto ec) {  // consume element e (already exponentiated)
-    constexpr int e = decltype(ec)::value;
-    constexpr int tb = e / 16, i = e % 16;
-    asm_add(lsum, p_prev);
-    if constexpr ((i & 1) == 1) pf[tb * 2 + (i >> 3)][(i & 7) >> 1] = asm_cvt_pk_bf16(p_prev2, p_prev);
-  };
-  auto sm_elem = [&](auto ec) {
-    constexpr int e = decltype(ec)::value;
-    constexpr int tb = e / 16, i = e % 16;
-    const float x = asm_fma(s_cur[tb][i], sc2, neg_m);
-    const float pv = asm_exp2(x);
-    if constexpr (e > 0) sm_finish(std::integral_constant<int, e - 1>{});
-    p_prev2 = p_prev;
-    p_prev = pv;
-    if constexpr (e == NE - 1) {
-      wait_states<1>();
-      sm_finish(std::integral_constant<int, NE - 1>{});
+  u32x4_t pf[TOK / 16];  // bf16 weights: B operands of the 16-token contraction steps
+  auto v_mfma = [&](auto ic) {
+    constexpr int i = decltype(ic)::value;
+    if constexpr (i < NP) {
+      constexpr int st = i / NDB, db = i % NDB;
+      const u32x4_t a4 = {vlo[i % VRS][0], vlo[i % VRS][1], vhi[i % VRS][0], vhi[i % VRS][1]};
+      mfma_acc_a(o[db], a4, pf[st]);
+      if constexpr (i + VRS < NP) v_issue(std::integral_constant<int, i + VRS>{});
+    } else {
+      mfma_acc_a(o_one, ones_bits, pf[i - NP]);
     }
   };
-  // elements [lo, hi) of the tile's NE scores
-  auto sm_range = [&](auto loc, auto hic) {
-    constexpr int lo = decltype(loc)::value, hi_ = decltype(hic)::value;
-    static_for<lo, hi_>(sm_elem);
-  };
 
-  // running-max bookkeeping for the tile in s_cur (tile index j of the unit):
-  // masks invisible keys, and moves the reference when the row max has grown by
-  // more than 2^8 (lazy: weights stay <= 256 otherwise), rescaling O and the sums
-  auto sm_begin = [&](int tile_j) {
+  // softmax of one tile as a three-deep software pipeline over its NE scores:
+  // slot q does  x_q = s_q * sc2 - m ,  p_{q-1} = 2^x_{q-1} ,  sum += p_{q-2}  and,
+  // when q-2 is odd, packs (p_{q-3}, p_{q-2}) to bf16.  No instruction consumes
+  // the result of its predecessor (v_exp_f32 results in particular).
+  float neg_m = 0.f, lsum = 0.f;
+  float sx[NE], sp[NE];
+  auto sm_slot = [&](auto qc, f32x16_t (&sc)[NTB]) {
+    constexpr int q = decltype(qc)::value;
+    if constexpr (q < NE) sx[q] = asm_fma(sc[q / 16][q % 16], sc2, neg_m);
+    if constexpr (q >= 1 && q - 1 < NE) sp[q - 1] = asm_exp2(sx[q - 1]);
+    if constexpr (q >= 2 && q - 2 < NE) {
+      constexpr int e = q - 2;
+      asm_add(lsum, sp[e]);
+      if constexpr ((e & 1) == 1) pf[(e / 16) * 2 + ((e % 16) >> 3)][(e & 7) >> 1] = asm_cvt_pk_bf16(sp[e - 1], sp[e]);
+    }
+  };
+  constexpr int NQ = NE + 2;                       // pipeline slots
+  constexpr int S0 = NS >= 16 ? 4 : (NS >= 8 ? 2 : 1);  // score steps that overlap the row-max search
+
+  // one tile: [A] softmax of tile k (scores in s_rd) under the score MFMAs of
+  // tile k+1 (into s_wr), then [B] value MFMAs of tile k under the loads of tile
+  // k + STAGES - 1.  `k` is the chunk-local tile index, tile_j its index in the unit.
+  auto tile_iter = [&](f32x16_t (&s_rd)[NTB], f32x16_t (&s_wr)[NTB], int k, int tile_j, bool has_next, int seg_L) {
+    // ---- tile k+1 landed?  (also: every wave is done with tile k-1, so its stage is free)
+    if (has_next) {
+      if (issued - 2 - k >= STAGES - 3) wait_vmcnt<LPW * (STAGES - 3)>();
+      else wait_vmcnt<0>();
+    }
+    lds_barrier();
+    if (has_next) zero_tail(k + 1, tile_j + 1, seg_L);
+
+    // ---- [A] first score steps of tile k+1 (stage (k+1) % STAGES; without a next
+    //          tile they read whatever is there and the result is dropped), under
+    //          the masking and row-max search of tile k
+    static_for<0, (RS < NS ? RS : NS)>(s_issue);
     const int tile_tok0 = tile_j * TOK;
     if (tile_tok0 + TOK > n_vis_min) {
       const int lim = n_vis - tile_tok0 - 4 * hi;  // element (tb, i) is visible iff its constant < lim
@@ -577,14 +612,23 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
         for (int i = 0; i < 16; ++i)
-          s_cur[tb][i] = (32 * tb + 8 * (i >> 2) + (i & 3)) < lim ? s_cur[tb][i] : -INFINITY;
+          s_rd[tb][i] = (32 * tb + 8 * (i >> 2) + (i & 3)) < lim ? s_rd[tb][i] : -INFINITY;
     }
     float mx = -INFINITY;
-#pragma unroll
-    for (int tb = 0; tb < NTB; ++tb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s_cur[tb][i]);
+    static_for<0, S0>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      if constexpr (i % 4 == 0) s_wait(ic);
+      constexpr int e0 = (i * NE) / S0, e1 = ((i + 1) * NE) / S0;
+      static_for<e0 / 2, e1 / 2>([&](auto jc) {
+        constexpr int e = 2 * decltype(jc)::value;
+        mx = __builtin_fmaxf(mx, __builtin_fmaxf(s_rd[e / 16][e % 16], s_rd[(e + 1) / 16][(e + 1) % 16]));
+      });
+      s_mfma(ic, s_wr);
+      __builtin_amdgcn_sched_barrier(0);
+    });
     mx = half_swap_max(mx) * sc2;
+    // lazy reference update: keep the old reference while the row max stays
+    // within 2^8 of it (weights then stay <= 256, exact enough in fp32 / bf16)
     const bool bump = mx > m_ref + 8.0f;
     if (__ballot(bump)) {
       wait_states<16>();  // output accumulators are about to be read by the vector ALU
@@ -612,8 +656,49 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     }
     neg_m = m_ref == -INFINITY ? 0.f : -m_ref;
     lsum = 0.f;
+    pin_arch(neg_m);
+    pin_arch(lsum);
+    // ---- [A] remaining score steps of tile k+1 under the exponentials of tile k
+    static_for<S0, NS>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      if constexpr (i % 4 == 0) s_wait(ic);
+      constexpr int q0 = ((i - S0) * NQ) / (NS - S0), q1 = ((i - S0 + 1) * NQ) / (NS - S0);
+      static_for<q0, q1>([&](auto qc) { sm_slot(qc, s_rd); });
+      s_mfma(ic, s_wr);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    l_run += lsum;
+
+    // ---- [B] O^T += V^T . P^T for tile k under the loads of the tile that reuses
+    //          the stage of tile k-1.  Contraction slot (hi, j) of step st is token
+    //          16*st + 8*(j/4) + 4*hi + j%4, matching the score accumulator layout.
+    //          The LDS addresses move on to the next stages in the gaps.
+    static_for<0, (VRS < NP ? VRS : NP)>(v_issue);
+    dma_prepare((k + STAGES - 1) % STAGES);
+    const int ks_step = stage_step(k + 1), vs_step = stage_step(k);
+    wait_states<2>();  // the last weights were packed by the vector ALU just above
+    static_for<0, NB>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      if constexpr (i < NP && i % 2 == 0) v_wait(ic);
+      v_mfma(ic);
+      // loads of the next tile
+      static_for<(i * LPW) / NB, ((i + 1) * LPW) / NB>(dma_load);
+      // score addresses: used again only in the next [A]
+      static_for<(i * (8 + NKR)) / NB, ((i + 1) * (8 + NKR)) / NB>([&](auto ec) {
+        constexpr int e = decltype(ec)::value;
+        if constexpr (e < 8) ka[e] += ks_step;
+        else ra[e - 8] += ks_step;
+      });
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // value addresses: every read of this tile has been issued
+#pragma unroll
+    for (int d4 = 0; d4 < 4; ++d4)
+#pragma unroll
+      for (int a = 0; a < 2; ++a) va[d4][a] += vs_step;
   };
 
+  f32x16_t s_a[NTB], s_b[NTB];
   int k = 0;  // chunk-local index of the tile at `cur`
   while (k < n_tiles) {
     // ================= segment: the tiles of cur's unit that lie in this chunk
@@ -666,60 +751,42 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     else wait_vmcnt<0>();
     lds_barrier();
     zero_tail(k, seg_j0, seg_L);
-    s_addr(stage_addr(k));
-    static_for<0, (PD < NS ? PD : NS)>(s_issue);
-    wait_states<2>();  // query fragments were just moved into place by the vector ALU
-    static_for<0, NS>([&](auto ic) { s_step(ic, s_nxt); });
+    {
+      const unsigned sa = stage_addr(k);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ka[e] = k_off[e] + sa;
+#pragma unroll
+      for (int e = 0; e < NKR; ++e) ra[e] = r_off[e] + sa;
+#pragma unroll
+      for (int d4 = 0; d4 < 4; ++d4)
+#pragma unroll
+        for (int a = 0; a < 2; ++a) va[d4][a] = v_off[d4][a] + sa;
+    }
+    static_for<0, (RS < NS ? RS : NS)>(s_issue);
+    static_for<0, NS>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      if constexpr (i % 4 == 0) s_wait(ic);
+      s_mfma(ic, s_a);
+    });
+    {
+      const int st = stage_step(k);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ka[e] += st;
+#pragma unroll
+      for (int e = 0; e < NKR; ++e) ra[e] += st;
+    }
     wait_states<16>();  // the scores are read by the vector ALU right below
 
-    for (int t = 0; t < seg_n; ++t, ++k) {
-      const bool has_next = t + 1 < seg_n;
-#pragma unroll
-      for (int tb = 0; tb < NTB; ++tb) s_cur[tb] = s_nxt[tb];
-      // ---- tile k+1 landed?  (also: every wave is done with tile k-1, so its stage is free)
-      if (has_next) {
-        if (issued - 2 - k >= STAGES - 3) wait_vmcnt<LPW * (STAGES - 3)>();
-        else wait_vmcnt<0>();
+    // two tiles per trip so that the two score register sets swap roles without copies
+    for (int t = 0; t < seg_n; t += 2) {
+      tile_iter(s_a, s_b, k, seg_j0 + t, t + 1 < seg_n, seg_L);
+      ++k;
+      if (t + 1 < seg_n) {
+        tile_iter(s_b, s_a, k, seg_j0 + t + 1, t + 2 < seg_n, seg_L);
+        ++k;
       }
-      lds_barrier();
-      if (has_next) zero_tail(k + 1, seg_j0 + t + 1, seg_L);
-
-      // ---- [A] softmax of tile k on the vector ALU, interleaved with the score
-      //          MFMAs of tile k+1.  One code path: without a next tile the MFMAs
-      //          re-run on tile k's stage and their result is simply dropped.
-      s_addr(stage_addr(has_next ? k + 1 : k));
-      static_for<0, (PD < NS ? PD : NS)>(s_issue);
-      sm_begin(seg_j0 + t);
-      static_for<0, NS>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        s_step(ic, s_nxt);
-        sm_range(std::integral_constant<int, (i * NE) / NS>{}, std::integral_constant<int, ((i + 1) * NE) / NS>{});
-        __builtin_amdgcn_sched_barrier(0);
-      });
-      l_run += lsum;
-
-      // ---- [B] O^T += V^T . P^T for tile k, interleaved with the loads of the
-      //          tile that will reuse the stage of tile k-1.  Contraction slot
-      //          (hi, j) of step st is token 16*st + 8*(j/4) + 4*hi + j%4,
-      //          matching the score accumulator layout.
-      v_addr(stage_addr(k));
-      static_for<0, (VPD < NP ? VPD : NP)>(v_issue);
-      wait_states<2>();  // the last weights were packed by the vector ALU just above
-      const bool do_dma = issued < n_tiles;
-      if (do_dma) dma_prepare();
-      static_for<0, NP>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        v_step(ic);
-        if constexpr (((i + 1) * LPW) / NP > (i * LPW) / NP) {
-          if (do_dma) dma_load(std::integral_constant<int, (i * LPW) / NP>{});
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      });
-      wait_states<2>();
-#pragma unroll
-      for (int st = 0; st < TOK / 16; ++st) mfma_acc_a(o_one, ones_bits, pf[st]);
-      advance<TOK>(p, UPB, cur);
     }
+    for (int t = 0; t < seg_n; ++t) advance<TOK>(p, UPB, cur);
 
     // ================= end of segment: write the unit's result or its partial
     wait_states<16>();  // output accumulators: last MFMA -> vector ALU reads
@@ -727,7 +794,9 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       const bool unit_done = seg_j0 + seg_n == (seg_L + TOK - 1) / TOK;
       const bool complete = unit_done && seg_j0 == 0;
       const float l_tot = half_swap_sum(l_run);
-      const float r_tot = o_one[0];
+      f32x16_t one_t = o_one;
+      pin_arch(one_t);
+      const float r_tot = one_t[0];
       const float inv = r_tot > 0.f ? 1.0f / r_tot : 0.f;
       const float lse = l_tot > 0.f ? (m_ref + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
       const int lr = wave * 32 + col;
