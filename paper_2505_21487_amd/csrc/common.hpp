@@ -33,7 +33,6 @@ struct DevParams {
   // tuned kernel: flat partition of all key tiles of the batch into chunks
   int32_t num_chunks;       // grid size of the main kernel
   int32_t chunk_tiles;      // > 0: fixed tiles per chunk; 0: ceil(total / num_chunks)
-  int32_t debug_flags;      // experiments only (env GLA_DEBUG): bit 0 = skip the tile loads (results invalid)
 };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t v) {

@@ -124,25 +124,44 @@ __device__ __forceinline__ void wait_states() {
 }
 
 // Vector-ALU pieces of the softmax, issued by hand so that they stay exactly
-// where they are written between the MFMAs they overlap with.  v_exp_f32 is a
-// transcendental: its result must not be read by the very next instruction.
-__device__ __forceinline__ float asm_fma(float a, float b, float c) {
-  float d;
-  asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
-  return d;
+// where they are written between the MFMAs they overlap with.  One statement
+// per pipeline slot: x_q = s_q * sc2 - m ; p_{q-1} = 2^{x_{q-1}} ; sum += p_{q-2} ;
+// on odd q-2 also pack (p_{q-3}, p_{q-2}) to bf16.  Inside a statement no
+// instruction reads the result of the one before it (v_exp_f32 is a
+// transcendental: its result must not be consumed by the next instruction).
+__device__ __forceinline__ void sm_ops_f(float& x, float s, float sc2, float neg_m) {
+  asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(x) : "v"(s), "v"(sc2), "v"(neg_m));
 }
-__device__ __forceinline__ float asm_exp2(float x) {
-  float d;
-  asm volatile("v_exp_f32 %0, %1" : "=v"(d) : "v"(x));
-  return d;
+__device__ __forceinline__ void sm_ops_fe(float& x, float s, float sc2, float neg_m, float& p1, float x1) {
+  asm volatile("v_fma_f32 %0, %2, %3, %4\n\tv_exp_f32 %1, %5"
+               : "=&v"(x), "=v"(p1) : "v"(s), "v"(sc2), "v"(neg_m), "v"(x1));
 }
-__device__ __forceinline__ void asm_add(float& acc, float x) {
-  asm volatile("v_add_f32 %0, %0, %1" : "+v"(acc) : "v"(x));
+__device__ __forceinline__ void sm_ops_fea(float& x, float s, float sc2, float neg_m, float& p1, float x1,
+                                           float& sum, float p2) {
+  asm volatile("v_fma_f32 %0, %3, %4, %5\n\tv_exp_f32 %1, %6\n\tv_add_f32 %2, %2, %7"
+               : "=&v"(x), "=&v"(p1), "+v"(sum) : "v"(s), "v"(sc2), "v"(neg_m), "v"(x1), "v"(p2));
 }
-__device__ __forceinline__ uint32_t asm_cvt_pk_bf16(float lo, float hi) {
-  uint32_t d;
-  asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(d) : "v"(lo), "v"(hi));
-  return d;
+__device__ __forceinline__ void sm_ops_feac(float& x, float s, float sc2, float neg_m, float& p1, float x1,
+                                            float& sum, float p2, uint32_t& pk, float p3) {
+  asm volatile("v_fma_f32 %0, %4, %5, %6\n\tv_exp_f32 %1, %7\n\tv_add_f32 %2, %2, %8\n\tv_cvt_pk_bf16_f32 %3, %9, %8"
+               : "=&v"(x), "=&v"(p1), "+v"(sum), "=&v"(pk)
+               : "v"(s), "v"(sc2), "v"(neg_m), "v"(x1), "v"(p2), "v"(p3));
+}
+__device__ __forceinline__ void sm_ops_ea(float& p1, float x1, float& sum, float p2) {
+  asm volatile("v_exp_f32 %0, %2\n\tv_add_f32 %1, %1, %3" : "=&v"(p1), "+v"(sum) : "v"(x1), "v"(p2));
+}
+__device__ __forceinline__ void sm_ops_eac(float& p1, float x1, float& sum, float p2, uint32_t& pk, float p3) {
+  asm volatile("v_exp_f32 %0, %3\n\tv_add_f32 %1, %1, %4\n\tv_cvt_pk_bf16_f32 %2, %5, %4"
+               : "=&v"(p1), "+v"(sum), "=&v"(pk) : "v"(x1), "v"(p2), "v"(p3));
+}
+__device__ __forceinline__ void sm_ops_a(float& sum, float p2) {
+  asm volatile("s_nop 0\n\tv_add_f32 %0, %0, %1" : "+v"(sum) : "v"(p2));
+}
+__device__ __forceinline__ void sm_ops_ac(float& sum, float p2, uint32_t& pk, float p3) {
+  asm volatile("s_nop 0\n\tv_add_f32 %0, %0, %2\n\tv_cvt_pk_bf16_f32 %1, %3, %2" : "+v"(sum), "=&v"(pk) : "v"(p2), "v"(p3));
+}
+__device__ __forceinline__ void asm_max3(float& m, float a, float b) {
+  asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(m) : "v"(a), "v"(b));
 }
 // 16-byte global load straight into an accumulation VGPR tuple (no staging in
 // architectural VGPRs); complete after the next wait_vmcnt<0>().
@@ -300,19 +319,20 @@ struct TunedTraits {
   static constexpr int kRowBytes = DV * 2;
   static constexpr int kStateBytes = TOK * kRowBytes;
   static constexpr int kRopeBytes = TOK * DR * 2;
-  static constexpr int kStageBytes = kStateBytes + kRopeBytes;
-  static constexpr int kSmemBytes = STAGES * kStageBytes;
+  // LDS layout: the STAGES state tiles first, then the STAGES RoPE tiles, so
+  // that every operand read is "lane register + immediate" for a known stage.
+  static constexpr int kRopeBase = STAGES * kStateBytes;
+  static constexpr int kSmemBytes = STAGES * (kStateBytes + kRopeBytes);
   static constexpr int kStateLoads = kStateBytes / 1024;  // wave-wide 16 B/lane loads
   static constexpr int kRopeLoads = kRopeBytes / 1024;
   static constexpr int kLoadsPerWave = (kStateLoads + kRopeLoads) / NWAVES;
-  static constexpr int kAhead = STAGES >= 2 ? STAGES - 2 : 0;  // tiles in flight past the awaited one
   static constexpr int kThreads = 64 * NWAVES;
   static constexpr int kTilesPerPage = kPage / TOK;
   static constexpr size_t kSlotFloats = (size_t)kRows * DV + kRows;  // partial out + lse
   static_assert(TOK == 32 || TOK == 64, "a tile is a page or half a page");
-  static_assert(STAGES >= 3, "one stage feeds PV, one the next scores, at least one is loading");
+  static_assert(STAGES >= 3 && STAGES % 2 == 0, "PV stage + score stage + loading stages; even for the score register swap");
   static_assert(kStateLoads % NWAVES == 0 && kRopeLoads % NWAVES == 0, "tile loads must split evenly over waves");
-  static_assert(kLoadsPerWave * kAhead <= 63, "vmcnt range");
+  static_assert(kLoadsPerWave * (STAGES - 2) <= 63, "vmcnt range");
   static_assert(DR == 64, "RoPE key tile layout assumes 64 dims");
   static_assert(kRowBytes >= 256 && (kRowBytes & (kRowBytes - 1)) == 0 && kRowBytes <= 1024, "state row bytes");
   static_assert(kSmemBytes <= 160 * 1024, "LDS capacity");
@@ -322,7 +342,8 @@ template <int DV, int DN, int DR, int NWAVES, int TOK, int STAGES>
 __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   using TT = TunedTraits<DV, DN, DR, NWAVES, TOK, STAGES>;
   constexpr int ROWB = TT::kRowBytes;
-  constexpr int SB = TT::kStageBytes;
+  constexpr int STB = TT::kStateBytes;   // state tile bytes
+  constexpr int RTB = TT::kRopeBytes;    // RoPE tile bytes
   constexpr int NTB = TOK / 32;          // 32-token blocks per tile
   constexpr int NKN = DN / 16;           // contraction steps over the state dims
   constexpr int NKR = DR / 16;           // ... over the RoPE dims
@@ -334,7 +355,7 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   constexpr int LPW = TT::kLoadsPerWave;
   constexpr int SLW = TT::kStateLoads / NWAVES;  // 1 KiB state blocks per wave and tile
   constexpr int RLW = TT::kRopeLoads / NWAVES;   // 1 KiB RoPE blocks per wave and tile
-  constexpr int TPP = TT::kTilesPerPage;
+  constexpr unsigned TPP = TT::kTilesPerPage;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[TT::kSmemBytes];
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
@@ -377,17 +398,24 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       (unsigned)(s_rl * ROWB + ((s_pc & ~15) << 4) + (((s_pc & 15) ^ swz16(s_rl) ^ swz16(wave * SLW * RPL)) << 4));
   const int r_rl = lane >> 3, r_pc = lane & 7;
   const unsigned r_lane_w = (unsigned)(r_rl * 128 + ((r_pc ^ (r_rl >> 1) ^ (((wave * RLW) & 1) << 2)) << 4));
+  const uint32_t st_page_bytes = (uint32_t)p.st_s[0] * 2u, st_group_bytes = (uint32_t)p.st_s[1] * 2u;
+  const uint32_t rp_page_bytes = (uint32_t)p.rp_s[0] * 2u;
+  const unsigned char* const state_w = (const unsigned char*)p.state + wave * (SLW * 1024);
+  const unsigned char* const rope_w = (const unsigned char*)p.rope + wave * (RLW * 1024);
+  unsigned char* const lds_state_w = smem + wave * (SLW * 1024);
+  unsigned char* const lds_rope_w = smem + TT::kRopeBase + wave * (RLW * 1024);
 
   int pt_b = -1, pt_base = 0;
   int pt_vec = 0;
-  int pre_g = pre.ub / MB;
-  const unsigned char* pre_sp = nullptr;  // state / RoPE page of the prefetch cursor (group folded in)
+  unsigned pre_goff = (unsigned)(pre.ub / MB) * st_group_bytes;  // byte offset of the cursor's group in a page
+  const unsigned char* pre_sp = nullptr;  // state / RoPE page of the prefetch cursor
   const unsigned char* pre_rp = nullptr;
   bool pre_page_valid = false;
   // addresses of the tile being issued (this wave's share)
   const unsigned char* dma_s = nullptr;
   const unsigned char* dma_r = nullptr;
-  unsigned char* dma_l = nullptr;
+  unsigned char* dma_ls = nullptr;
+  unsigned char* dma_lr = nullptr;
   int issued = 0;  // tiles whose loads have been issued
 
   // Prepare the loads of the next tile into `stage`.  Once every tile of the
@@ -395,24 +423,25 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   // then re-read lines that are still in L2 into a stage nobody reads, which
   // keeps the steady-state loop free of branches around the load instructions.
   auto dma_prepare = [&](int stage) {
-    dma_l = smem + stage * SB + wave * (SLW * 1024);
+    dma_ls = lds_state_w + stage * STB;
+    dma_lr = lds_rope_w + stage * RTB;
     if (issued >= n_tiles) return;
-    const int page_idx = pre.j / TPP;
-    const int tip = pre.j - page_idx * TPP;  // tile within the page
+    const unsigned page_idx = (unsigned)pre.j / TPP;
+    const unsigned tip = (unsigned)pre.j % TPP;  // tile within the page
     if (tip == 0 || !pre_page_valid) {
-      if (pre.b != pt_b || page_idx < pt_base || page_idx >= pt_base + 64) {
+      if (pre.b != pt_b || (int)page_idx < pt_base || (int)page_idx >= pt_base + 64) {
         pt_b = pre.b;
-        pt_base = page_idx;
-        const int idx = min(page_idx + lane, p.max_pages - 1);
+        pt_base = (int)page_idx;
+        const int idx = min((int)page_idx + lane, p.max_pages - 1);
         pt_vec = load_i32_sync(p.page_table + (int64_t)pre.b * p.max_pages + idx);
       }
-      const int64_t page = __builtin_amdgcn_readlane(pt_vec, page_idx - pt_base);
-      pre_sp = (const unsigned char*)(p.state + page * p.st_s[0] + (int64_t)pre_g * p.st_s[1]) + wave * (SLW * 1024);
-      pre_rp = (const unsigned char*)(p.rope + page * p.rp_s[0]) + wave * (RLW * 1024);
+      const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pt_vec, (int)page_idx - pt_base);
+      pre_sp = state_w + ((uint64_t)page * st_page_bytes + pre_goff);
+      pre_rp = rope_w + (uint64_t)page * rp_page_bytes;
       pre_page_valid = true;
     }
-    dma_s = pre_sp + tip * TT::kStateBytes;
-    dma_r = pre_rp + tip * TT::kRopeBytes;
+    dma_s = pre_sp + tip * STB;
+    dma_r = pre_rp + tip * RTB;
     // advance the prefetch cursor
     ++issued;
     if (++pre.j == pre.tiles_b) {
@@ -426,25 +455,24 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
           pre.tiles_b = tiles_of<TOK>(pre.L);
         } while (pre.b < p.B && pre.tiles_b == 0);
       }
-      pre_g = pre.ub / MB;
+      pre_goff = (unsigned)(pre.ub / MB) * st_group_bytes;
     }
   };
   // i-th of this wave's LPW loads of the prepared tile
   auto dma_load = [&](auto ic) {
     constexpr int i = decltype(ic)::value;
-    if (p.debug_flags & 1) return;
+#ifndef GLA_EXPERIMENT_NO_TILE_LOADS
     if constexpr (i < SLW) {
       const unsigned voff = s_lane_w ^ ((unsigned)swz16(i * RPL) << 4);
       __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_s + (i / 4) * 4096 + voff),
-                                       (lds_void_t*)(dma_l + (i / 4) * 4096), 16, (i % 4) * 1024, 0);
+                                       (lds_void_t*)(dma_ls + (i / 4) * 4096), 16, (i % 4) * 1024, 0);
     } else {
       constexpr int ir = i - SLW;
       const unsigned voff = r_lane_w ^ ((unsigned)(ir & 1) << 6);
-      __builtin_amdgcn_global_load_lds(
-          (global_cvoid_t*)(dma_r + (ir / 4) * 4096 + voff),
-          (lds_void_t*)(dma_l + (TT::kStateBytes - wave * (SLW * 1024) + wave * (RLW * 1024)) + (ir / 4) * 4096), 16,
-          (ir % 4) * 1024, 0);
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_r + (ir / 4) * 4096 + voff),
+                                       (lds_void_t*)(dma_lr + (ir / 4) * 4096), 16, (ir % 4) * 1024, 0);
     }
+#endif
   };
 
   // ---- prologue: fill STAGES-1 stages
@@ -456,29 +484,29 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     }
   }
 
-  // ---- lane-constant LDS read offsets (relative to the stage base)
+  // ---- lane-constant LDS read addresses (stage 0; other stages are immediates)
   // score operand (K rows, 16 B): token = 32*tb + col, logical chunk = 2*ks + hi
   const int sw_col = swz16(col);
-  unsigned k_off[8];  // index: ks & 7
+  unsigned k_off[8], ka[8];  // index: ks & 7; ka: working copy pointing at a stage
 #pragma unroll
-  for (int e = 0; e < 8; ++e) k_off[e] = (unsigned)(col * ROWB + ((((2 * e) | hi) ^ sw_col) << 4));
-  unsigned r_off[NKR];
+  for (int e = 0; e < 8; ++e) k_off[e] = lds_base + (unsigned)(col * ROWB + ((((2 * e) | hi) ^ sw_col) << 4));
+  unsigned r_off[NKR], ra[NKR];
 #pragma unroll
   for (int e = 0; e < NKR; ++e)
-    r_off[e] = (unsigned)(TT::kStateBytes + col * 128 + ((((2 * e) | hi) ^ swz8(col)) << 4));
+    r_off[e] = lds_base + (unsigned)(TT::kRopeBase + col * 128 + ((((2 * e) | hi) ^ swz8(col)) << 4));
   // value operand (transposing 8 B reads): 16-lane block bk = lane / 16 covers
   // 4 tokens x 16 dims; lane 4r+q of the block addresses token r, dims 4q..4q+3.
   const int i16 = lane & 15;
   const int tr_r = i16 >> 2, tr_q = i16 & 3;
   const int dh = (lane >> 4) & 1;
-  unsigned v_off[4][2];  // [db & 3][a]
+  unsigned v_off[4][2], va[4][2];  // [db & 3][a]
 #pragma unroll
   for (int d4 = 0; d4 < 4; ++d4)
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
       const int key = (tr_r << 2) | (2 * a + hi);           // swz16 of token 8a + 4hi + r
       const int lc = (4 * d4 + 2 * dh + (tr_q >> 1)) ^ key;  // chunk within the 16-chunk run
-      v_off[d4][a] = (unsigned)((4 * hi + tr_r) * ROWB + (lc << 4) + (tr_q & 1) * 8);
+      v_off[d4][a] = lds_base + (unsigned)((4 * hi + tr_r) * ROWB + (lc << 4) + (tr_q & 1) * 8);
     }
 
   float sc2 = p.scale * 1.4426950408889634f;  // scores in base-2 units (scale > 0)
@@ -497,18 +525,18 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   int row_b = 0, row_t = 0, row_h = 0;
 
   // ---- building blocks of the tile pipeline ---------------------------------------
-  auto stage_addr = [&](int kk) { return lds_base + (unsigned)((kk % STAGES) * SB); };
-  // byte step from the stage of tile kk to the stage of tile kk + 1
-  auto stage_step = [&](int kk) { return ((kk + 1) % STAGES == 0) ? -(STAGES - 1) * SB : SB; };
+  // The blocks take a stage parameter SG: SG >= 0 folds a compile-time stage into
+  // the immediate offsets; SG < 0 (what the loop uses) means the stage has been
+  // added to the address registers ka / ra / va by the caller.
 
   // zero the value rows at or beyond the sequence end in a freshly landed tile:
   // those slots may hold anything (NaN included) and 0-weight x garbage must not leak
-  auto zero_tail = [&](int kk, int tile_j, int L) {
+  auto zero_tail = [&](int stage, int tile_j, int L) {
     const int tok0 = tile_j * TOK;
     if (tok0 + TOK > L) {
       const int valid = L - tok0;
-      unsigned char* sb = smem + (kk % STAGES) * SB;
-      for (int off = valid * ROWB + tid * 16; off < TT::kStateBytes; off += TT::kThreads * 16)
+      unsigned char* sb = smem + stage * STB;
+      for (int off = valid * ROWB + tid * 16; off < STB; off += TT::kThreads * 16)
         *(u32x4_t*)(sb + off) = u32x4_t{0, 0, 0, 0};
     }
   };
@@ -516,12 +544,14 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   // score operand ring: RS slots, all RS reads in flight, waited for in groups of 4
   constexpr int RS = 8;
   u32x4_t kfrag[RS];
-  unsigned ka[8], ra[NKR];  // absolute LDS addresses for the stage the next score MFMAs read
-  auto s_issue = [&](auto ic) {
+  auto s_issue = [&](auto sgc, auto ic) {
+    constexpr int SG = decltype(sgc)::value;
     constexpr int i = decltype(ic)::value;
     constexpr int ks = i / NTB, tb = i % NTB;
-    if constexpr (ks < NKN) lds_read_b128<tb * 32 * ROWB + ((2 * ks) & ~15) * 16>(kfrag[i % RS], ka[ks & 7]);
-    else lds_read_b128<tb * 32 * 128>(kfrag[i % RS], ra[ks - NKN]);
+    constexpr int so = SG < 0 ? 0 : SG * STB, ro = SG < 0 ? 0 : SG * RTB;
+    u32x4_t& f = kfrag[i % RS];
+    if constexpr (ks < NKN) lds_read_b128<so + tb * 32 * ROWB + ((2 * ks) & ~15) * 16>(f, ka[ks & 7]);
+    else lds_read_b128<ro + tb * 32 * 128>(f, ra[ks - NKN]);
   };
   auto s_wait = [&](auto ic) {  // before step i (i % 4 == 0): fragments i .. i+3 have arrived
     constexpr int i = decltype(ic)::value;
@@ -530,25 +560,26 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     u32x4_t &f0 = kfrag[i % RS], &f1 = kfrag[(i + 1) % RS], &f2 = kfrag[(i + 2) % RS], &f3 = kfrag[(i + 3) % RS];
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3) : "n"(issued_r - need));
   };
-  auto s_mfma = [&](auto ic, f32x16_t (&acc)[NTB]) {
+  auto s_mfma = [&](auto sgc, auto ic, f32x16_t (&acc)[NTB]) {
     constexpr int i = decltype(ic)::value;
     constexpr int ks = i / NTB, tb = i % NTB;
     if constexpr (ks == 0) mfma_first_v(acc[tb], kfrag[i % RS], qn[0]);
     else if constexpr (ks < NKN) mfma_acc_v(acc[tb], kfrag[i % RS], qn[ks]);
     else mfma_acc_v(acc[tb], kfrag[i % RS], qr[ks - NKN]);
-    if constexpr (i + RS < NS) s_issue(std::integral_constant<int, i + RS>{});
+    if constexpr (i + RS < NS) s_issue(sgc, std::integral_constant<int, i + RS>{});
   };
 
   // value operand ring: VRS fragments of two transposing reads each, waited for in pairs
   constexpr int VRS = 6;
   u32x2_t vlo[VRS], vhi[VRS];
-  unsigned va[4][2];  // absolute LDS addresses for the stage the value MFMAs read
-  auto v_issue = [&](auto ic) {
+  auto v_issue = [&](auto sgc, auto ic) {
+    constexpr int SG = decltype(sgc)::value;
     constexpr int i = decltype(ic)::value;
     constexpr int st = i / NDB, db = i % NDB;
-    constexpr int base = st * 16 * ROWB + (db >> 2) * 256;
-    lds_read_tr16_b64<base>(vlo[i % VRS], va[db & 3][0]);
-    lds_read_tr16_b64<base + 8 * ROWB>(vhi[i % VRS], va[db & 3][1]);
+    constexpr int base = (SG < 0 ? 0 : SG * STB) + st * 16 * ROWB + (db >> 2) * 256;
+    u32x2_t &l = vlo[i % VRS], &h = vhi[i % VRS];
+    lds_read_tr16_b64<base>(l, va[db & 3][0]);
+    lds_read_tr16_b64<base + 8 * ROWB>(h, va[db & 3][1]);
   };
   auto v_wait = [&](auto ic) {  // before step i (i even): fragments i, i+1 have arrived
     constexpr int i = decltype(ic)::value;
@@ -557,54 +588,72 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     u32x2_t &l0 = vlo[i % VRS], &h0 = vhi[i % VRS], &l1 = vlo[(i + 1) % VRS], &h1 = vhi[(i + 1) % VRS];
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(l0), "+v"(h0), "+v"(l1), "+v"(h1) : "n"(2 * (issued_f - need)));
   };
-  u32x4_t pf[TOK / 16];  // bf16 weights: B operands of the 16-token contraction steps
-  auto v_mfma = [&](auto ic) {
+  uint32_t pkw[TOK / 16][4];  // bf16 weight pairs: B operands of the 16-token contraction steps
+  auto v_mfma = [&](auto sgc, auto ic) {
     constexpr int i = decltype(ic)::value;
     if constexpr (i < NP) {
       constexpr int st = i / NDB, db = i % NDB;
       const u32x4_t a4 = {vlo[i % VRS][0], vlo[i % VRS][1], vhi[i % VRS][0], vhi[i % VRS][1]};
-      mfma_acc_a(o[db], a4, pf[st]);
-      if constexpr (i + VRS < NP) v_issue(std::integral_constant<int, i + VRS>{});
+      const u32x4_t b4 = {pkw[st][0], pkw[st][1], pkw[st][2], pkw[st][3]};
+      mfma_acc_a(o[db], a4, b4);
+      if constexpr (i + VRS < NP) v_issue(sgc, std::integral_constant<int, i + VRS>{});
     } else {
-      mfma_acc_a(o_one, ones_bits, pf[i - NP]);
+      const u32x4_t b4 = {pkw[i - NP][0], pkw[i - NP][1], pkw[i - NP][2], pkw[i - NP][3]};
+      mfma_acc_a(o_one, ones_bits, b4);
     }
   };
 
-  // softmax of one tile as a three-deep software pipeline over its NE scores:
-  // slot q does  x_q = s_q * sc2 - m ,  p_{q-1} = 2^x_{q-1} ,  sum += p_{q-2}  and,
-  // when q-2 is odd, packs (p_{q-3}, p_{q-2}) to bf16.  No instruction consumes
-  // the result of its predecessor (v_exp_f32 results in particular).
+  // softmax of one tile: three-deep software pipeline over its NE scores
   float neg_m = 0.f, lsum = 0.f;
-  float sx[NE], sp[NE];
+  float sx[NE + 1], sp[NE + 1];
   auto sm_slot = [&](auto qc, f32x16_t (&sc)[NTB]) {
     constexpr int q = decltype(qc)::value;
-    if constexpr (q < NE) sx[q] = asm_fma(sc[q / 16][q % 16], sc2, neg_m);
-    if constexpr (q >= 1 && q - 1 < NE) sp[q - 1] = asm_exp2(sx[q - 1]);
-    if constexpr (q >= 2 && q - 2 < NE) {
-      constexpr int e = q - 2;
-      asm_add(lsum, sp[e]);
-      if constexpr ((e & 1) == 1) pf[(e / 16) * 2 + ((e % 16) >> 3)][(e & 7) >> 1] = asm_cvt_pk_bf16(sp[e - 1], sp[e]);
+    constexpr int e = q - 2;  // element whose weight is summed (and maybe packed) in this slot
+    constexpr bool pack = e >= 1 && (e & 1) == 1;
+    constexpr int pi = e >= 0 ? (e / 16) * 2 + ((e % 16) >> 3) : 0, pj = e >= 0 ? (e & 7) >> 1 : 0;
+    if constexpr (q == 0) {
+      sm_ops_f(sx[0], sc[0][0], sc2, neg_m);
+    } else if constexpr (q == 1) {
+      sm_ops_fe(sx[1], sc[1 / 16][1 % 16], sc2, neg_m, sp[0], sx[0]);
+    } else if constexpr (q < NE) {
+      if constexpr (pack) sm_ops_feac(sx[q], sc[q / 16][q % 16], sc2, neg_m, sp[q - 1], sx[q - 1], lsum, sp[e], pkw[pi][pj], sp[e - 1]);
+      else sm_ops_fea(sx[q], sc[q / 16][q % 16], sc2, neg_m, sp[q - 1], sx[q - 1], lsum, sp[e]);
+    } else if constexpr (q == NE) {
+      if constexpr (pack) sm_ops_eac(sp[q - 1], sx[q - 1], lsum, sp[e], pkw[pi][pj], sp[e - 1]);
+      else sm_ops_ea(sp[q - 1], sx[q - 1], lsum, sp[e]);
+    } else {
+      if constexpr (pack) sm_ops_ac(lsum, sp[e], pkw[pi][pj], sp[e - 1]);
+      else sm_ops_a(lsum, sp[e]);
     }
   };
-  constexpr int NQ = NE + 2;                       // pipeline slots
+  constexpr int NQ = NE + 2;                            // pipeline slots
   constexpr int S0 = NS >= 16 ? 4 : (NS >= 8 ? 2 : 1);  // score steps that overlap the row-max search
 
-  // one tile: [A] softmax of tile k (scores in s_rd) under the score MFMAs of
+  // One tile: [A] softmax of tile k (scores in s_rd) under the score MFMAs of
   // tile k+1 (into s_wr), then [B] value MFMAs of tile k under the loads of tile
-  // k + STAGES - 1.  `k` is the chunk-local tile index, tile_j its index in the unit.
+  // k + STAGES - 1.  k: chunk-local tile index, tile_j: index in the unit, PSG /
+  // SSG: stage of tile k / of tile k+1 (or -1, see above), pv_stage: stage of tile k.
   auto tile_iter = [&](f32x16_t (&s_rd)[NTB], f32x16_t (&s_wr)[NTB], int k, int tile_j, bool has_next, int seg_L) {
+    constexpr std::integral_constant<int, -1> psgc{}, ssgc{};  // stages live in the address registers
+    const int pv_stage = k % STAGES;
     // ---- tile k+1 landed?  (also: every wave is done with tile k-1, so its stage is free)
     if (has_next) {
       if (issued - 2 - k >= STAGES - 3) wait_vmcnt<LPW * (STAGES - 3)>();
       else wait_vmcnt<0>();
     }
     lds_barrier();
-    if (has_next) zero_tail(k + 1, tile_j + 1, seg_L);
+    if (has_next) zero_tail((pv_stage + 1) % STAGES, tile_j + 1, seg_L);
 
-    // ---- [A] first score steps of tile k+1 (stage (k+1) % STAGES; without a next
-    //          tile they read whatever is there and the result is dropped), under
-    //          the masking and row-max search of tile k
-    static_for<0, (RS < NS ? RS : NS)>(s_issue);
+#ifdef GLA_EXPERIMENT_NO_COMPUTE
+    dma_prepare((pv_stage + STAGES - 1) % STAGES);
+    static_for<0, LPW>(dma_load);
+    (void)s_rd; (void)s_wr; (void)tile_j;
+    return;
+#endif
+    // ---- [A] first score steps of tile k+1 (without a next tile they read
+    //          whatever is in that stage and the result is dropped), under the
+    //          masking and row-max search of tile k
+    static_for<0, (RS < NS ? RS : NS)>([&](auto ic) { s_issue(ssgc, ic); });
     const int tile_tok0 = tile_j * TOK;
     if (tile_tok0 + TOK > n_vis_min) {
       const int lim = n_vis - tile_tok0 - 4 * hi;  // element (tb, i) is visible iff its constant < lim
@@ -615,15 +664,16 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
           s_rd[tb][i] = (32 * tb + 8 * (i >> 2) + (i & 3)) < lim ? s_rd[tb][i] : -INFINITY;
     }
     float mx = -INFINITY;
+    pin_arch(mx);
     static_for<0, S0>([&](auto ic) {
       constexpr int i = decltype(ic)::value;
       if constexpr (i % 4 == 0) s_wait(ic);
       constexpr int e0 = (i * NE) / S0, e1 = ((i + 1) * NE) / S0;
       static_for<e0 / 2, e1 / 2>([&](auto jc) {
         constexpr int e = 2 * decltype(jc)::value;
-        mx = __builtin_fmaxf(mx, __builtin_fmaxf(s_rd[e / 16][e % 16], s_rd[(e + 1) / 16][(e + 1) % 16]));
+        asm_max3(mx, s_rd[e / 16][e % 16], s_rd[(e + 1) / 16][(e + 1) % 16]);
       });
-      s_mfma(ic, s_wr);
+      s_mfma(ssgc, ic, s_wr);
       __builtin_amdgcn_sched_barrier(0);
     });
     mx = half_swap_max(mx) * sc2;
@@ -664,7 +714,7 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       if constexpr (i % 4 == 0) s_wait(ic);
       constexpr int q0 = ((i - S0) * NQ) / (NS - S0), q1 = ((i - S0 + 1) * NQ) / (NS - S0);
       static_for<q0, q1>([&](auto qc) { sm_slot(qc, s_rd); });
-      s_mfma(ic, s_wr);
+      s_mfma(ssgc, ic, s_wr);
       __builtin_amdgcn_sched_barrier(0);
     });
     l_run += lsum;
@@ -672,22 +722,23 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     // ---- [B] O^T += V^T . P^T for tile k under the loads of the tile that reuses
     //          the stage of tile k-1.  Contraction slot (hi, j) of step st is token
     //          16*st + 8*(j/4) + 4*hi + j%4, matching the score accumulator layout.
-    //          The LDS addresses move on to the next stages in the gaps.
-    static_for<0, (VRS < NP ? VRS : NP)>(v_issue);
-    dma_prepare((k + STAGES - 1) % STAGES);
-    const int ks_step = stage_step(k + 1), vs_step = stage_step(k);
+    //          The address registers move on to the next stages in the gaps.
+    static_for<0, (VRS < NP ? VRS : NP)>([&](auto ic) { v_issue(psgc, ic); });
+    dma_prepare((pv_stage + STAGES - 1) % STAGES);
+    const bool s_wrap = (pv_stage + 2) % STAGES == 0, v_wrap = (pv_stage + 1) % STAGES == 0;
+    const int k_step = s_wrap ? -(STAGES - 1) * STB : STB, r_step = s_wrap ? -(STAGES - 1) * RTB : RTB;
+    const int v_step = v_wrap ? -(STAGES - 1) * STB : STB;
     wait_states<2>();  // the last weights were packed by the vector ALU just above
     static_for<0, NB>([&](auto ic) {
       constexpr int i = decltype(ic)::value;
       if constexpr (i < NP && i % 2 == 0) v_wait(ic);
-      v_mfma(ic);
-      // loads of the next tile
-      static_for<(i * LPW) / NB, ((i + 1) * LPW) / NB>(dma_load);
-      // score addresses: used again only in the next [A]
+      v_mfma(psgc, ic);
+      static_for<(i * LPW) / NB, ((i + 1) * LPW) / NB>(dma_load);  // loads of the next tile
+      // score addresses: next used in the next tile's [A]
       static_for<(i * (8 + NKR)) / NB, ((i + 1) * (8 + NKR)) / NB>([&](auto ec) {
         constexpr int e = decltype(ec)::value;
-        if constexpr (e < 8) ka[e] += ks_step;
-        else ra[e - 8] += ks_step;
+        if constexpr (e < 8) ka[e] += k_step;
+        else ra[e - 8] += r_step;
       });
       __builtin_amdgcn_sched_barrier(0);
     });
@@ -695,10 +746,10 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
 #pragma unroll
     for (int d4 = 0; d4 < 4; ++d4)
 #pragma unroll
-      for (int a = 0; a < 2; ++a) va[d4][a] += vs_step;
+      for (int a = 0; a < 2; ++a) va[d4][a] += v_step;
   };
-
-  f32x16_t s_a[NTB], s_b[NTB];
+  // the two score register sets: tile t of a segment reads the one tile t-1 wrote
+  f32x16_t s_even[NTB], s_odd[NTB];
   int k = 0;  // chunk-local index of the tile at `cur`
   while (k < n_tiles) {
     // ================= segment: the tiles of cur's unit that lie in this chunk
@@ -746,47 +797,46 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       n_vis_min = uniform(mn);
     }
 
-    // ---- segment prologue: scores of its first tile
+    // ---- segment prologue: point the address registers at the stages of tile k
+    //      (value reads) and, after its scores are done, of tile k+1 (score reads)
     if (issued - 1 - k >= STAGES - 2) wait_vmcnt<LPW * (STAGES - 2)>();
     else wait_vmcnt<0>();
     lds_barrier();
-    zero_tail(k, seg_j0, seg_L);
+    zero_tail(k % STAGES, seg_j0, seg_L);
     {
-      const unsigned sa = stage_addr(k);
+      const int ss = k % STAGES;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) ka[e] = k_off[e] + sa;
+      for (int e = 0; e < 8; ++e) ka[e] = k_off[e] + ss * STB;
 #pragma unroll
-      for (int e = 0; e < NKR; ++e) ra[e] = r_off[e] + sa;
+      for (int e = 0; e < NKR; ++e) ra[e] = r_off[e] + ss * RTB;
 #pragma unroll
       for (int d4 = 0; d4 < 4; ++d4)
 #pragma unroll
-        for (int a = 0; a < 2; ++a) va[d4][a] = v_off[d4][a] + sa;
-    }
-    static_for<0, (RS < NS ? RS : NS)>(s_issue);
-    static_for<0, NS>([&](auto ic) {
-      constexpr int i = decltype(ic)::value;
-      if constexpr (i % 4 == 0) s_wait(ic);
-      s_mfma(ic, s_a);
-    });
-    {
-      const int st = stage_step(k);
+        for (int a = 0; a < 2; ++a) va[d4][a] = v_off[d4][a] + ss * STB;
+      constexpr std::integral_constant<int, -1> rt{};
+      static_for<0, (RS < NS ? RS : NS)>([&](auto ic) { s_issue(rt, ic); });
+      static_for<0, NS>([&](auto ic) {
+        if constexpr (decltype(ic)::value % 4 == 0) s_wait(ic);
+        s_mfma(rt, ic, s_even);
+      });
+      const bool wrap = (ss + 1) % STAGES == 0;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) ka[e] += st;
+      for (int e = 0; e < 8; ++e) ka[e] += wrap ? -(STAGES - 1) * STB : STB;
 #pragma unroll
-      for (int e = 0; e < NKR; ++e) ra[e] += st;
+      for (int e = 0; e < NKR; ++e) ra[e] += wrap ? -(STAGES - 1) * RTB : RTB;
     }
     wait_states<16>();  // the scores are read by the vector ALU right below
 
     // two tiles per trip so that the two score register sets swap roles without copies
     for (int t = 0; t < seg_n; t += 2) {
-      tile_iter(s_a, s_b, k, seg_j0 + t, t + 1 < seg_n, seg_L);
+      tile_iter(s_even, s_odd, k, seg_j0 + t, t + 1 < seg_n, seg_L);
       ++k;
       if (t + 1 < seg_n) {
-        tile_iter(s_b, s_a, k, seg_j0 + t + 1, t + 2 < seg_n, seg_L);
+        tile_iter(s_odd, s_even, k, seg_j0 + t + 1, t + 2 < seg_n, seg_L);
         ++k;
       }
     }
-    for (int t = 0; t < seg_n; ++t) advance<TOK>(p, UPB, cur);
+    for (int i = 0; i < seg_n; ++i) advance<TOK>(p, UPB, cur);
 
     // ================= end of segment: write the unit's result or its partial
     wait_states<16>();  // output accumulators: last MFMA -> vector ALU reads
@@ -809,12 +859,12 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       }
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {  // one 16-register block at a time
-        f32x16_t t = o[db];
-        pin_arch(t);
+        f32x16_t t16 = o[db];
+        pin_arch(t16);
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           const int dim = 32 * db + 8 * q4 + 4 * hi;
-          const f32x4_t v = {t[4 * q4] * inv, t[4 * q4 + 1] * inv, t[4 * q4 + 2] * inv, t[4 * q4 + 3] * inv};
+          const f32x4_t v = {t16[4 * q4] * inv, t16[4 * q4 + 1] * inv, t16[4 * q4 + 2] * inv, t16[4 * q4 + 3] * inv};
           if (!complete) {
             *(f32x4_t*)(slot + (size_t)lr * DV + dim) = v;
           } else if (row_valid) {
@@ -948,6 +998,10 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
   // layout the kernels assume: token rows contiguous, everything 16-byte aligned
   if (p->state_stride[2] != p->d_v || p->rope_stride[1] != p->d_rope) return false;
   if (p->state_stride[0] % 8 || p->state_stride[1] % 8 || p->rope_stride[0] % 8) return false;
+  if (p->state_stride[0] < 0 || p->state_stride[1] < 0 || p->rope_stride[0] < 0 ||
+      p->state_stride[0] >= (1ll << 30) || p->state_stride[1] >= (1ll << 30) || p->rope_stride[0] >= (1ll << 30))
+    return false;  // page / group strides are handled as 32-bit byte counts
+  if (p->num_pages >= (1ll << 31)) return false;
   for (int i = 0; i < 3; ++i)
     if (p->q_nope_stride[i] % 8 || p->q_rope_stride[i] % 8 || p->out_stride[i] % 4) return false;
   if (p->q_nope && !(aligned16(p->q_nope) && aligned16(p->q_rope) && aligned16(p->state_cache) &&
@@ -961,7 +1015,6 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
   plan->rows = 32 * nwaves;
   plan->mb = (rows_group + plan->rows - 1) / plan->rows;
   int tok = 32, stages = 4, per_cu = nwaves == 4 ? 1 : 2;
-  if (nwaves == 4) stages = 8;
   tuning_override(&tok, &stages, &per_cu);
   plan->tok = tok;
   plan->stages = stages;
@@ -1010,16 +1063,11 @@ inline int launch_tuned_shape(const TunedPlan& plan, DevParams& d, int units, hi
                               hipEvent_t* ev) {
   const int key = plan.nwaves * 10000 + plan.tok * 100 + plan.stages;
   switch (key) {
-    case 1 * 10000 + 3200 + 3: return launch_tuned_variant<DV, DN, 1, 32, 3>(plan, d, units, st, ev);
     case 1 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 1, 32, 4>(plan, d, units, st, ev);
-    case 2 * 10000 + 3200 + 3: return launch_tuned_variant<DV, DN, 2, 32, 3>(plan, d, units, st, ev);
     case 2 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 2, 32, 4>(plan, d, units, st, ev);
+    case 2 * 10000 + 3200 + 6: return launch_tuned_variant<DV, DN, 2, 32, 6>(plan, d, units, st, ev);
     case 2 * 10000 + 3200 + 8: return launch_tuned_variant<DV, DN, 2, 32, 8>(plan, d, units, st, ev);
-    case 2 * 10000 + 6400 + 4: return launch_tuned_variant<DV, DN, 2, 64, 4>(plan, d, units, st, ev);
     case 4 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 4, 32, 4>(plan, d, units, st, ev);
-    case 4 * 10000 + 3200 + 6: return launch_tuned_variant<DV, DN, 4, 32, 6>(plan, d, units, st, ev);
-    case 4 * 10000 + 3200 + 8: return launch_tuned_variant<DV, DN, 4, 32, 8>(plan, d, units, st, ev);
-    case 4 * 10000 + 6400 + 4: return launch_tuned_variant<DV, DN, 4, 64, 4>(plan, d, units, st, ev);
     default: return GLA_ERR_UNSUPPORTED_SHAPE;
   }
 }
@@ -1031,7 +1079,6 @@ inline int tuned_launch(const gla_decode_params* p, int is_gta, DevParams& d, hi
   d.ws_out = (float*)p->workspace;
   d.num_chunks = plan.num_chunks;
   d.chunk_tiles = plan.chunk_tiles;
-  if (const char* e = std::getenv("GLA_DEBUG")) d.debug_flags = std::atoi(e);
   const int units = p->batch * p->num_groups * plan.mb;
   if (plan.dv == 256 && plan.dn == 256) return launch_tuned_shape<256, 256>(plan, d, units, st, ev);
   if (plan.dv == 128 && plan.dn == 64) return launch_tuned_shape<128, 64>(plan, d, units, st, ev);
