@@ -8,7 +8,7 @@ from .binding import (GLA_ERR_INVALID_ARG, GLA_ERR_LAUNCH, GLA_ERR_UNSUPPORTED_S
                       GLA_IMPL_TUNED, GLA_OK, GlaDecodeParams, GlaError, gla_decode,
                       gla_decode_profile, gla_decode_select_impl, gla_decode_version,
                       gla_decode_workspace_size, gla_status_string, gta_decode, load_library,
-                      make_params, shape_params)
+                      make_params, shape_params, decode_prepared)
 
 __all__ = [n for n in dir() if n.startswith(("gla_", "gta_", "GLA_", "Gla"))] + [
-    "load_library", "make_params", "shape_params"]
+    "load_library", "make_params", "shape_params", "decode_prepared"]

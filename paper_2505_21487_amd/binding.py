@@ -204,6 +204,16 @@ def gta_decode(q_nope, q_rope, state_cache, rope_cache, page_table, seq_lens, so
                    softmax_scale, **kw)
 
 
+def decode_prepared(p: GlaDecodeParams, is_gta: bool = False) -> None:
+    """Enqueue one decode call from an already filled parameter block (see
+    make_params): the per-call path of a serving loop, with no tensor
+    inspection and no allocation on the Python side."""
+    lib = load_library()
+    rc = (lib.gta_decode if is_gta else lib.gla_decode)(ctypes.byref(p))
+    if rc != GLA_OK:
+        raise GlaError(rc)
+
+
 def gla_decode_profile(p: GlaDecodeParams, is_gta: bool, iters: int) -> Tuple[float, float]:
     """Mean (main kernel, combine kernel) durations in microseconds over
     `iters` calls, measured with HIP events on p.stream."""

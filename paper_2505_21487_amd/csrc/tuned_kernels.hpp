@@ -1,10 +1,14 @@
 // Tuned decode-attention path for gfx950: split-KV main kernel on bf16 MFMA
 // with LDS-staged page tiles, plus the merge kernel for its partial results.
 //
-// Work decomposition.  A "unit" is (sequence b, group g, row block mb): the
-// g_q * T query rows of one group (ordered t-major) cut into blocks of
-// ROWS = 32 * NWAVES rows.  A unit owns ceil(L_b / TOK) key tiles of TOK tokens
-// (a page of 64 tokens or half of one).  All tiles of all units, in unit order,
+// Work decomposition.  A workgroup has NG * WPG waves: it serves NG groups
+// (latent heads / tied KV heads) at once with WPG waves of 32 query rows each
+// per group, so that the RoPE-key tile, which all groups share, is fetched once
+// for all of them.  A "unit" is (sequence b, group block gb, row block mb): the
+// g_q * T query rows of each group (ordered t-major) are cut into blocks of
+// 32 * WPG rows, the h_c groups into blocks of NG.  A unit owns ceil(L_b / TOK)
+// key tiles of TOK tokens (a page of 64 tokens or half of one); a tile is the
+// NG state tiles of its groups plus one RoPE tile.  All tiles of all units, in unit order,
 // form one flat list that is cut into equal chunks, one workgroup per chunk, so
 // ragged batches balance by construction and at most two units per chunk are
 // left incomplete.  A unit that lies inside one chunk is written straight to
@@ -313,34 +317,39 @@ __host__ __device__ constexpr int swz16(int t) { return ((t & 3) << 2) | ((t >> 
 // RoPE rows are 128 bytes (8 chunks): two tokens share a 256-byte bank row.
 __host__ __device__ constexpr int swz8(int t) { return (t >> 1) & 7; }
 
-template <int DV, int DN, int DR, int NWAVES, int TOK, int STAGES>
+template <int DV, int DN, int DR, int NG, int WPG, int TOK, int STAGES>
 struct TunedTraits {
-  static constexpr int kRows = 32 * NWAVES;
+  static constexpr int NWAVES = NG * WPG;
+  static constexpr int kRows = 32 * NWAVES;  // query rows of a unit, all groups together
   static constexpr int kRowBytes = DV * 2;
   static constexpr int kStateBytes = TOK * kRowBytes;
   static constexpr int kRopeBytes = TOK * DR * 2;
-  // LDS layout: the STAGES state tiles first, then the STAGES RoPE tiles, so
-  // that every operand read is "lane register + immediate" for a known stage.
-  static constexpr int kRopeBase = STAGES * kStateBytes;
-  static constexpr int kSmemBytes = STAGES * (kStateBytes + kRopeBytes);
-  static constexpr int kStateLoads = kStateBytes / 1024;  // wave-wide 16 B/lane loads
+  // LDS layout: for each of the NG groups its STAGES state tiles, then the
+  // STAGES RoPE tiles, so that stepping to the next stage is one add for every
+  // operand address and each wave's group is a constant folded into its bases.
+  static constexpr int kGroupBytes = STAGES * kStateBytes;
+  static constexpr int kRopeBase = NG * kGroupBytes;
+  static constexpr int kSmemBytes = STAGES * (NG * kStateBytes + kRopeBytes);
+  static constexpr int kStateLoads = kStateBytes / 1024;  // wave-wide 16 B/lane loads per group tile
   static constexpr int kRopeLoads = kRopeBytes / 1024;
-  static constexpr int kLoadsPerWave = (kStateLoads + kRopeLoads) / NWAVES;
+  static constexpr int kLoadsPerWave = kStateLoads / WPG + kRopeLoads / NWAVES;
   static constexpr int kThreads = 64 * NWAVES;
   static constexpr int kTilesPerPage = kPage / TOK;
   static constexpr size_t kSlotFloats = (size_t)kRows * DV + kRows;  // partial out + lse
   static_assert(TOK == 32 || TOK == 64, "a tile is a page or half a page");
   static_assert(STAGES >= 3 && STAGES % 2 == 0, "PV stage + score stage + loading stages; even for the score register swap");
-  static_assert(kStateLoads % NWAVES == 0 && kRopeLoads % NWAVES == 0, "tile loads must split evenly over waves");
+  static_assert(kStateLoads % WPG == 0 && kRopeLoads % NWAVES == 0, "tile loads must split evenly over waves");
+  static_assert(((kStateLoads / WPG) & (kStateLoads / WPG - 1)) == 0, "per-wave state blocks: power of two (swizzle keys combine by XOR)");
   static_assert(kLoadsPerWave * (STAGES - 2) <= 63, "vmcnt range");
   static_assert(DR == 64, "RoPE key tile layout assumes 64 dims");
   static_assert(kRowBytes >= 256 && (kRowBytes & (kRowBytes - 1)) == 0 && kRowBytes <= 1024, "state row bytes");
   static_assert(kSmemBytes <= 160 * 1024, "LDS capacity");
 };
 
-template <int DV, int DN, int DR, int NWAVES, int TOK, int STAGES>
-__global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
-  using TT = TunedTraits<DV, DN, DR, NWAVES, TOK, STAGES>;
+template <int DV, int DN, int DR, int NG, int WPG, int TOK, int STAGES>
+__global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) {
+  using TT = TunedTraits<DV, DN, DR, NG, WPG, TOK, STAGES>;
+  constexpr int NWAVES = NG * WPG;
   constexpr int ROWB = TT::kRowBytes;
   constexpr int STB = TT::kStateBytes;   // state tile bytes
   constexpr int RTB = TT::kRopeBytes;    // RoPE tile bytes
@@ -353,7 +362,7 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   constexpr int NP = (TOK / 16) * NDB;   // value MFMAs per tile
   constexpr int NB = NP + TOK / 16;      // ... plus the row-sum MFMAs
   constexpr int LPW = TT::kLoadsPerWave;
-  constexpr int SLW = TT::kStateLoads / NWAVES;  // 1 KiB state blocks per wave and tile
+  constexpr int SLW = TT::kStateLoads / WPG;     // 1 KiB state blocks per wave and tile
   constexpr int RLW = TT::kRopeLoads / NWAVES;   // 1 KiB RoPE blocks per wave and tile
   constexpr unsigned TPP = TT::kTilesPerPage;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[TT::kSmemBytes];
@@ -362,12 +371,23 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
+  const int gl = wave / WPG;   // this wave's group within the unit's group block
+  const int wg = wave % WPG;   // this wave's 32-row slab within the group's row block
   const int col = lane & 31;  // query row inside the wave's 32-row slab == MFMA column
   const int hi = lane >> 5;   // which half of the contraction slots this lane feeds
 
   const int rows_group = p.g_q * p.T;
-  const int MB = (rows_group + TT::kRows - 1) / TT::kRows;
-  const int UPB = p.h_c * MB;
+  const int MB = (rows_group + 32 * WPG - 1) / (32 * WPG);
+  const int UPB = (p.h_c / NG) * MB;
+#ifdef GLA_EXPERIMENT_TIMESTAMPS
+  // experiment build: wall-clock stamps of workgroup phases, 8 per workgroup,
+  // written 192 MiB into the workspace (the experiment passes a larger one)
+  long long* const stamps = (long long*)((char*)p.ws_out + (192ll << 20)) + (size_t)blockIdx.x * 8;
+#define GLA_STAMP(i) do { if (tid == 0) stamps[i] = (long long)wall_clock64(); } while (0)
+#else
+#define GLA_STAMP(i) do { } while (0)
+#endif
+  GLA_STAMP(0);
 
   // ---- plan: this workgroup's chunk [c0, c1) of the flat tile list
   const int n_total = total_tiles<TOK>(p, UPB, lane);
@@ -381,12 +401,13 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
 
   TileCursor cur = locate_tile<TOK>(p, UPB, c0, lane);  // compute position
   TileCursor pre = cur;                                  // prefetch position
+  GLA_STAMP(1);
 
   // ---- tile loads, global -> LDS, 16 B per lane, 1 KiB per wave instruction.
   // The LDS side is linear in the lane index, so each lane fetches the global
   // chunk whose swizzled home is its LDS slot.  Wave w moves the contiguous
-  // 1 KiB blocks [w*SLW, (w+1)*SLW) of the state tile and [w*RLW, (w+1)*RLW) of
-  // the RoPE tile; block i of a wave sits at  i*1024 + (lane_part ^ key(i) << 4)
+  // 1 KiB blocks [wg*SLW, (wg+1)*SLW) of its own group's state tile and blocks
+  // [w*RLW, (w+1)*RLW) of the RoPE tile; block i of a wave sits at  i*1024 + (lane_part ^ key(i) << 4)
   // past the wave's start, i.e. one XOR per load, and four loads share one
   // pair of base addresses through the instruction's immediate offset (which
   // the hardware adds to the global and to the LDS address alike).  Page ids
@@ -395,19 +416,19 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
   constexpr int CPR = ROWB / 16;    // 16 B chunks per state row
   const int s_rl = lane / CPR, s_pc = lane % CPR;
   const unsigned s_lane_w =
-      (unsigned)(s_rl * ROWB + ((s_pc & ~15) << 4) + (((s_pc & 15) ^ swz16(s_rl) ^ swz16(wave * SLW * RPL)) << 4));
+      (unsigned)(s_rl * ROWB + ((s_pc & ~15) << 4) + (((s_pc & 15) ^ swz16(s_rl) ^ swz16(wg * SLW * RPL)) << 4));
   const int r_rl = lane >> 3, r_pc = lane & 7;
   const unsigned r_lane_w = (unsigned)(r_rl * 128 + ((r_pc ^ (r_rl >> 1) ^ (((wave * RLW) & 1) << 2)) << 4));
   const uint32_t st_page_bytes = (uint32_t)p.st_s[0] * 2u, st_group_bytes = (uint32_t)p.st_s[1] * 2u;
   const uint32_t rp_page_bytes = (uint32_t)p.rp_s[0] * 2u;
-  const unsigned char* const state_w = (const unsigned char*)p.state + wave * (SLW * 1024);
+  const unsigned char* const state_w = (const unsigned char*)p.state + gl * (uint64_t)st_group_bytes + wg * (SLW * 1024);
   const unsigned char* const rope_w = (const unsigned char*)p.rope + wave * (RLW * 1024);
-  unsigned char* const lds_state_w = smem + wave * (SLW * 1024);
+  unsigned char* const lds_state_w = smem + gl * TT::kGroupBytes + wg * (SLW * 1024);
   unsigned char* const lds_rope_w = smem + TT::kRopeBase + wave * (RLW * 1024);
 
   int pt_b = -1, pt_base = 0;
   int pt_vec = 0;
-  unsigned pre_goff = (unsigned)(pre.ub / MB) * st_group_bytes;  // byte offset of the cursor's group in a page
+  uint64_t pre_goff = (uint64_t)(pre.ub / MB) * NG * st_group_bytes;  // byte offset of the cursor's group block in a page
   const unsigned char* pre_sp = nullptr;  // state / RoPE page of the prefetch cursor
   const unsigned char* pre_rp = nullptr;
   bool pre_page_valid = false;
@@ -455,7 +476,7 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
           pre.tiles_b = tiles_of<TOK>(pre.L);
         } while (pre.b < p.B && pre.tiles_b == 0);
       }
-      pre_goff = (unsigned)(pre.ub / MB) * st_group_bytes;
+      pre_goff = (uint64_t)(pre.ub / MB) * NG * st_group_bytes;
     }
   };
   // i-th of this wave's LPW loads of the prepared tile
@@ -484,12 +505,13 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     }
   }
 
+  GLA_STAMP(2);
   // ---- lane-constant LDS read addresses (stage 0; other stages are immediates)
   // score operand (K rows, 16 B): token = 32*tb + col, logical chunk = 2*ks + hi
   const int sw_col = swz16(col);
   unsigned k_off[8], ka[8];  // index: ks & 7; ka: working copy pointing at a stage
 #pragma unroll
-  for (int e = 0; e < 8; ++e) k_off[e] = lds_base + (unsigned)(col * ROWB + ((((2 * e) | hi) ^ sw_col) << 4));
+  for (int e = 0; e < 8; ++e) k_off[e] = lds_base + (unsigned)(gl * TT::kGroupBytes + col * ROWB + ((((2 * e) | hi) ^ sw_col) << 4));
   unsigned r_off[NKR], ra[NKR];
 #pragma unroll
   for (int e = 0; e < NKR; ++e)
@@ -506,7 +528,7 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     for (int a = 0; a < 2; ++a) {
       const int key = (tr_r << 2) | (2 * a + hi);           // swz16 of token 8a + 4hi + r
       const int lc = (4 * d4 + 2 * dh + (tr_q >> 1)) ^ key;  // chunk within the 16-chunk run
-      v_off[d4][a] = lds_base + (unsigned)((4 * hi + tr_r) * ROWB + (lc << 4) + (tr_q & 1) * 8);
+      v_off[d4][a] = lds_base + (unsigned)(gl * TT::kGroupBytes + (4 * hi + tr_r) * ROWB + (lc << 4) + (tr_q & 1) * 8);
     }
 
   float sc2 = p.scale * 1.4426950408889634f;  // scores in base-2 units (scale > 0)
@@ -535,9 +557,12 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     const int tok0 = tile_j * TOK;
     if (tok0 + TOK > L) {
       const int valid = L - tok0;
-      unsigned char* sb = smem + stage * STB;
-      for (int off = valid * ROWB + tid * 16; off < STB; off += TT::kThreads * 16)
-        *(u32x4_t*)(sb + off) = u32x4_t{0, 0, 0, 0};
+#pragma unroll
+      for (int g2 = 0; g2 < NG; ++g2) {
+        unsigned char* sb = smem + g2 * TT::kGroupBytes + stage * STB;
+        for (int off = valid * ROWB + tid * 16; off < STB; off += TT::kThreads * 16)
+          *(u32x4_t*)(sb + off) = u32x4_t{0, 0, 0, 0};
+      }
     }
   };
 
@@ -756,11 +781,14 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
     const int seg_n = min(n_tiles - k, cur.tiles_b - cur.j);
     const int seg_j0 = cur.j;
     const int seg_L = cur.L;
+    const int seg_tiles_b = cur.tiles_b;
+    const int seg_unit = cur.b * UPB + cur.ub;
     {
       // query fragments of this wave's 32 rows: B operand, lane holds 8 dims of row `col`
-      const int g = cur.ub / MB;
-      const int mb = cur.ub - g * MB;
-      const int R = mb * TT::kRows + wave * 32 + col;
+      const int gb = cur.ub / MB;
+      const int mb = cur.ub - gb * MB;
+      const int g = gb * NG + gl;
+      const int R = (mb * WPG + wg) * 32 + col;
       row_valid = R < rows_group;
       const int Rc = row_valid ? R : rows_group - 1;
       row_t = Rc / p.g_q;
@@ -826,10 +854,12 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       for (int e = 0; e < NKR; ++e) ra[e] += wrap ? -(STAGES - 1) * RTB : RTB;
     }
     wait_states<16>();  // the scores are read by the vector ALU right below
+    if (k == 0) GLA_STAMP(3);
 
     // two tiles per trip so that the two score register sets swap roles without copies
     for (int t = 0; t < seg_n; t += 2) {
       tile_iter(s_even, s_odd, k, seg_j0 + t, t + 1 < seg_n, seg_L);
+      if (k == 0) GLA_STAMP(7);
       ++k;
       if (t + 1 < seg_n) {
         tile_iter(s_odd, s_even, k, seg_j0 + t + 1, t + 2 < seg_n, seg_L);
@@ -837,6 +867,7 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       }
     }
     for (int i = 0; i < seg_n; ++i) advance<TOK>(p, UPB, cur);
+    GLA_STAMP(4);
 
     // ================= end of segment: write the unit's result or its partial
     wait_states<16>();  // output accumulators: last MFMA -> vector ALU reads
@@ -848,11 +879,23 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
       pin_arch(one_t);
       const float r_tot = one_t[0];
       const float inv = r_tot > 0.f ? 1.0f / r_tot : 0.f;
+#ifdef GLA_EXPERIMENT_NO_STORES
+      if (inv != 12345.678f) continue;  // experiment build: results are computed and dropped
+#endif
       const float lse = l_tot > 0.f ? (m_ref + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
       const int lr = wave * 32 + col;
       const int64_t ob = row_b * p.out_s[0] + row_t * p.out_s[1] + row_h * p.out_s[2];
       // partial: slot 1 if the unit's first tile is in this chunk, slot 0 if it began earlier
       float* slot = p.ws_out + ((size_t)blockIdx.x * 2 + (seg_j0 == 0 ? 1 : 0)) * TT::kSlotFloats;
+      if (seg_j0 == 0 && tid == 0) {
+        // tell the merge kernel which chunks hold this unit: it starts here and
+        // ends in the chunk of its last tile
+        const int s_u = c0 + (k - seg_n);
+        int2 span;
+        span.x = (int)blockIdx.x;
+        span.y = (s_u + seg_tiles_b - 1) / chunk;
+        ((int2*)p.ws_lse)[seg_unit] = span;
+      }
       if (hi == 0) {
         if (!complete) slot[(size_t)TT::kRows * DV + lr] = lse;
         else if (row_valid) p.lse[((int64_t)row_b * p.T + row_t) * p.h_q + row_h] = lse;
@@ -866,7 +909,8 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
           const int dim = 32 * db + 8 * q4 + 4 * hi;
           const f32x4_t v = {t16[4 * q4] * inv, t16[4 * q4 + 1] * inv, t16[4 * q4 + 2] * inv, t16[4 * q4 + 3] * inv};
           if (!complete) {
-            *(f32x4_t*)(slot + (size_t)lr * DV + dim) = v;
+            // fragment order: one contiguous 1 KiB block per (wave, db, q4), lane-linear
+            *(f32x4_t*)(slot + (size_t)((wave * NDB + db) * 4 + q4) * 256 + lane * 4) = v;
           } else if (row_valid) {
             if (p.out_fp32) {
               *(f32x4_t*)((float*)p.out + ob + dim) = v;
@@ -880,71 +924,87 @@ __global__ __launch_bounds__(64 * NWAVES) void tuned_main_kernel(DevParams p) {
         }
       }
     }
+    GLA_STAMP(5);
   }
+  GLA_STAMP(6);
 }
+#undef GLA_STAMP
 
 // Merge of the partial results of units that span several chunks, and zero fill
 // of units without any key:  lse = ln sum_s exp(lse_s),
-// out = sum_s exp(lse_s - lse) out_s.  Grid (units, ROWS / 4): one wave per row.
-template <int DV, int NWAVES, int TOK>
+// out = sum_s exp(lse_s - lse) out_s.  The main kernel leaves, per unit, the
+// range of chunks that hold it, and stores partial outputs in the register
+// order of its waves (one contiguous 1 KiB block per wave, 32-dim block and
+// quarter), so one wave here owns one (32-row slab, 32-dim block) of a unit and
+// every access of a partial is a full 1 KiB line run.
+// Grid (units, NG * WPG * DV / 32 / 4), 4 waves per workgroup.
+template <int DV, int NG, int WPG, int TOK>
 __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
+  constexpr int NWAVES = NG * WPG;
+  constexpr int NDB = DV / 32;
   constexpr int kRows = 32 * NWAVES;
   constexpr size_t kSlotFloats = (size_t)kRows * DV + kRows;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int col = lane & 31, hi = lane >> 5;
+  const int wv = blockIdx.y * 4 + (tid >> 6);
+  const int w = wv / NDB, db = wv - w * NDB;  // slab (a wave of the main kernel) and 32-dim block
   const int rows_group = p.g_q * p.T;
-  const int MB = (rows_group + kRows - 1) / kRows;
-  const int UPB = p.h_c * MB;
+  const int MB = (rows_group + 32 * WPG - 1) / (32 * WPG);
+  const int UPB = (p.h_c / NG) * MB;
   const int unit = blockIdx.x;
   const int b = unit / UPB;
   const int ub = unit - b * UPB;
-  const int g = ub / MB, mb = ub - g * MB;
-  const int r = blockIdx.y * 4 + wave;  // row within the unit's block
-  const int R = mb * kRows + r;
+  const int gb = ub / MB, mb = ub - gb * MB;
   const int L = p.seq_lens[b];
-  const int tl = tiles_of<TOK>(L);
-
-  int k_first = 0, k_last = -1;
-  if (tl > 0) {
-    const int n_total = total_tiles<TOK>(p, UPB, lane);
-    const int chunk = p.chunk_tiles > 0 ? p.chunk_tiles : (n_total + p.num_chunks - 1) / p.num_chunks;
-    const int s_u = tiles_before<TOK>(p, UPB, b, lane) + ub * tl;
-    k_first = s_u / chunk;
-    k_last = (s_u + tl - 1) / chunk;
-    if (k_first == k_last) return;  // written directly by the main kernel
-  }
+  const int2 span = ((const int2*)p.ws_lse)[unit];  // garbage for units without tiles: not used then
+  const bool empty = tiles_of<TOK>(L) == 0;
+  if (!empty && span.x == span.y) return;  // written directly by the main kernel
+  const int g = gb * NG + w / WPG;
+  const int R = (mb * WPG + w % WPG) * 32 + col;
   if (R >= rows_group) return;
   const int t = R / p.g_q;
   const int h = g * p.g_q + (R - t * p.g_q);
-  // Chunk k_first holds the unit's first tile (partial slot 1); every later
+  const int r = w * 32 + col;  // row within the unit's slot
+  // Chunk span.x holds the unit's first tile (partial slot 1); every later
   // chunk sees a unit that began before it (slot 0).
+  const int k_first = empty ? 0 : span.x, k_last = empty ? -1 : span.y;
+  const float* const slot0 = p.ws_out + (size_t)kRows * DV + r;
   float m = -INFINITY;
+#pragma unroll 4
   for (int k = k_first; k <= k_last; ++k)
-    m = fmaxf(m, p.ws_out[((size_t)k * 2 + (k == k_first)) * kSlotFloats + (size_t)kRows * DV + r]);
+    m = fmaxf(m, slot0[((size_t)k * 2 + (k == k_first)) * kSlotFloats]);
   float z = 0.f;
-  if (m != -INFINITY)
-    for (int k = k_first; k <= k_last; ++k)
-      z += expf(p.ws_out[((size_t)k * 2 + (k == k_first)) * kSlotFloats + (size_t)kRows * DV + r] - m);
+  if (m != -INFINITY) {
+#pragma unroll 4
+    for (int k = k_first; k <= k_last; ++k) z += expf(slot0[((size_t)k * 2 + (k == k_first)) * kSlotFloats] - m);
+  }
   const float lse = m == -INFINITY ? -INFINITY : m + logf(z);
-  if (lane == 0) p.lse[((int64_t)b * p.T + t) * p.h_q + h] = lse;
+  if (db == 0 && hi == 0) p.lse[((int64_t)b * p.T + t) * p.h_q + h] = lse;
+  f32x4_t acc[4];
+#pragma unroll
+  for (int q4 = 0; q4 < 4; ++q4) acc[q4] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  if (m != -INFINITY) {
+    const float* const frag0 = p.ws_out + (size_t)((w * NDB + db) * 4) * 256 + lane * 4;
+#pragma unroll 2
+    for (int k = k_first; k <= k_last; ++k) {
+      const size_t so = ((size_t)k * 2 + (k == k_first)) * kSlotFloats;
+      const float ls = slot0[so];
+      const float wgt = ls == -INFINITY ? 0.f : expf(ls - lse);
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) acc[q4] += wgt * *(const f32x4_t*)(frag0 + so + q4 * 256);
+    }
+  }
   const int64_t ob = b * p.out_s[0] + t * p.out_s[1] + h * p.out_s[2];
-  for (int d = lane * 4; d < DV; d += 256) {
-    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-    if (m != -INFINITY)
-      for (int k = k_first; k <= k_last; ++k) {
-        const float* slot = p.ws_out + ((size_t)k * 2 + (k == k_first)) * kSlotFloats;
-        const float ls = slot[(size_t)kRows * DV + r];
-        if (ls == -INFINITY) continue;
-        const float w = expf(ls - lse);
-        const f32x4_t v = *(const f32x4_t*)(slot + (size_t)r * DV + d);
-        acc += w * v;
-      }
+#pragma unroll
+  for (int q4 = 0; q4 < 4; ++q4) {
+    const int dim = 32 * db + 8 * q4 + 4 * hi;
     if (p.out_fp32) {
-      *(f32x4_t*)((float*)p.out + ob + d) = acc;
+      *(f32x4_t*)((float*)p.out + ob + dim) = acc[q4];
     } else {
       u32x2_t pk;
-      pk[0] = (uint32_t)f32_to_bf16_bits(acc[0]) | ((uint32_t)f32_to_bf16_bits(acc[1]) << 16);
-      pk[1] = (uint32_t)f32_to_bf16_bits(acc[2]) | ((uint32_t)f32_to_bf16_bits(acc[3]) << 16);
-      *(u32x2_t*)((uint16_t*)p.out + ob + d) = pk;
+      pk[0] = (uint32_t)f32_to_bf16_bits(acc[q4][0]) | ((uint32_t)f32_to_bf16_bits(acc[q4][1]) << 16);
+      pk[1] = (uint32_t)f32_to_bf16_bits(acc[q4][2]) | ((uint32_t)f32_to_bf16_bits(acc[q4][3]) << 16);
+      *(u32x2_t*)((uint16_t*)p.out + ob + dim) = pk;
     }
   }
 }
@@ -953,10 +1013,11 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
 
 struct TunedPlan {
   int dv, dn;      // state dims (value / score)
-  int nwaves;      // waves per workgroup
+  int ng, wpg;     // groups per workgroup, waves per group
   int tok, stages; // tile tokens and pipeline depth of the chosen instantiation
-  int rows;        // 32 * nwaves
+  int rows;        // 32 * ng * wpg
   int mb;          // row blocks per (sequence, group)
+  int units;       // batch * (h_c / ng) * mb
   int num_chunks;  // main-kernel grid
   int chunk_tiles; // fixed tiles per chunk, 0: derived on the device
   size_t slot_floats;
@@ -1008,18 +1069,28 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
                      aligned16(p->rope_cache) && aligned16(p->out)))
     return false;
   const int rows_group = (p->num_q_heads / p->num_groups) * p->q_len;
-  const int nwaves = rows_group <= 32 ? 1 : (rows_group <= 64 ? 2 : 4);
+  // waves per group from the rows of a group, then as many groups per workgroup
+  // as four waves allow (they share one RoPE-key tile)
+  const int wpg = rows_group <= 32 ? 1 : (rows_group <= 64 ? 2 : 4);
+  int ng = 4 / wpg;
+  while (ng > 1 && (p->num_groups % ng || 4 * (ng * 32 * p->d_v * 2 + 32 * 128) > 160 * 1024)) ng >>= 1;
   plan->dv = p->d_v;
   plan->dn = p->d_nope;
-  plan->nwaves = nwaves;
-  plan->rows = 32 * nwaves;
-  plan->mb = (rows_group + plan->rows - 1) / plan->rows;
-  int tok = 32, stages = 4, per_cu = nwaves == 4 ? 1 : 2;
+  plan->ng = ng;
+  plan->wpg = wpg;
+  plan->rows = 32 * ng * wpg;
+  plan->mb = (rows_group + 32 * wpg - 1) / (32 * wpg);
+  plan->units = p->batch * (p->num_groups / ng) * plan->mb;
+  int tok = 32, stages = 4, per_cu = 0;
   tuning_override(&tok, &stages, &per_cu);
+  if (per_cu == 0) {  // co-resident workgroups per CU: one wave per SIMD, 160 KiB of LDS
+    const int smem = stages * (ng * tok * p->d_v * 2 + tok * 128);
+    per_cu = std::max(1, std::min((160 * 1024) / smem, 4 / (ng * wpg)));
+  }
   plan->tok = tok;
   plan->stages = stages;
   const int64_t max_tiles = (int64_t)p->max_pages_per_seq * (kPage / tok);
-  const int64_t bound = (int64_t)p->batch * p->num_groups * plan->mb * max_tiles;
+  const int64_t bound = (int64_t)plan->units * max_tiles;
   if (bound > 0x3fffffff) return false;
   if (p->num_splits > 0) {
     plan->chunk_tiles = (int)((max_tiles + p->num_splits - 1) / p->num_splits);
@@ -1037,37 +1108,43 @@ inline bool tuned_supported(const gla_decode_params* p, int is_gta) {
   return tuned_plan(p, is_gta, &plan);
 }
 
+// Workspace: two partial slots per chunk, then per unit the chunk range holding it.
+inline size_t tuned_slots_bytes(const TunedPlan& plan) {
+  return (((size_t)plan.num_chunks * 2 * plan.slot_floats * sizeof(float)) + 255) & ~(size_t)255;
+}
+
 inline size_t tuned_workspace(const gla_decode_params* p, int is_gta) {
   TunedPlan plan;
   if (!tuned_plan(p, is_gta, &plan)) return 0;
-  return (size_t)plan.num_chunks * 2 * plan.slot_floats * sizeof(float);
+  return tuned_slots_bytes(plan) + (size_t)plan.units * 2 * sizeof(int32_t);
 }
 
-template <int DV, int DN, int NWAVES, int TOK, int STAGES>
-inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, int units, hipStream_t st,
-                                hipEvent_t* ev) {
+template <int DV, int DN, int NG, int WPG, int TOK, int STAGES>
+inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
   if (ev) (void)hipEventRecord(ev[0], st);
-  hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NWAVES, TOK, STAGES>), dim3(plan.num_chunks),
-                     dim3(64 * NWAVES), 0, st, d);
+  hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, TOK, STAGES>), dim3(plan.num_chunks),
+                     dim3(64 * NG * WPG), 0, st, d);
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[1], st);
-  hipLaunchKernelGGL((tuned_combine_kernel<DV, NWAVES, TOK>), dim3(units, (32 * NWAVES) / 4), dim3(256),
-                     0, st, d);
+  hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, TOK>), dim3(plan.units, (NG * WPG * (DV / 32) + 3) / 4),
+                     dim3(256), 0, st, d);
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[2], st);
   return GLA_OK;
 }
 
 template <int DV, int DN>
-inline int launch_tuned_shape(const TunedPlan& plan, DevParams& d, int units, hipStream_t st,
-                              hipEvent_t* ev) {
-  const int key = plan.nwaves * 10000 + plan.tok * 100 + plan.stages;
-  switch (key) {
-    case 1 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 1, 32, 4>(plan, d, units, st, ev);
-    case 2 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 2, 32, 4>(plan, d, units, st, ev);
-    case 2 * 10000 + 3200 + 6: return launch_tuned_variant<DV, DN, 2, 32, 6>(plan, d, units, st, ev);
-    case 2 * 10000 + 3200 + 8: return launch_tuned_variant<DV, DN, 2, 32, 8>(plan, d, units, st, ev);
-    case 4 * 10000 + 3200 + 4: return launch_tuned_variant<DV, DN, 4, 32, 4>(plan, d, units, st, ev);
+inline int launch_tuned_shape(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
+  if (plan.tok != 32 || plan.stages != 4) return GLA_ERR_UNSUPPORTED_SHAPE;
+  switch (plan.ng * 10 + plan.wpg) {
+    case 11: return launch_tuned_variant<DV, DN, 1, 1, 32, 4>(plan, d, st, ev);
+    case 12: return launch_tuned_variant<DV, DN, 1, 2, 32, 4>(plan, d, st, ev);
+    case 14: return launch_tuned_variant<DV, DN, 1, 4, 32, 4>(plan, d, st, ev);
+    case 21: return launch_tuned_variant<DV, DN, 2, 1, 32, 4>(plan, d, st, ev);
+    case 22: return launch_tuned_variant<DV, DN, 2, 2, 32, 4>(plan, d, st, ev);
+    case 41:
+      if constexpr (DV <= 128) return launch_tuned_variant<DV, DN, 4, 1, 32, 4>(plan, d, st, ev);
+      else return GLA_ERR_UNSUPPORTED_SHAPE;
     default: return GLA_ERR_UNSUPPORTED_SHAPE;
   }
 }
@@ -1077,11 +1154,11 @@ inline int tuned_launch(const gla_decode_params* p, int is_gta, DevParams& d, hi
   TunedPlan plan;
   if (!tuned_plan(p, is_gta, &plan)) return GLA_ERR_UNSUPPORTED_SHAPE;
   d.ws_out = (float*)p->workspace;
+  d.ws_lse = (float*)((char*)p->workspace + tuned_slots_bytes(plan));  // per-unit chunk ranges (int32 pairs)
   d.num_chunks = plan.num_chunks;
   d.chunk_tiles = plan.chunk_tiles;
-  const int units = p->batch * p->num_groups * plan.mb;
-  if (plan.dv == 256 && plan.dn == 256) return launch_tuned_shape<256, 256>(plan, d, units, st, ev);
-  if (plan.dv == 128 && plan.dn == 64) return launch_tuned_shape<128, 64>(plan, d, units, st, ev);
+  if (plan.dv == 256 && plan.dn == 256) return launch_tuned_shape<256, 256>(plan, d, st, ev);
+  if (plan.dv == 128 && plan.dn == 64) return launch_tuned_shape<128, 64>(plan, d, st, ev);
   return GLA_ERR_UNSUPPORTED_SHAPE;
 }
 
