@@ -241,9 +241,9 @@ struct TileCursor {
 
 // Total number of tiles of the batch (every wave computes the same value).
 template <int TOK>
-__device__ __forceinline__ int total_tiles(const DevParams& p, int UPB, int lane) {
-  int acc = 0;
-  for (int base = 0; base < p.B; base += 64) {
+__device__ __forceinline__ int total_tiles(const DevParams& p, int UPB, int lane, int L_first) {
+  int acc = tiles_of<TOK>(L_first) * UPB;  // L_first: this lane's length among the first 64 (0 beyond B)
+  for (int base = 64; base < p.B; base += 64) {
     const int idx = base + lane;
     acc += idx < p.B ? tiles_of<TOK>(p.seq_lens[idx]) * UPB : 0;
   }
@@ -254,12 +254,12 @@ __device__ __forceinline__ int total_tiles(const DevParams& p, int UPB, int lane
 
 // Locate flat tile index `pos` (< total): which sequence / unit / tile.
 template <int TOK>
-__device__ __forceinline__ TileCursor locate_tile(const DevParams& p, int UPB, int pos, int lane) {
+__device__ __forceinline__ TileCursor locate_tile(const DevParams& p, int UPB, int pos, int lane, int L_first) {
   TileCursor c = {0, 0, 0, 0, 0};
   int before = 0;
   for (int base = 0; base < p.B; base += 64) {
     const int idx = base + lane;
-    const int L = idx < p.B ? p.seq_lens[idx] : 0;
+    const int L = base == 0 ? L_first : (idx < p.B ? p.seq_lens[idx] : 0);
     const int tl = tiles_of<TOK>(L);
     const int w = tl * UPB;
     const int incl = wave_incl_scan(w, lane) + before;
@@ -390,16 +390,26 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
   GLA_STAMP(0);
 
   // ---- plan: this workgroup's chunk [c0, c1) of the flat tile list
-  const int n_total = total_tiles<TOK>(p, UPB, lane);
+  const int L_first = lane < p.B ? p.seq_lens[lane] : 0;  // lengths of the first 64 sequences, reused below
+  const int n_total = total_tiles<TOK>(p, UPB, lane, L_first);
+  if (n_total <= 0) return;
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2):
+  // give every XCD a contiguous run of chunks, so the chunks of one sequence
+  // (same page-table row, same queries) meet in one L2.
+  const int xcd = (int)blockIdx.x & 7, xi = (int)blockIdx.x >> 3;
+  const int xq = (int)gridDim.x >> 3, xr = (int)gridDim.x & 7;
+  const int chunk_id = xcd * xq + min(xcd, xr) + xi;
+  // Chunk i covers tiles [i * chunk, (i + 1) * chunk): a fixed length if the
+  // caller chose a split count, else an equal share of the list.
   const int chunk = p.chunk_tiles > 0 ? p.chunk_tiles
                                       : (n_total + (int)gridDim.x - 1) / (int)gridDim.x;
-  if (chunk <= 0) return;
-  const int c0 = (int)blockIdx.x * chunk;
-  if (c0 >= n_total) return;
-  const int c1 = min(n_total, c0 + chunk);
+  auto chunk_start = [&](int i) -> int { return (int)min((int64_t)n_total, (int64_t)i * chunk); };
+  const int c0 = chunk_start(chunk_id);
+  const int c1 = chunk_start(chunk_id + 1);
+  if (c0 >= c1) return;  // only chunks past the end of the list are empty: no unit spans them
   const int n_tiles = c1 - c0;
 
-  TileCursor cur = locate_tile<TOK>(p, UPB, c0, lane);  // compute position
+  TileCursor cur = locate_tile<TOK>(p, UPB, c0, lane, L_first);  // compute position
   TileCursor pre = cur;                                  // prefetch position
   GLA_STAMP(1);
 
@@ -496,6 +506,35 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
 #endif
   };
 
+  // ---- query fragments of the unit at `cur`: this wave's 32 rows, B operand of
+  //      the score MFMAs, lane holds 8 dims of row `col` per contraction step.
+  //      Requested here, ahead of the first tiles, and again whenever the unit
+  //      changes; complete after the next vmcnt wait that covers them.
+  u32x4_t qn[NKN];  // raw bf16 bits (accumulation VGPRs)
+  u32x4_t qr[NKR];
+  bool row_valid = false;
+  int row_b = 0, row_t = 0, row_h = 0;
+  auto q_issue = [&]() {
+    const int gb = cur.ub / MB;
+    const int mb = cur.ub - gb * MB;
+    const int g = gb * NG + gl;
+    const int R = (mb * WPG + wg) * 32 + col;
+    row_valid = R < rows_group;
+    const int Rc = row_valid ? R : rows_group - 1;
+    row_t = Rc / p.g_q;
+    row_h = g * p.g_q + (Rc - row_t * p.g_q);
+    row_b = cur.b;
+    const uint16_t* qn_ptr = p.q_nope + row_b * p.qn_s[0] + row_t * p.qn_s[1] + row_h * p.qn_s[2] + 8 * hi;
+    const uint16_t* qr_ptr = p.q_rope + row_b * p.qr_s[0] + row_t * p.qr_s[1] + row_h * p.qr_s[2] + 8 * hi;
+    // padding rows re-read the last valid row: their columns are computed and never stored
+#pragma unroll
+    for (int ks = 0; ks < NKN; ++ks) load_b128_async(qn[ks], qn_ptr + 16 * ks);
+#pragma unroll
+    for (int ks = 0; ks < NKR; ++ks) load_b128_async(qr[ks], qr_ptr + 16 * ks);
+  };
+  q_issue();
+  bool q_early = true;
+
   // ---- prologue: fill STAGES-1 stages
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s) {
@@ -537,14 +576,10 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
   pin_arch(ones_bits);  // a live register, never re-materialised right in front of an MFMA
 
   // ---- per-unit state
-  u32x4_t qn[NKN];  // raw bf16 bits of the query fragments (accumulation VGPRs)
-  u32x4_t qr[NKR];
   f32x16_t o[NDB];
   f32x16_t o_one;   // every row: sum of the bf16-rounded weights (V block of ones)
   float m_ref = -INFINITY, l_run = 0.f;
   int n_vis = 0, n_vis_min = 0;
-  bool row_valid = false;
-  int row_b = 0, row_t = 0, row_h = 0;
 
   // ---- building blocks of the tile pipeline ---------------------------------------
   // The blocks take a stage parameter SG: SG >= 0 folds a compile-time stage into
@@ -783,25 +818,13 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
     const int seg_L = cur.L;
     const int seg_tiles_b = cur.tiles_b;
     const int seg_unit = cur.b * UPB + cur.ub;
+    // query fragments (unless already requested ahead of the first tiles); the
+    // wait also covers tile k: loads complete in issue order
+    if (!q_early) q_issue();
+    if (q_early && issued - 1 - k >= STAGES - 2) wait_vmcnt<LPW * (STAGES - 2)>();
+    else wait_vmcnt<0>();
+    q_early = false;
     {
-      // query fragments of this wave's 32 rows: B operand, lane holds 8 dims of row `col`
-      const int gb = cur.ub / MB;
-      const int mb = cur.ub - gb * MB;
-      const int g = gb * NG + gl;
-      const int R = (mb * WPG + wg) * 32 + col;
-      row_valid = R < rows_group;
-      const int Rc = row_valid ? R : rows_group - 1;
-      row_t = Rc / p.g_q;
-      row_h = g * p.g_q + (Rc - row_t * p.g_q);
-      row_b = cur.b;
-      const uint16_t* qn_ptr = p.q_nope + row_b * p.qn_s[0] + row_t * p.qn_s[1] + row_h * p.qn_s[2] + 8 * hi;
-      const uint16_t* qr_ptr = p.q_rope + row_b * p.qr_s[0] + row_t * p.qr_s[1] + row_h * p.qr_s[2] + 8 * hi;
-      // padding rows re-read the last valid row: their columns are computed and never stored
-#pragma unroll
-      for (int ks = 0; ks < NKN; ++ks) load_b128_async(qn[ks], qn_ptr + 16 * ks);
-#pragma unroll
-      for (int ks = 0; ks < NKR; ++ks) load_b128_async(qr[ks], qr_ptr + 16 * ks);
-      wait_vmcnt<0>();
 #pragma unroll
       for (int ks = 0; ks < NKN; ++ks) pin_acc(qn[ks]);
 #pragma unroll
@@ -827,8 +850,6 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
 
     // ---- segment prologue: point the address registers at the stages of tile k
     //      (value reads) and, after its scores are done, of tile k+1 (score reads)
-    if (issued - 1 - k >= STAGES - 2) wait_vmcnt<LPW * (STAGES - 2)>();
-    else wait_vmcnt<0>();
     lds_barrier();
     zero_tail(k % STAGES, seg_j0, seg_L);
     {
@@ -886,13 +907,13 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
       const int lr = wave * 32 + col;
       const int64_t ob = row_b * p.out_s[0] + row_t * p.out_s[1] + row_h * p.out_s[2];
       // partial: slot 1 if the unit's first tile is in this chunk, slot 0 if it began earlier
-      float* slot = p.ws_out + ((size_t)blockIdx.x * 2 + (seg_j0 == 0 ? 1 : 0)) * TT::kSlotFloats;
+      float* slot = p.ws_out + ((size_t)chunk_id * 2 + (seg_j0 == 0 ? 1 : 0)) * TT::kSlotFloats;
       if (seg_j0 == 0 && tid == 0) {
         // tell the merge kernel which chunks hold this unit: it starts here and
         // ends in the chunk of its last tile
         const int s_u = c0 + (k - seg_n);
         int2 span;
-        span.x = (int)blockIdx.x;
+        span.x = chunk_id;
         span.y = (s_u + seg_tiles_b - 1) / chunk;
         ((int2*)p.ws_lse)[seg_unit] = span;
       }
@@ -946,6 +967,10 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
   constexpr size_t kSlotFloats = (size_t)kRows * DV + kRows;
   const int tid = threadIdx.x, lane = tid & 63;
   const int col = lane & 31, hi = lane >> 5;
+#ifdef GLA_EXPERIMENT_TIMESTAMPS
+  if (tid == 0)
+    ((long long*)((char*)p.ws_out + (193ll << 20)))[blockIdx.y * gridDim.x + blockIdx.x] = (long long)wall_clock64();
+#endif
   const int wv = blockIdx.y * 4 + (tid >> 6);
   const int w = wv / NDB, db = wv - w * NDB;  // slab (a wave of the main kernel) and 32-dim block
   const int rows_group = p.g_q * p.T;
@@ -989,9 +1014,15 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
     for (int k = k_first; k <= k_last; ++k) {
       const size_t so = ((size_t)k * 2 + (k == k_first)) * kSlotFloats;
       const float ls = slot0[so];
-      const float wgt = ls == -INFINITY ? 0.f : expf(ls - lse);
+      // a slot marked "no key" may hold anything (an empty chunk never wrote its
+      // data part): its values are dropped, not multiplied by zero
+      const bool live = ls != -INFINITY;
+      const float wgt = live ? expf(ls - lse) : 0.f;
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) acc[q4] += wgt * *(const f32x4_t*)(frag0 + so + q4 * 256);
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4_t v = *(const f32x4_t*)(frag0 + so + q4 * 256);
+        acc[q4] += wgt * (live ? v : f32x4_t{0.f, 0.f, 0.f, 0.f});
+      }
     }
   }
   const int64_t ob = b * p.out_s[0] + t * p.out_s[1] + h * p.out_s[2];
@@ -1038,18 +1069,16 @@ inline int device_cu_count() {
 
 inline bool aligned16(const void* ptr) { return ((uintptr_t)ptr & 15u) == 0; }
 
-// Tuning knob for experiments: GLA_TUNED_CONFIG="tok,stages,wgs_per_cu" overrides
-// the tile size, pipeline depth and grid density chosen below (only values with
-// a compiled instantiation are honoured).
-inline void tuning_override(int* tok, int* stages, int* per_cu) {
-  const char* e = std::getenv("GLA_TUNED_CONFIG");
-  if (!e) return;
-  int a = 0, b = 0, c = 0;
-  if (std::sscanf(e, "%d,%d,%d", &a, &b, &c) >= 2) {
-    if (a == 32 || a == 64) *tok = a;
-    if (b >= 2 && b <= 8) *stages = b;
-    if (c >= 1 && c <= 8) *per_cu = c;
-  }
+// Tile tokens and pipeline depth of the instantiation for a shape: the deepest
+// even ring (at most 8 stages) that fits the LDS and whose loads in flight per
+// wave stay countable by the 6-bit vmcnt.
+constexpr int kTok = 32;
+constexpr int tuned_stages(int dv, int ng, int wpg) {
+  const int stage_bytes = ng * kTok * dv * 2 + kTok * 128;
+  const int loads_per_wave = (kTok * dv * 2 / 1024) / wpg + (kTok * 128 / 1024) / (ng * wpg);
+  int st = 8;
+  while (st > 4 && (st * stage_bytes > 159 * 1024 || loads_per_wave * (st - 2) > 63)) st -= 2;
+  return st;
 }
 
 inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) {
@@ -1081,12 +1110,10 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
   plan->rows = 32 * ng * wpg;
   plan->mb = (rows_group + 32 * wpg - 1) / (32 * wpg);
   plan->units = p->batch * (p->num_groups / ng) * plan->mb;
-  int tok = 32, stages = 4, per_cu = 0;
-  tuning_override(&tok, &stages, &per_cu);
-  if (per_cu == 0) {  // co-resident workgroups per CU: one wave per SIMD, 160 KiB of LDS
-    const int smem = stages * (ng * tok * p->d_v * 2 + tok * 128);
-    per_cu = std::max(1, std::min((160 * 1024) / smem, 4 / (ng * wpg)));
-  }
+  const int tok = kTok, stages = tuned_stages(p->d_v, ng, wpg);
+  // co-resident workgroups per CU: one wave per SIMD, 160 KiB of LDS
+  const int smem = stages * (ng * tok * p->d_v * 2 + tok * 128);
+  const int per_cu = std::max(1, std::min((160 * 1024) / smem, 4 / (ng * wpg)));
   plan->tok = tok;
   plan->stages = stages;
   const int64_t max_tiles = (int64_t)p->max_pages_per_seq * (kPage / tok);
@@ -1135,15 +1162,14 @@ inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, hipStream_t
 
 template <int DV, int DN>
 inline int launch_tuned_shape(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
-  if (plan.tok != 32 || plan.stages != 4) return GLA_ERR_UNSUPPORTED_SHAPE;
   switch (plan.ng * 10 + plan.wpg) {
-    case 11: return launch_tuned_variant<DV, DN, 1, 1, 32, 4>(plan, d, st, ev);
-    case 12: return launch_tuned_variant<DV, DN, 1, 2, 32, 4>(plan, d, st, ev);
-    case 14: return launch_tuned_variant<DV, DN, 1, 4, 32, 4>(plan, d, st, ev);
-    case 21: return launch_tuned_variant<DV, DN, 2, 1, 32, 4>(plan, d, st, ev);
-    case 22: return launch_tuned_variant<DV, DN, 2, 2, 32, 4>(plan, d, st, ev);
+    case 11: return launch_tuned_variant<DV, DN, 1, 1, kTok, tuned_stages(DV, 1, 1)>(plan, d, st, ev);
+    case 12: return launch_tuned_variant<DV, DN, 1, 2, kTok, tuned_stages(DV, 1, 2)>(plan, d, st, ev);
+    case 14: return launch_tuned_variant<DV, DN, 1, 4, kTok, tuned_stages(DV, 1, 4)>(plan, d, st, ev);
+    case 21: return launch_tuned_variant<DV, DN, 2, 1, kTok, tuned_stages(DV, 2, 1)>(plan, d, st, ev);
+    case 22: return launch_tuned_variant<DV, DN, 2, 2, kTok, tuned_stages(DV, 2, 2)>(plan, d, st, ev);
     case 41:
-      if constexpr (DV <= 128) return launch_tuned_variant<DV, DN, 4, 1, 32, 4>(plan, d, st, ev);
+      if constexpr (DV <= 128) return launch_tuned_variant<DV, DN, 4, 1, kTok, tuned_stages(DV, 4, 1)>(plan, d, st, ev);
       else return GLA_ERR_UNSUPPORTED_SHAPE;
     default: return GLA_ERR_UNSUPPORTED_SHAPE;
   }
