@@ -7,6 +7,19 @@ disjoint draws of the workload alternate so that no call re-reads the pages of
 the previous one.  Prints one JSON line.
 
     python bench.py [--steps K] [--warmup W] [--config 1] [--q-len T]
+
+HBM traffic of the main kernel cannot be read from inside the process: it comes
+from two separate counter runs of this same script,
+
+    rocprofv3 --pmc FETCH_SIZE -d <dirF> -o f --output-format csv -- \
+        python3 bench.py --steps 2 --warmup 1 --profile-iters 1 --no-cpu-baseline --calibration-copy
+    rocprofv3 --pmc WRITE_SIZE -d <dirW> -o w --output-format csv -- (same command)
+    python bench.py --summarise-pmc <dirF> <dirW>      # no GPU needed
+
+The last step scales each counter by what it reads for a plain 1 GiB device
+copy made in the same run (--calibration-copy), prints a summary and stores
+bytes per launch in paper_2505_21487_amd/traffic.json, which later plain runs
+report as roofline.traffic for the matching workload.
 """
 from __future__ import annotations
 
@@ -60,17 +73,94 @@ def cpu_baseline(p, budget_s: float = 15.0):
     }
 
 
+CAL_COPY_BYTES = 1 << 30
+TRAFFIC_JSON = os.path.join(ROOT, "paper_2505_21487_amd", "traffic.json")
+
+
+def workload_key(config: int, q_len: int) -> str:
+    return f"configs[{config}] q_len={q_len}"
+
+
+def stored_traffic(config: int, q_len: int):
+    try:
+        with open(TRAFFIC_JSON) as fh:
+            return json.load(fh).get(workload_key(config, q_len), {}).get("bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def _per_dispatch(csv_dir: str, counter: str):
+    """{kernel name: [value per dispatch]} for one counter, summed over the
+    counter's instances (XCDs) within a dispatch; values are KiB."""
+    import collections
+    import csv
+    import glob
+    per = collections.defaultdict(lambda: collections.defaultdict(float))
+    for path in glob.glob(os.path.join(csv_dir, "**", "*counter_collection.csv"), recursive=True):
+        with open(path) as fh:
+            for r in csv.DictReader(fh):
+                if r["Counter_Name"] == counter:
+                    per[r["Kernel_Name"]][r["Dispatch_Id"]] += float(r["Counter_Value"])
+    return {k: list(v.values()) for k, v in per.items()}
+
+
+def summarise_pmc(fetch_dir: str, write_dir: str) -> int:
+    out = {}
+    workload = None
+    for counter, d in (("FETCH_SIZE", fetch_dir), ("WRITE_SIZE", write_dir)):
+        per = _per_dispatch(d, counter)
+        copies = [max(v) for k, v in per.items() if "copyBuffer" in k or "copy_kernel" in k]
+        mains = [v for k, v in per.items() if "tuned_main_kernel" in k]
+        if not copies or not mains:
+            print(f"{counter}: no calibration copy or no main-kernel dispatch found in {d}", file=sys.stderr)
+            return 1
+        cal_kib = max(copies)
+        factor = (CAL_COPY_BYTES / 1024.0) / cal_kib
+        main_kib = sum(mains[0]) / len(mains[0])
+        out[counter] = {"copy_reads_KiB": cal_kib, "copy_expected_KiB": CAL_COPY_BYTES / 1024.0,
+                        "factor": factor, "main_KiB_per_launch": main_kib,
+                        "main_bytes_per_launch_scaled": main_kib * 1024.0 * factor,
+                        "main_launches": len(mains[0])}
+        for path in (os.path.join(d, "workload.txt"),):
+            if os.path.exists(path):
+                workload = open(path).read().strip()
+    total = out["FETCH_SIZE"]["main_bytes_per_launch_scaled"] + out["WRITE_SIZE"]["main_bytes_per_launch_scaled"]
+    print(json.dumps({"workload": workload, "counters": out, "traffic_bytes_per_launch": total}, indent=1))
+    if workload:
+        try:
+            with open(TRAFFIC_JSON) as fh:
+                table = json.load(fh)
+        except (OSError, ValueError):
+            table = {}
+        table[workload] = {"bytes_per_launch": total,
+                           "fetch_bytes": out["FETCH_SIZE"]["main_bytes_per_launch_scaled"],
+                           "write_bytes": out["WRITE_SIZE"]["main_bytes_per_launch_scaled"],
+                           "fetch_factor": out["FETCH_SIZE"]["factor"],
+                           "write_factor": out["WRITE_SIZE"]["factor"]}
+        with open(TRAFFIC_JSON, "w") as fh:
+            json.dump(table, fh, indent=1, sort_keys=True)
+            fh.write("\n")
+    return 0
+
+
 def main() -> int:
+    if len(sys.argv) >= 4 and sys.argv[1] == "--summarise-pmc":
+        return summarise_pmc(sys.argv[2], sys.argv[3])
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=300,
+                    help="untimed calls first; the default outlasts the clock transient of the first ~10 ms of load")
     ap.add_argument("--config", type=int, default=1, help="index into the configuration list")
     ap.add_argument("--q-len", type=int, default=0, help="override query length (1..4)")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--impl", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--profile-iters", type=int, default=50)
+    ap.add_argument("--profile-iters", type=int, default=200)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also make a plain 1 GiB device copy (reference for the HBM counters)")
+    ap.add_argument("--note-workload", default="",
+                    help="directory in which to leave workload.txt (used by --summarise-pmc)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); nothing here uses a second "
@@ -138,7 +228,7 @@ def main() -> int:
         roof = {"bound": "mfma", "achieved": fl / (main_us * 1e-6) / 1e12,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = stored_traffic(args.config, p0.T)
     roof["kernel"] = "main (split-KV attention)"
     roof["kernel_us"] = main_us
     roof["combine_us"] = comb_us
@@ -170,6 +260,16 @@ def main() -> int:
         "flops_per_cache_byte": ai,
         "roofline": roof,
     }
+    if args.calibration_copy:
+        src = torch.empty(CAL_COPY_BYTES // 4, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+    if args.note_workload:
+        os.makedirs(args.note_workload, exist_ok=True)
+        with open(os.path.join(args.note_workload, "workload.txt"), "w") as fh:
+            fh.write(workload_key(args.config, p0.T) + "\n")
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(p0)
     print(json.dumps(rec, ensure_ascii=False), flush=True)
