@@ -92,6 +92,11 @@ __device__ __forceinline__ void lds_read_tr16_b64(u32x2_t& dst, unsigned addr) {
   static_assert(OFF >= 0 && OFF < 65536, "ds offset field");
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
 }
+template <int OFF>
+__device__ __forceinline__ void lds_write_b128(unsigned addr, const u32x4_t& v) {
+  static_assert(OFF >= 0 && OFF < 65536, "ds offset field");
+  asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(addr), "v"(v), "n"(OFF) : "memory");
+}
 template <int N>
 __device__ __forceinline__ void lds_wait(u32x4_t& x) {
   static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
@@ -317,10 +322,10 @@ __host__ __device__ constexpr int swz16(int t) { return ((t & 3) << 2) | ((t >> 
 // RoPE rows are 128 bytes (8 chunks): two tokens share a 256-byte bank row.
 __host__ __device__ constexpr int swz8(int t) { return (t >> 1) & 7; }
 
-template <int DV, int DN, int DR, int NG, int WPG, int TOK, int STAGES>
+template <int DV, int DN, int DR, int NG, int WPG, int KS, int TOK, int STAGES>
 struct TunedTraits {
-  static constexpr int NWAVES = NG * WPG;
-  static constexpr int kRows = 32 * NWAVES;  // query rows of a unit, all groups together
+  static constexpr int NWAVES = NG * WPG * KS;
+  static constexpr int kRows = 32 * NG * WPG;  // query rows of a unit, all groups together
   static constexpr int kRowBytes = DV * 2;
   static constexpr int kStateBytes = TOK * kRowBytes;
   static constexpr int kRopeBytes = TOK * DR * 2;
@@ -329,40 +334,49 @@ struct TunedTraits {
   // operand address and each wave's group is a constant folded into its bases.
   static constexpr int kGroupBytes = STAGES * kStateBytes;
   static constexpr int kRopeBase = NG * kGroupBytes;
-  static constexpr int kSmemBytes = STAGES * (NG * kStateBytes + kRopeBytes);
+  static constexpr int kTileBytes = STAGES * (NG * kStateBytes + kRopeBytes);
+  // KS > 1: one 4 KiB mailbox per wave for the partial scores the KS waves of a row slab exchange
+  static constexpr int kXchgBase = kTileBytes;
+  static constexpr int kSmemBytes = kTileBytes + (KS > 1 ? NWAVES * 4096 : 0);
   static constexpr int kStateLoads = kStateBytes / 1024;  // wave-wide 16 B/lane loads per group tile
   static constexpr int kRopeLoads = kRopeBytes / 1024;
-  static constexpr int kLoadsPerWave = kStateLoads / WPG + kRopeLoads / NWAVES;
+  static constexpr int kLoadsPerWave = kStateLoads / (WPG * KS) + kRopeLoads / NWAVES;
   static constexpr int kThreads = 64 * NWAVES;
   static constexpr int kTilesPerPage = kPage / TOK;
-  static constexpr size_t kSlotFloats = (size_t)kRows * DV + kRows;  // partial out + lse
+  static constexpr size_t kSlotFloats = (size_t)kRows * DV + 32 * NWAVES;  // partial out + one lse per wave row
   static_assert(TOK == 32 || TOK == 64, "a tile is a page or half a page");
   static_assert(STAGES >= 3 && STAGES % 2 == 0, "PV stage + score stage + loading stages; even for the score register swap");
-  static_assert(kStateLoads % WPG == 0 && kRopeLoads % NWAVES == 0, "tile loads must split evenly over waves");
-  static_assert(((kStateLoads / WPG) & (kStateLoads / WPG - 1)) == 0, "per-wave state blocks: power of two (swizzle keys combine by XOR)");
+  static_assert(KS == 1 || (KS == 2 && DN == DV), "row slabs are split over 1 or 2 waves; the split is by state dims");
+  static_assert(kStateLoads % (WPG * KS) == 0 && kRopeLoads % NWAVES == 0, "tile loads must split evenly over waves");
+  static_assert(((kStateLoads / (WPG * KS)) & (kStateLoads / (WPG * KS) - 1)) == 0, "per-wave state blocks: power of two (swizzle keys combine by XOR)");
+  static_assert(KS == 1 || ((DN / KS * 2) % 256 == 0 && (DV / KS * 2) % 256 == 0), "a wave's share of a state row starts on a swizzle-run boundary");
   static_assert(kLoadsPerWave * (STAGES - 2) <= 63, "vmcnt range");
   static_assert(DR == 64, "RoPE key tile layout assumes 64 dims");
   static_assert(kRowBytes >= 256 && (kRowBytes & (kRowBytes - 1)) == 0 && kRowBytes <= 1024, "state row bytes");
   static_assert(kSmemBytes <= 160 * 1024, "LDS capacity");
 };
 
-template <int DV, int DN, int DR, int NG, int WPG, int TOK, int STAGES>
-__global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) {
-  using TT = TunedTraits<DV, DN, DR, NG, WPG, TOK, STAGES>;
-  constexpr int NWAVES = NG * WPG;
+template <int DV, int DN, int DR, int NG, int WPG, int KS, int TOK, int STAGES>
+__global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParams p) {
+  using TT = TunedTraits<DV, DN, DR, NG, WPG, KS, TOK, STAGES>;
+  constexpr int NWAVES = NG * WPG * KS;
   constexpr int ROWB = TT::kRowBytes;
   constexpr int STB = TT::kStateBytes;   // state tile bytes
   constexpr int RTB = TT::kRopeBytes;    // RoPE tile bytes
   constexpr int NTB = TOK / 32;          // 32-token blocks per tile
-  constexpr int NKN = DN / 16;           // contraction steps over the state dims
-  constexpr int NKR = DR / 16;           // ... over the RoPE dims
-  constexpr int NDB = DV / 32;           // 32-dim output blocks
+  // With KS = 2 the two waves of a row slab each take half of the state dims
+  // (for the scores and for the output) and half of the RoPE dims, and add up
+  // their partial scores through LDS; everything below is per wave.
+  constexpr int DVW = DV / KS, DNW = DN / KS, DRW = DR / KS;
+  constexpr int NKN = DNW / 16;          // contraction steps over the state dims
+  constexpr int NKR = DRW / 16;          // ... over the RoPE dims
+  constexpr int NDB = DVW / 32;          // 32-dim output blocks
   constexpr int NE = 16 * NTB;           // scores per lane per tile
   constexpr int NS = (NKN + NKR) * NTB;  // score MFMAs per tile
   constexpr int NP = (TOK / 16) * NDB;   // value MFMAs per tile
   constexpr int NB = NP + TOK / 16;      // ... plus the row-sum MFMAs
   constexpr int LPW = TT::kLoadsPerWave;
-  constexpr int SLW = TT::kStateLoads / WPG;     // 1 KiB state blocks per wave and tile
+  constexpr int SLW = TT::kStateLoads / (WPG * KS);  // 1 KiB state blocks per wave and tile
   constexpr int RLW = TT::kRopeLoads / NWAVES;   // 1 KiB RoPE blocks per wave and tile
   constexpr unsigned TPP = TT::kTilesPerPage;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[TT::kSmemBytes];
@@ -371,8 +385,10 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = uniform(tid >> 6);
-  const int gl = wave / WPG;   // this wave's group within the unit's group block
-  const int wg = wave % WPG;   // this wave's 32-row slab within the group's row block
+  const int gl = wave / (WPG * KS);    // this wave's group within the unit's group block
+  const int wpos = wave % (WPG * KS);  // position among the waves of that group
+  const int wg = wpos / KS;            // this wave's 32-row slab within the group's row block
+  const int kx = wpos % KS;            // which share of the state / RoPE dims this wave works on
   const int col = lane & 31;  // query row inside the wave's 32-row slab == MFMA column
   const int hi = lane >> 5;   // which half of the contraction slots this lane feeds
 
@@ -426,14 +442,14 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
   constexpr int CPR = ROWB / 16;    // 16 B chunks per state row
   const int s_rl = lane / CPR, s_pc = lane % CPR;
   const unsigned s_lane_w =
-      (unsigned)(s_rl * ROWB + ((s_pc & ~15) << 4) + (((s_pc & 15) ^ swz16(s_rl) ^ swz16(wg * SLW * RPL)) << 4));
+      (unsigned)(s_rl * ROWB + ((s_pc & ~15) << 4) + (((s_pc & 15) ^ swz16(s_rl) ^ swz16(wpos * SLW * RPL)) << 4));
   const int r_rl = lane >> 3, r_pc = lane & 7;
   const unsigned r_lane_w = (unsigned)(r_rl * 128 + ((r_pc ^ (r_rl >> 1) ^ (((wave * RLW) & 1) << 2)) << 4));
   const uint32_t st_page_bytes = (uint32_t)p.st_s[0] * 2u, st_group_bytes = (uint32_t)p.st_s[1] * 2u;
   const uint32_t rp_page_bytes = (uint32_t)p.rp_s[0] * 2u;
-  const unsigned char* const state_w = (const unsigned char*)p.state + gl * (uint64_t)st_group_bytes + wg * (SLW * 1024);
+  const unsigned char* const state_w = (const unsigned char*)p.state + gl * (uint64_t)st_group_bytes + wpos * (SLW * 1024);
   const unsigned char* const rope_w = (const unsigned char*)p.rope + wave * (RLW * 1024);
-  unsigned char* const lds_state_w = smem + gl * TT::kGroupBytes + wg * (SLW * 1024);
+  unsigned char* const lds_state_w = smem + gl * TT::kGroupBytes + wpos * (SLW * 1024);
   unsigned char* const lds_rope_w = smem + TT::kRopeBase + wave * (RLW * 1024);
 
   int pt_b = -1, pt_base = 0;
@@ -524,8 +540,8 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
     row_t = Rc / p.g_q;
     row_h = g * p.g_q + (Rc - row_t * p.g_q);
     row_b = cur.b;
-    const uint16_t* qn_ptr = p.q_nope + row_b * p.qn_s[0] + row_t * p.qn_s[1] + row_h * p.qn_s[2] + 8 * hi;
-    const uint16_t* qr_ptr = p.q_rope + row_b * p.qr_s[0] + row_t * p.qr_s[1] + row_h * p.qr_s[2] + 8 * hi;
+    const uint16_t* qn_ptr = p.q_nope + row_b * p.qn_s[0] + row_t * p.qn_s[1] + row_h * p.qn_s[2] + kx * DNW + 8 * hi;
+    const uint16_t* qr_ptr = p.q_rope + row_b * p.qr_s[0] + row_t * p.qr_s[1] + row_h * p.qr_s[2] + kx * DRW + 8 * hi;
     // padding rows re-read the last valid row: their columns are computed and never stored
 #pragma unroll
     for (int ks = 0; ks < NKN; ++ks) load_b128_async(qn[ks], qn_ptr + 16 * ks);
@@ -550,11 +566,12 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
   const int sw_col = swz16(col);
   unsigned k_off[8], ka[8];  // index: ks & 7; ka: working copy pointing at a stage
 #pragma unroll
-  for (int e = 0; e < 8; ++e) k_off[e] = lds_base + (unsigned)(gl * TT::kGroupBytes + col * ROWB + ((((2 * e) | hi) ^ sw_col) << 4));
+  for (int e = 0; e < 8; ++e)
+    k_off[e] = lds_base + (unsigned)(gl * TT::kGroupBytes + col * ROWB + kx * (DNW * 2) + ((((2 * e) | hi) ^ sw_col) << 4));
   unsigned r_off[NKR], ra[NKR];
 #pragma unroll
   for (int e = 0; e < NKR; ++e)
-    r_off[e] = lds_base + (unsigned)(TT::kRopeBase + col * 128 + ((((2 * e) | hi) ^ swz8(col)) << 4));
+    r_off[e] = lds_base + (unsigned)(TT::kRopeBase + col * 128 + (((kx * (DRW / 8) + ((2 * e) | hi)) ^ swz8(col)) << 4));
   // value operand (transposing 8 B reads): 16-lane block bk = lane / 16 covers
   // 4 tokens x 16 dims; lane 4r+q of the block addresses token r, dims 4q..4q+3.
   const int i16 = lane & 15;
@@ -567,7 +584,7 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
     for (int a = 0; a < 2; ++a) {
       const int key = (tr_r << 2) | (2 * a + hi);           // swz16 of token 8a + 4hi + r
       const int lc = (4 * d4 + 2 * dh + (tr_q >> 1)) ^ key;  // chunk within the 16-chunk run
-      v_off[d4][a] = lds_base + (unsigned)(gl * TT::kGroupBytes + (4 * hi + tr_r) * ROWB + (lc << 4) + (tr_q & 1) * 8);
+      v_off[d4][a] = lds_base + (unsigned)(gl * TT::kGroupBytes + (4 * hi + tr_r) * ROWB + kx * (DVW * 2) + (lc << 4) + (tr_q & 1) * 8);
     }
 
   float sc2 = p.scale * 1.4426950408889634f;  // scores in base-2 units (scale > 0)
@@ -689,6 +706,45 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
   constexpr int NQ = NE + 2;                            // pipeline slots
   constexpr int S0 = NS >= 16 ? 4 : (NS >= 8 ? 2 : 1);  // score steps that overlap the row-max search
 
+  // KS = 2: the two waves of a row slab hold partial scores (each over its share
+  // of the contraction dims).  Each posts its 16 values per lane in its own
+  // mailbox; after the next workgroup barrier it adds its partner's to its own
+  // (both get bit-identical sums: a + b == b + a), and a second barrier lets
+  // the mailboxes be overwritten.
+  const unsigned xchg_mine = lds_base + (unsigned)(TT::kXchgBase + wave * 4096 + lane * 16);
+  const unsigned xchg_peer = lds_base + (unsigned)(TT::kXchgBase + (wave ^ 1) * 4096 + lane * 16);
+  auto xchg_post = [&](f32x16_t (&sc)[NTB]) {
+    if constexpr (KS > 1) {
+      static_assert(NTB == 1, "mailbox holds one 32-token block");
+      // MFMA results are read by the LDS stores below.  The wait is tied to the
+      // accumulator so that no copy of it can be scheduled ahead of the wait.
+      asm volatile("s_nop 15" : "+v"(sc[0]));
+      static_for<0, 4>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        // (vector elements go through scalars: a bit cast applied directly to an
+        // element of a vector reads the vector's first element)
+        const float f0 = sc[0][4 * i], f1 = sc[0][4 * i + 1], f2 = sc[0][4 * i + 2], f3 = sc[0][4 * i + 3];
+        const u32x4_t v = {__builtin_bit_cast(uint32_t, f0), __builtin_bit_cast(uint32_t, f1),
+                           __builtin_bit_cast(uint32_t, f2), __builtin_bit_cast(uint32_t, f3)};
+        lds_write_b128<i * 1024>(xchg_mine, v);
+      });
+    }
+  };
+  u32x4_t xin[4];
+  auto xchg_fetch = [&]() {  // issue the reads of the partner's mailbox
+    if constexpr (KS > 1) static_for<0, 4>([&](auto ic) { lds_read_b128<decltype(ic)::value * 1024>(xin[decltype(ic)::value], xchg_peer); });
+  };
+  auto xchg_add = [&](f32x16_t (&sc)[NTB]) {  // call with exactly the RS score-operand reads issued after xchg_fetch
+    if constexpr (KS > 1) {
+      asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(xin[0]), "+v"(xin[1]), "+v"(xin[2]), "+v"(xin[3]) : "n"(RS < NS ? RS : NS));
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const uint32_t u = xin[i >> 2][i & 3];
+        sc[0][i] += __builtin_bit_cast(float, u);
+      }
+      asm volatile("s_barrier" ::: "memory");
+    }
+  };
   // One tile: [A] softmax of tile k (scores in s_rd) under the score MFMAs of
   // tile k+1 (into s_wr), then [B] value MFMAs of tile k under the loads of tile
   // k + STAGES - 1.  k: chunk-local tile index, tile_j: index in the unit, PSG /
@@ -713,7 +769,9 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
     // ---- [A] first score steps of tile k+1 (without a next tile they read
     //          whatever is in that stage and the result is dropped), under the
     //          masking and row-max search of tile k
+    xchg_fetch();
     static_for<0, (RS < NS ? RS : NS)>([&](auto ic) { s_issue(ssgc, ic); });
+    xchg_add(s_rd);
     const int tile_tok0 = tile_j * TOK;
     if (tile_tok0 + TOK > n_vis_min) {
       const int lim = n_vis - tile_tok0 - 4 * hi;  // element (tb, i) is visible iff its constant < lim
@@ -778,6 +836,7 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
       __builtin_amdgcn_sched_barrier(0);
     });
     l_run += lsum;
+    xchg_post(s_wr);
 
     // ---- [B] O^T += V^T . P^T for tile k under the loads of the tile that reuses
     //          the stage of tile k-1.  Contraction slot (hi, j) of step st is token
@@ -875,6 +934,7 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
       for (int e = 0; e < NKR; ++e) ra[e] += wrap ? -(STAGES - 1) * RTB : RTB;
     }
     wait_states<16>();  // the scores are read by the vector ALU right below
+    xchg_post(s_even);
     if (k == 0) GLA_STAMP(3);
 
     // two tiles per trip so that the two score register sets swap roles without copies
@@ -919,7 +979,7 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
       }
       if (hi == 0) {
         if (!complete) slot[(size_t)TT::kRows * DV + lr] = lse;
-        else if (row_valid) p.lse[((int64_t)row_b * p.T + row_t) * p.h_q + row_h] = lse;
+        else if (row_valid && kx == 0) p.lse[((int64_t)row_b * p.T + row_t) * p.h_q + row_h] = lse;
       }
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {  // one 16-register block at a time
@@ -927,7 +987,7 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
         pin_arch(t16);
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          const int dim = 32 * db + 8 * q4 + 4 * hi;
+          const int dim = kx * DVW + 32 * db + 8 * q4 + 4 * hi;
           const f32x4_t v = {t16[4 * q4] * inv, t16[4 * q4 + 1] * inv, t16[4 * q4 + 2] * inv, t16[4 * q4 + 3] * inv};
           if (!complete) {
             // fragment order: one contiguous 1 KiB block per (wave, db, q4), lane-linear
@@ -959,12 +1019,12 @@ __global__ __launch_bounds__(64 * NG * WPG) void tuned_main_kernel(DevParams p) 
 // quarter), so one wave here owns one (32-row slab, 32-dim block) of a unit and
 // every access of a partial is a full 1 KiB line run.
 // Grid (units, NG * WPG * DV / 32 / 4), 4 waves per workgroup.
-template <int DV, int NG, int WPG, int TOK>
+template <int DV, int NG, int WPG, int KS, int TOK>
 __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
-  constexpr int NWAVES = NG * WPG;
-  constexpr int NDB = DV / 32;
-  constexpr int kRows = 32 * NWAVES;
-  constexpr size_t kSlotFloats = (size_t)kRows * DV + kRows;
+  constexpr int NWAVES = NG * WPG * KS;
+  constexpr int NDB = DV / KS / 32;  // 32-dim blocks per wave of the main kernel
+  constexpr int kRows = 32 * NG * WPG;
+  constexpr size_t kSlotFloats = (size_t)kRows * DV + 32 * NWAVES;
   const int tid = threadIdx.x, lane = tid & 63;
   const int col = lane & 31, hi = lane >> 5;
 #ifdef GLA_EXPERIMENT_TIMESTAMPS
@@ -972,7 +1032,8 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
     ((long long*)((char*)p.ws_out + (193ll << 20)))[blockIdx.y * gridDim.x + blockIdx.x] = (long long)wall_clock64();
 #endif
   const int wv = blockIdx.y * 4 + (tid >> 6);
-  const int w = wv / NDB, db = wv - w * NDB;  // slab (a wave of the main kernel) and 32-dim block
+  const int w = wv / NDB, db = wv - w * NDB;  // wave of the main kernel and one of its 32-dim blocks
+  const int wpos = w % (WPG * KS), kx = wpos % KS;
   const int rows_group = p.g_q * p.T;
   const int MB = (rows_group + 32 * WPG - 1) / (32 * WPG);
   const int UPB = (p.h_c / NG) * MB;
@@ -984,8 +1045,8 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
   const int2 span = ((const int2*)p.ws_lse)[unit];  // garbage for units without tiles: not used then
   const bool empty = tiles_of<TOK>(L) == 0;
   if (!empty && span.x == span.y) return;  // written directly by the main kernel
-  const int g = gb * NG + w / WPG;
-  const int R = (mb * WPG + w % WPG) * 32 + col;
+  const int g = gb * NG + w / (WPG * KS);
+  const int R = (mb * WPG + wpos / KS) * 32 + col;
   if (R >= rows_group) return;
   const int t = R / p.g_q;
   const int h = g * p.g_q + (R - t * p.g_q);
@@ -1004,7 +1065,7 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
     for (int k = k_first; k <= k_last; ++k) z += expf(slot0[((size_t)k * 2 + (k == k_first)) * kSlotFloats] - m);
   }
   const float lse = m == -INFINITY ? -INFINITY : m + logf(z);
-  if (db == 0 && hi == 0) p.lse[((int64_t)b * p.T + t) * p.h_q + h] = lse;
+  if (db == 0 && hi == 0 && kx == 0) p.lse[((int64_t)b * p.T + t) * p.h_q + h] = lse;
   f32x4_t acc[4];
 #pragma unroll
   for (int q4 = 0; q4 < 4; ++q4) acc[q4] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -1028,7 +1089,7 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
   const int64_t ob = b * p.out_s[0] + t * p.out_s[1] + h * p.out_s[2];
 #pragma unroll
   for (int q4 = 0; q4 < 4; ++q4) {
-    const int dim = 32 * db + 8 * q4 + 4 * hi;
+    const int dim = kx * (DV / KS) + 32 * db + 8 * q4 + 4 * hi;
     if (p.out_fp32) {
       *(f32x4_t*)((float*)p.out + ob + dim) = acc[q4];
     } else {
@@ -1044,7 +1105,7 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
 
 struct TunedPlan {
   int dv, dn;      // state dims (value / score)
-  int ng, wpg;     // groups per workgroup, waves per group
+  int ng, wpg, ks; // groups per workgroup, row slabs per group, waves per row slab
   int tok, stages; // tile tokens and pipeline depth of the chosen instantiation
   int rows;        // 32 * ng * wpg
   int mb;          // row blocks per (sequence, group)
@@ -1073,18 +1134,19 @@ inline bool aligned16(const void* ptr) { return ((uintptr_t)ptr & 15u) == 0; }
 // even ring (at most 8 stages) that fits the LDS and whose loads in flight per
 // wave stay countable by the 6-bit vmcnt.
 constexpr int kTok = 32;
-constexpr int tuned_stages(int dv, int ng, int wpg) {
+constexpr int tuned_stages(int dv, int ng, int wpg, int ks) {
   const int stage_bytes = ng * kTok * dv * 2 + kTok * 128;
-  const int loads_per_wave = (kTok * dv * 2 / 1024) / wpg + (kTok * 128 / 1024) / (ng * wpg);
+  const int mailboxes = ks > 1 ? ng * wpg * ks * 4096 : 0;
+  const int loads_per_wave = (kTok * dv * 2 / 1024) / (wpg * ks) + (kTok * 128 / 1024) / (ng * wpg * ks);
   int st = 8;
-  while (st > 4 && (st * stage_bytes > 159 * 1024 || loads_per_wave * (st - 2) > 63)) st -= 2;
+  while (st > 4 && (st * stage_bytes + mailboxes > 160 * 1024 || loads_per_wave * (st - 2) > 63)) st -= 2;
   return st;
 }
 
 inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) {
   if (p->page_size != kPage || p->d_rope != 64) return false;
   if (!(p->softmax_scale > 0.f)) return false;  // row maxima are taken on the raw dot products
-  if (!((!is_gta && p->d_v == 256) || (is_gta && p->d_v == 128))) return false;
+  if (!((!is_gta && (p->d_v == 256 || p->d_v == 512)) || (is_gta && p->d_v == 128))) return false;
   // layout the kernels assume: token rows contiguous, everything 16-byte aligned
   if (p->state_stride[2] != p->d_v || p->rope_stride[1] != p->d_rope) return false;
   if (p->state_stride[0] % 8 || p->state_stride[1] % 8 || p->rope_stride[0] % 8) return false;
@@ -1100,20 +1162,24 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
   const int rows_group = (p->num_q_heads / p->num_groups) * p->q_len;
   // waves per group from the rows of a group, then as many groups per workgroup
   // as four waves allow (they share one RoPE-key tile)
-  const int wpg = rows_group <= 32 ? 1 : (rows_group <= 64 ? 2 : 4);
-  int ng = 4 / wpg;
+  // A latent of 512 dims needs two waves per row slab: 32 rows x 512 fp32
+  // output accumulators alone would fill a wave's accumulation registers.
+  const int ks = p->d_v > 256 ? 2 : 1;
+  const int wpg = rows_group <= 32 ? 1 : ((rows_group <= 64 || ks == 2) ? 2 : 4);
+  int ng = 4 / (wpg * ks);
   while (ng > 1 && (p->num_groups % ng || 4 * (ng * 32 * p->d_v * 2 + 32 * 128) > 160 * 1024)) ng >>= 1;
   plan->dv = p->d_v;
   plan->dn = p->d_nope;
   plan->ng = ng;
   plan->wpg = wpg;
+  plan->ks = ks;
   plan->rows = 32 * ng * wpg;
   plan->mb = (rows_group + 32 * wpg - 1) / (32 * wpg);
   plan->units = p->batch * (p->num_groups / ng) * plan->mb;
-  const int tok = kTok, stages = tuned_stages(p->d_v, ng, wpg);
+  const int tok = kTok, stages = tuned_stages(p->d_v, ng, wpg, ks);
   // co-resident workgroups per CU: one wave per SIMD, 160 KiB of LDS
-  const int smem = stages * (ng * tok * p->d_v * 2 + tok * 128);
-  const int per_cu = std::max(1, std::min((160 * 1024) / smem, 4 / (ng * wpg)));
+  const int smem = stages * (ng * tok * p->d_v * 2 + tok * 128) + (ks > 1 ? ng * wpg * ks * 4096 : 0);
+  const int per_cu = std::max(1, std::min((160 * 1024) / smem, 4 / (ng * wpg * ks)));
   plan->tok = tok;
   plan->stages = stages;
   const int64_t max_tiles = (int64_t)p->max_pages_per_seq * (kPage / tok);
@@ -1126,7 +1192,7 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
     plan->chunk_tiles = 0;
     plan->num_chunks = (int)std::max<int64_t>(1, std::min<int64_t>(bound, (int64_t)device_cu_count() * per_cu));
   }
-  plan->slot_floats = (size_t)plan->rows * p->d_v + plan->rows;
+  plan->slot_floats = (size_t)plan->rows * p->d_v + (size_t)32 * ng * wpg * ks;
   return true;
 }
 
@@ -1146,14 +1212,14 @@ inline size_t tuned_workspace(const gla_decode_params* p, int is_gta) {
   return tuned_slots_bytes(plan) + (size_t)plan.units * 2 * sizeof(int32_t);
 }
 
-template <int DV, int DN, int NG, int WPG, int TOK, int STAGES>
+template <int DV, int DN, int NG, int WPG, int KS, int TOK, int STAGES>
 inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
   if (ev) (void)hipEventRecord(ev[0], st);
-  hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, TOK, STAGES>), dim3(plan.num_chunks),
-                     dim3(64 * NG * WPG), 0, st, d);
+  hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES>), dim3(plan.num_chunks),
+                     dim3(64 * NG * WPG * KS), 0, st, d);
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[1], st);
-  hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, TOK>), dim3(plan.units, (NG * WPG * (DV / 32) + 3) / 4),
+  hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK>), dim3(plan.units, (NG * WPG * (DV / 32) + 3) / 4),
                      dim3(256), 0, st, d);
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[2], st);
@@ -1162,16 +1228,24 @@ inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, hipStream_t
 
 template <int DV, int DN>
 inline int launch_tuned_shape(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
-  switch (plan.ng * 10 + plan.wpg) {
-    case 11: return launch_tuned_variant<DV, DN, 1, 1, kTok, tuned_stages(DV, 1, 1)>(plan, d, st, ev);
-    case 12: return launch_tuned_variant<DV, DN, 1, 2, kTok, tuned_stages(DV, 1, 2)>(plan, d, st, ev);
-    case 14: return launch_tuned_variant<DV, DN, 1, 4, kTok, tuned_stages(DV, 1, 4)>(plan, d, st, ev);
-    case 21: return launch_tuned_variant<DV, DN, 2, 1, kTok, tuned_stages(DV, 2, 1)>(plan, d, st, ev);
-    case 22: return launch_tuned_variant<DV, DN, 2, 2, kTok, tuned_stages(DV, 2, 2)>(plan, d, st, ev);
-    case 41:
-      if constexpr (DV <= 128) return launch_tuned_variant<DV, DN, 4, 1, kTok, tuned_stages(DV, 4, 1)>(plan, d, st, ev);
-      else return GLA_ERR_UNSUPPORTED_SHAPE;
-    default: return GLA_ERR_UNSUPPORTED_SHAPE;
+  if constexpr (DV > 256) {
+    switch (plan.ng * 100 + plan.wpg * 10 + plan.ks) {
+      case 112: return launch_tuned_variant<DV, DN, 1, 1, 2, kTok, tuned_stages(DV, 1, 1, 2)>(plan, d, st, ev);
+      case 122: return launch_tuned_variant<DV, DN, 1, 2, 2, kTok, tuned_stages(DV, 1, 2, 2)>(plan, d, st, ev);
+      default: return GLA_ERR_UNSUPPORTED_SHAPE;
+    }
+  } else {
+    switch (plan.ng * 100 + plan.wpg * 10 + plan.ks) {
+      case 111: return launch_tuned_variant<DV, DN, 1, 1, 1, kTok, tuned_stages(DV, 1, 1, 1)>(plan, d, st, ev);
+      case 121: return launch_tuned_variant<DV, DN, 1, 2, 1, kTok, tuned_stages(DV, 1, 2, 1)>(plan, d, st, ev);
+      case 141: return launch_tuned_variant<DV, DN, 1, 4, 1, kTok, tuned_stages(DV, 1, 4, 1)>(plan, d, st, ev);
+      case 211: return launch_tuned_variant<DV, DN, 2, 1, 1, kTok, tuned_stages(DV, 2, 1, 1)>(plan, d, st, ev);
+      case 221: return launch_tuned_variant<DV, DN, 2, 2, 1, kTok, tuned_stages(DV, 2, 2, 1)>(plan, d, st, ev);
+      case 411:
+        if constexpr (DV <= 128) return launch_tuned_variant<DV, DN, 4, 1, 1, kTok, tuned_stages(DV, 4, 1, 1)>(plan, d, st, ev);
+        else return GLA_ERR_UNSUPPORTED_SHAPE;
+      default: return GLA_ERR_UNSUPPORTED_SHAPE;
+    }
   }
 }
 
@@ -1185,6 +1259,7 @@ inline int tuned_launch(const gla_decode_params* p, int is_gta, DevParams& d, hi
   d.chunk_tiles = plan.chunk_tiles;
   if (plan.dv == 256 && plan.dn == 256) return launch_tuned_shape<256, 256>(plan, d, st, ev);
   if (plan.dv == 128 && plan.dn == 64) return launch_tuned_shape<128, 64>(plan, d, st, ev);
+  if (plan.dv == 512 && plan.dn == 512) return launch_tuned_shape<512, 512>(plan, d, st, ev);
   return GLA_ERR_UNSUPPORTED_SHAPE;
 }
 

@@ -31,7 +31,7 @@ def tuned_available(p):
     return gla.gla_decode_select_impl(prm, p.kind == "gta") == TUNED
 
 
-TUNED_SHAPES = {("gla", 256), ("gta", 128)}   # (kind, d_v) with an MFMA instantiation
+TUNED_SHAPES = {("gla", 256), ("gla", 512), ("gta", 128)}   # (kind, d_v) with an MFMA instantiation
 
 
 def impls_for(p):
@@ -73,11 +73,21 @@ def test_split_count_does_not_change_the_result(splits):
         check_problem(p, impl=impl, num_splits=splits, what=f"splits={splits} impl={impl}")
 
 
-def test_mla_shape_small():
-    p = make_problem("mla_small", seq_lens=[513, 64, 1, 200], h_q=128, h_c=1, d_v=512, seed=130,
-                     num_pages=1024, poison_tail=True)
+@pytest.mark.parametrize("T", [1, 2])
+def test_mla_shape_small(T):
+    """One latent head of 512: two waves share a row slab and exchange partial scores."""
+    p = make_problem("mla_small", seq_lens=[513, 64, 1, 200, 0, 1100], T=T, h_q=128, h_c=1, d_v=512,
+                     seed=130 + T, num_pages=1024, poison_tail=True)
     for impl in impls_for(p):
-        check_problem(p, impl=impl, what=f"mla impl={impl}")
+        check_problem(p, impl=impl, what=f"mla T={T} impl={impl}")
+
+
+def test_mla_shape_few_heads():
+    """16 heads on a 512-dim latent: a single row slab (two waves per workgroup)."""
+    p = make_problem("mla_few", seq_lens=[300, 65, 31], T=2, h_q=16, h_c=1, d_v=512, seed=133,
+                     num_pages=256, poison_tail=True)
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, what=f"mla few heads impl={impl}")
 
 
 @pytest.mark.parametrize("T", [1, 3])
