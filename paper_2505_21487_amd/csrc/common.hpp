@@ -31,7 +31,7 @@ struct DevParams {
   // generic kernel: uniform split of every sequence's page range
   int32_t splits, pages_per_split;
   // tuned kernel: flat partition of all key tiles of the batch into chunks
-  int32_t num_chunks;       // grid size of the main kernel
+  int32_t num_chunks;       // chunks of the tile list (the main kernel runs one workgroup per chunk and row block)
   int32_t chunk_tiles;      // > 0: fixed tiles per chunk; 0: ceil(total / num_chunks)
 };
 

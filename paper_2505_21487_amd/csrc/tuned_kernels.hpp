@@ -238,7 +238,7 @@ __device__ __forceinline__ int tiles_of(int L) {
 // Position in the flat tile list.
 struct TileCursor {
   int b;        // sequence
-  int ub;       // unit within the sequence: g * MB + mb
+  int ub;       // unit within the sequence (group block)
   int j;        // tile within the unit
   int tiles_b;  // tiles per unit of this sequence
   int L;        // its length
@@ -393,8 +393,8 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   const int hi = lane >> 5;   // which half of the contraction slots this lane feeds
 
   const int rows_group = p.g_q * p.T;
-  const int MB = (rows_group + 32 * WPG - 1) / (32 * WPG);
-  const int UPB = (p.h_c / NG) * MB;
+  const int MB = (rows_group + 32 * WPG - 1) / (32 * WPG);  // row blocks per group
+  const int UPB = p.h_c / NG;                               // units (group blocks) per sequence
 #ifdef GLA_EXPERIMENT_TIMESTAMPS
   // experiment build: wall-clock stamps of workgroup phases, 8 per workgroup,
   // written 192 MiB into the workspace (the experiment passes a larger one)
@@ -409,16 +409,26 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   const int L_first = lane < p.B ? p.seq_lens[lane] : 0;  // lengths of the first 64 sequences, reused below
   const int n_total = total_tiles<TOK>(p, UPB, lane, L_first);
   if (n_total <= 0) return;
-  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2):
-  // give every XCD a contiguous run of chunks, so the chunks of one sequence
-  // (same page-table row, same queries) meet in one L2.
-  const int xcd = (int)blockIdx.x & 7, xi = (int)blockIdx.x >> 3;
-  const int xq = (int)gridDim.x >> 3, xr = (int)gridDim.x & 7;
-  const int chunk_id = xcd * xq + min(xcd, xr) + xi;
+  // A chunk of the list is worked on by MB workgroups, one per row block of its
+  // groups (MB > 1 when a group has more query rows than a workgroup holds).
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): the
+  // MB workgroups of a chunk are placed on ONE XCD, where they run side by side
+  // so that the tiles the first one fetches are L2 hits for the others, and
+  // every XCD gets a contiguous run of chunks (same page-table rows, same
+  // queries).  Grids that do not divide evenly fall back to a plain order.
+  const int n_chunks = (int)gridDim.x / MB;  // the host launches n_chunks * MB workgroups
+  int chunk_id, mb_wg;
+  if ((int)gridDim.x % (8 * MB) == 0) {
+    const int xcd = (int)blockIdx.x & 7, n = (int)blockIdx.x >> 3;
+    mb_wg = n % MB;
+    chunk_id = xcd * (n_chunks >> 3) + n / MB;
+  } else {
+    mb_wg = (int)blockIdx.x % MB;
+    chunk_id = (int)blockIdx.x / MB;
+  }
   // Chunk i covers tiles [i * chunk, (i + 1) * chunk): a fixed length if the
   // caller chose a split count, else an equal share of the list.
-  const int chunk = p.chunk_tiles > 0 ? p.chunk_tiles
-                                      : (n_total + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int chunk = p.chunk_tiles > 0 ? p.chunk_tiles : (n_total + n_chunks - 1) / n_chunks;
   auto chunk_start = [&](int i) -> int { return (int)min((int64_t)n_total, (int64_t)i * chunk); };
   const int c0 = chunk_start(chunk_id);
   const int c1 = chunk_start(chunk_id + 1);
@@ -454,7 +464,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
 
   int pt_b = -1, pt_base = 0;
   int pt_vec = 0;
-  uint64_t pre_goff = (uint64_t)(pre.ub / MB) * NG * st_group_bytes;  // byte offset of the cursor's group block in a page
+  uint64_t pre_goff = (uint64_t)pre.ub * NG * st_group_bytes;  // byte offset of the cursor's group block in a page
   const unsigned char* pre_sp = nullptr;  // state / RoPE page of the prefetch cursor
   const unsigned char* pre_rp = nullptr;
   bool pre_page_valid = false;
@@ -469,27 +479,38 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   // chunk has been issued the previous tile's addresses are kept: the loads
   // then re-read lines that are still in L2 into a stage nobody reads, which
   // keeps the steady-state loop free of branches around the load instructions.
-  auto dma_prepare = [&](int stage) {
+  // The preparation is scalar work (a few dozen instructions).  It is cut in
+  // three pieces so that the tile loop can place them between value MFMAs
+  // instead of running them in one stretch with the matrix pipe idle.
+  bool prep_active = false, prep_need_page = false;
+  unsigned prep_page_idx = 0, prep_tip = 0;
+  auto dma_prepare_0 = [&](int stage) {  // where to, and is a page id needed
     dma_ls = lds_state_w + stage * STB;
     dma_lr = lds_rope_w + stage * RTB;
-    if (issued >= n_tiles) return;
-    const unsigned page_idx = (unsigned)pre.j / TPP;
-    const unsigned tip = (unsigned)pre.j % TPP;  // tile within the page
-    if (tip == 0 || !pre_page_valid) {
-      if (pre.b != pt_b || (int)page_idx < pt_base || (int)page_idx >= pt_base + 64) {
-        pt_b = pre.b;
-        pt_base = (int)page_idx;
-        const int idx = min((int)page_idx + lane, p.max_pages - 1);
-        pt_vec = load_i32_sync(p.page_table + (int64_t)pre.b * p.max_pages + idx);
-      }
-      const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pt_vec, (int)page_idx - pt_base);
+    prep_active = issued < n_tiles;
+    prep_page_idx = (unsigned)pre.j / TPP;
+    prep_tip = (unsigned)pre.j % TPP;  // tile within the page
+    prep_need_page = prep_active && (prep_tip == 0 || !pre_page_valid);
+    if (prep_need_page &&
+        (pre.b != pt_b || (int)prep_page_idx < pt_base || (int)prep_page_idx >= pt_base + 64)) {
+      pt_b = pre.b;
+      pt_base = (int)prep_page_idx;
+      const int idx = min((int)prep_page_idx + lane, p.max_pages - 1);
+      pt_vec = load_i32_sync(p.page_table + (int64_t)pre.b * p.max_pages + idx);
+    }
+  };
+  auto dma_prepare_1 = [&]() {  // page id -> page base addresses
+    if (prep_need_page) {
+      const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pt_vec, (int)prep_page_idx - pt_base);
       pre_sp = state_w + ((uint64_t)page * st_page_bytes + pre_goff);
       pre_rp = rope_w + (uint64_t)page * rp_page_bytes;
       pre_page_valid = true;
     }
-    dma_s = pre_sp + tip * STB;
-    dma_r = pre_rp + tip * RTB;
-    // advance the prefetch cursor
+  };
+  auto dma_prepare_2 = [&]() {  // tile addresses; advance the prefetch cursor
+    if (!prep_active) return;
+    dma_s = pre_sp + prep_tip * STB;
+    dma_r = pre_rp + prep_tip * RTB;
     ++issued;
     if (++pre.j == pre.tiles_b) {
       pre.j = 0;
@@ -502,8 +523,13 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
           pre.tiles_b = tiles_of<TOK>(pre.L);
         } while (pre.b < p.B && pre.tiles_b == 0);
       }
-      pre_goff = (uint64_t)(pre.ub / MB) * NG * st_group_bytes;
+      pre_goff = (uint64_t)pre.ub * NG * st_group_bytes;
     }
+  };
+  auto dma_prepare = [&](int stage) {
+    dma_prepare_0(stage);
+    dma_prepare_1();
+    dma_prepare_2();
   };
   // i-th of this wave's LPW loads of the prepared tile
   auto dma_load = [&](auto ic) {
@@ -531,8 +557,8 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   bool row_valid = false;
   int row_b = 0, row_t = 0, row_h = 0;
   auto q_issue = [&]() {
-    const int gb = cur.ub / MB;
-    const int mb = cur.ub - gb * MB;
+    const int gb = cur.ub;
+    const int mb = mb_wg;
     const int g = gb * NG + gl;
     const int R = (mb * WPG + wg) * 32 + col;
     row_valid = R < rows_group;
@@ -705,6 +731,27 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   };
   constexpr int NQ = NE + 2;                            // pipeline slots
   constexpr int S0 = NS >= 16 ? 4 : (NS >= 8 ? 2 : 1);  // score steps that overlap the row-max search
+  // Without a score exchange between waves (KS == 1) the masking and the row max
+  // of a tile are computed one phase early, under the value MFMAs of the tile
+  // before it, where the vector ALU is otherwise idle.
+  constexpr bool kEarlyMax = KS == 1;
+  constexpr int SA = kEarlyMax ? 0 : S0;                // first score step that carries softmax slots
+  constexpr int IW = ((NS - 1) / 4) * 4;                // step of the last wait for score operands
+  constexpr int VPRE = VRS < NP ? VRS : NP;             // value operands requested ahead of [B]
+  constexpr int MXS = 4;                                // [B] steps over which the row-max chain is spread
+  static_assert(2 + MXS <= NB, "row-max steps fit into [B]");
+  float mx_carry = -INFINITY;                           // kEarlyMax: lane-local max of the next tile's scores
+  auto mask_tile = [&](f32x16_t (&sc)[NTB], int tile_j) {
+    const int tile_tok0 = tile_j * TOK;
+    if (tile_tok0 + TOK > n_vis_min) {
+      const int lim = n_vis - tile_tok0 - 4 * hi;  // element (tb, i) is visible iff its constant < lim
+#pragma unroll
+      for (int tb = 0; tb < NTB; ++tb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          sc[tb][i] = (32 * tb + 8 * (i >> 2) + (i & 3)) < lim ? sc[tb][i] : -INFINITY;
+    }
+  };
 
   // KS = 2: the two waves of a row slab hold partial scores (each over its share
   // of the contraction dims).  Each posts its 16 values per lane in its own
@@ -749,7 +796,20 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   // tile k+1 (into s_wr), then [B] value MFMAs of tile k under the loads of tile
   // k + STAGES - 1.  k: chunk-local tile index, tile_j: index in the unit, PSG /
   // SSG: stage of tile k / of tile k+1 (or -1, see above), pv_stage: stage of tile k.
+#ifdef GLA_EXPERIMENT_PHASE_CLOCKS
+  // experiment build: core-clock time of wave 0 spent in the phases of the tile loop
+  long long ph_acc[4] = {0, 0, 0, 0};
+  long long ph_t = 0;
+  int ph_n = 0;
+#define GLA_PHASE(i) do { const long long t_ = (long long)clock64(); ph_acc[i] += t_ - ph_t; ph_t = t_; } while (0)
+#else
+#define GLA_PHASE(i) do { } while (0)
+#endif
   auto tile_iter = [&](f32x16_t (&s_rd)[NTB], f32x16_t (&s_wr)[NTB], int k, int tile_j, bool has_next, int seg_L) {
+#ifdef GLA_EXPERIMENT_PHASE_CLOCKS
+    ph_t = (long long)clock64();
+    ++ph_n;
+#endif
     constexpr std::integral_constant<int, -1> psgc{}, ssgc{};  // stages live in the address registers
     const int pv_stage = k % STAGES;
     // ---- tile k+1 landed?  (also: every wave is done with tile k-1, so its stage is free)
@@ -758,6 +818,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       else wait_vmcnt<0>();
     }
     lds_barrier();
+    GLA_PHASE(0);
     if (has_next) zero_tail((pv_stage + 1) % STAGES, tile_j + 1, seg_L);
 
 #ifdef GLA_EXPERIMENT_NO_COMPUTE
@@ -772,29 +833,28 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     xchg_fetch();
     static_for<0, (RS < NS ? RS : NS)>([&](auto ic) { s_issue(ssgc, ic); });
     xchg_add(s_rd);
-    const int tile_tok0 = tile_j * TOK;
-    if (tile_tok0 + TOK > n_vis_min) {
-      const int lim = n_vis - tile_tok0 - 4 * hi;  // element (tb, i) is visible iff its constant < lim
-#pragma unroll
-      for (int tb = 0; tb < NTB; ++tb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          s_rd[tb][i] = (32 * tb + 8 * (i >> 2) + (i & 3)) < lim ? s_rd[tb][i] : -INFINITY;
-    }
-    float mx = -INFINITY;
-    pin_arch(mx);
-    static_for<0, S0>([&](auto ic) {
-      constexpr int i = decltype(ic)::value;
-      if constexpr (i % 4 == 0) s_wait(ic);
-      constexpr int e0 = (i * NE) / S0, e1 = ((i + 1) * NE) / S0;
-      static_for<e0 / 2, e1 / 2>([&](auto jc) {
-        constexpr int e = 2 * decltype(jc)::value;
-        asm_max3(mx, s_rd[e / 16][e % 16], s_rd[(e + 1) / 16][(e + 1) % 16]);
+    float mx;
+    if constexpr (kEarlyMax) {
+      // masking and row max of tile k were done while the previous tile's value
+      // MFMAs ran (or in the segment prologue): only the cross-half step is left
+      mx = half_swap_max(mx_carry) * sc2;
+    } else {
+      mask_tile(s_rd, tile_j);
+      mx = -INFINITY;
+      pin_arch(mx);
+      static_for<0, S0>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        if constexpr (i % 4 == 0) s_wait(ic);
+        constexpr int e0 = (i * NE) / S0, e1 = ((i + 1) * NE) / S0;
+        static_for<e0 / 2, e1 / 2>([&](auto jc) {
+          constexpr int e = 2 * decltype(jc)::value;
+          asm_max3(mx, s_rd[e / 16][e % 16], s_rd[(e + 1) / 16][(e + 1) % 16]);
+        });
+        s_mfma(ssgc, ic, s_wr);
+        __builtin_amdgcn_sched_barrier(0);
       });
-      s_mfma(ssgc, ic, s_wr);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    mx = half_swap_max(mx) * sc2;
+      mx = half_swap_max(mx) * sc2;
+    }
     // lazy reference update: keep the old reference while the row max stays
     // within 2^8 of it (weights then stay <= 256, exact enough in fp32 / bf16)
     const bool bump = mx > m_ref + 8.0f;
@@ -826,24 +886,28 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     lsum = 0.f;
     pin_arch(neg_m);
     pin_arch(lsum);
-    // ---- [A] remaining score steps of tile k+1 under the exponentials of tile k
-    static_for<S0, NS>([&](auto ic) {
+    GLA_PHASE(1);
+    // ---- [A] (remaining) score steps of tile k+1 under the exponentials of tile k.
+    //          Once the last score operands have been waited for, the first value
+    //          operands of [B] are requested so that they arrive under these MFMAs.
+    static_for<SA, NS>([&](auto ic) {
       constexpr int i = decltype(ic)::value;
       if constexpr (i % 4 == 0) s_wait(ic);
-      constexpr int q0 = ((i - S0) * NQ) / (NS - S0), q1 = ((i - S0 + 1) * NQ) / (NS - S0);
+      constexpr int q0 = ((i - SA) * NQ) / (NS - SA), q1 = ((i - SA + 1) * NQ) / (NS - SA);
       static_for<q0, q1>([&](auto qc) { sm_slot(qc, s_rd); });
       s_mfma(ssgc, ic, s_wr);
+      if constexpr (i >= IW)
+        static_for<((i - IW) * VPRE) / (NS - IW), ((i - IW + 1) * VPRE) / (NS - IW)>([&](auto jc) { v_issue(psgc, jc); });
       __builtin_amdgcn_sched_barrier(0);
     });
     l_run += lsum;
     xchg_post(s_wr);
+    GLA_PHASE(2);
 
     // ---- [B] O^T += V^T . P^T for tile k under the loads of the tile that reuses
     //          the stage of tile k-1.  Contraction slot (hi, j) of step st is token
     //          16*st + 8*(j/4) + 4*hi + j%4, matching the score accumulator layout.
     //          The address registers move on to the next stages in the gaps.
-    static_for<0, (VRS < NP ? VRS : NP)>([&](auto ic) { v_issue(psgc, ic); });
-    dma_prepare((pv_stage + STAGES - 1) % STAGES);
     const bool s_wrap = (pv_stage + 2) % STAGES == 0, v_wrap = (pv_stage + 1) % STAGES == 0;
     const int k_step = s_wrap ? -(STAGES - 1) * STB : STB, r_step = s_wrap ? -(STAGES - 1) * RTB : RTB;
     const int v_step = v_wrap ? -(STAGES - 1) * STB : STB;
@@ -852,7 +916,23 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       constexpr int i = decltype(ic)::value;
       if constexpr (i < NP && i % 2 == 0) v_wait(ic);
       v_mfma(psgc, ic);
-      static_for<(i * LPW) / NB, ((i + 1) * LPW) / NB>(dma_load);  // loads of the next tile
+      if constexpr (kEarlyMax) {  // masking and lane-local row max of tile k+1 (its scores are complete)
+        if constexpr (i == 1) {
+          if (has_next) mask_tile(s_wr, tile_j + 1);
+          mx_carry = -INFINITY;
+          pin_arch(mx_carry);
+        } else if constexpr (i >= 2 && i < 2 + MXS) {
+          static_for<((i - 2) * (NE / 2)) / MXS, ((i - 1) * (NE / 2)) / MXS>([&](auto jc) {
+            constexpr int e = 2 * decltype(jc)::value;
+            asm_max3(mx_carry, s_wr[e / 16][e % 16], s_wr[(e + 1) / 16][(e + 1) % 16]);
+          });
+        }
+      }
+      // preparation of the next loads in the first steps, the loads themselves after it
+      if constexpr (i == 0) dma_prepare_0((pv_stage + STAGES - 1) % STAGES);
+      else if constexpr (i == 1) dma_prepare_1();
+      else if constexpr (i == 2) dma_prepare_2();
+      else static_for<((i - 3) * LPW) / (NB - 3), ((i - 2) * LPW) / (NB - 3)>(dma_load);
       // score addresses: next used in the next tile's [A]
       static_for<(i * (8 + NKR)) / NB, ((i + 1) * (8 + NKR)) / NB>([&](auto ec) {
         constexpr int e = decltype(ec)::value;
@@ -866,6 +946,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     for (int d4 = 0; d4 < 4; ++d4)
 #pragma unroll
       for (int a = 0; a < 2; ++a) va[d4][a] += v_step;
+    GLA_PHASE(3);
   };
   // the two score register sets: tile t of a segment reads the one tile t-1 wrote
   f32x16_t s_even[NTB], s_odd[NTB];
@@ -876,7 +957,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     const int seg_j0 = cur.j;
     const int seg_L = cur.L;
     const int seg_tiles_b = cur.tiles_b;
-    const int seg_unit = cur.b * UPB + cur.ub;
+    const int seg_unit = (cur.b * UPB + cur.ub) * MB + mb_wg;  // index of this (unit, row block)
     // query fragments (unless already requested ahead of the first tiles); the
     // wait also covers tile k: loads complete in issue order
     if (!q_early) q_issue();
@@ -933,7 +1014,18 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
 #pragma unroll
       for (int e = 0; e < NKR; ++e) ra[e] += wrap ? -(STAGES - 1) * RTB : RTB;
     }
-    wait_states<16>();  // the scores are read by the vector ALU right below
+    // the scores are read by the vector ALU next; the wait is tied to them so
+    // that no read can be scheduled ahead of it
+    asm volatile("s_nop 15" : "+v"(s_even[0]));
+    if constexpr (kEarlyMax) {
+      mask_tile(s_even, seg_j0);
+      mx_carry = -INFINITY;
+      pin_arch(mx_carry);
+      static_for<0, NE / 2>([&](auto jc) {
+        constexpr int e = 2 * decltype(jc)::value;
+        asm_max3(mx_carry, s_even[e / 16][e % 16], s_even[(e + 1) / 16][(e + 1) % 16]);
+      });
+    }
     xchg_post(s_even);
     if (k == 0) GLA_STAMP(3);
 
@@ -967,7 +1059,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       const int lr = wave * 32 + col;
       const int64_t ob = row_b * p.out_s[0] + row_t * p.out_s[1] + row_h * p.out_s[2];
       // partial: slot 1 if the unit's first tile is in this chunk, slot 0 if it began earlier
-      float* slot = p.ws_out + ((size_t)chunk_id * 2 + (seg_j0 == 0 ? 1 : 0)) * TT::kSlotFloats;
+      float* slot = p.ws_out + (((size_t)chunk_id * MB + mb_wg) * 2 + (seg_j0 == 0 ? 1 : 0)) * TT::kSlotFloats;
       if (seg_j0 == 0 && tid == 0) {
         // tell the merge kernel which chunks hold this unit: it starts here and
         // ends in the chunk of its last tile
@@ -1008,8 +1100,16 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     GLA_STAMP(5);
   }
   GLA_STAMP(6);
+#ifdef GLA_EXPERIMENT_PHASE_CLOCKS
+  if (tid == 0) {
+    long long* const out_ph = (long long*)((char*)p.ws_out + (194ll << 20)) + (size_t)blockIdx.x * 8;
+    for (int i = 0; i < 4; ++i) out_ph[i] = ph_acc[i];
+    out_ph[4] = ph_n;
+  }
+#endif
 }
 #undef GLA_STAMP
+#undef GLA_PHASE
 
 // Merge of the partial results of units that span several chunks, and zero fill
 // of units without any key:  lse = ln sum_s exp(lse_s),
@@ -1037,7 +1137,7 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
   const int rows_group = p.g_q * p.T;
   const int MB = (rows_group + 32 * WPG - 1) / (32 * WPG);
   const int UPB = (p.h_c / NG) * MB;
-  const int unit = blockIdx.x;
+  const int unit = blockIdx.x;  // (sequence, group block, row block)
   const int b = unit / UPB;
   const int ub = unit - b * UPB;
   const int gb = ub / MB, mb = ub - gb * MB;
@@ -1058,11 +1158,11 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
   float m = -INFINITY;
 #pragma unroll 4
   for (int k = k_first; k <= k_last; ++k)
-    m = fmaxf(m, slot0[((size_t)k * 2 + (k == k_first)) * kSlotFloats]);
+    m = fmaxf(m, slot0[(((size_t)k * MB + mb) * 2 + (k == k_first)) * kSlotFloats]);
   float z = 0.f;
   if (m != -INFINITY) {
 #pragma unroll 4
-    for (int k = k_first; k <= k_last; ++k) z += expf(slot0[((size_t)k * 2 + (k == k_first)) * kSlotFloats] - m);
+    for (int k = k_first; k <= k_last; ++k) z += expf(slot0[(((size_t)k * MB + mb) * 2 + (k == k_first)) * kSlotFloats] - m);
   }
   const float lse = m == -INFINITY ? -INFINITY : m + logf(z);
   if (db == 0 && hi == 0 && kx == 0) p.lse[((int64_t)b * p.T + t) * p.h_q + h] = lse;
@@ -1073,7 +1173,7 @@ __global__ __launch_bounds__(256) void tuned_combine_kernel(DevParams p) {
     const float* const frag0 = p.ws_out + (size_t)((w * NDB + db) * 4) * 256 + lane * 4;
 #pragma unroll 2
     for (int k = k_first; k <= k_last; ++k) {
-      const size_t so = ((size_t)k * 2 + (k == k_first)) * kSlotFloats;
+      const size_t so = (((size_t)k * MB + mb) * 2 + (k == k_first)) * kSlotFloats;
       const float ls = slot0[so];
       // a slot marked "no key" may hold anything (an empty chunk never wrote its
       // data part): its values are dropped, not multiplied by zero
@@ -1110,7 +1210,7 @@ struct TunedPlan {
   int rows;        // 32 * ng * wpg
   int mb;          // row blocks per (sequence, group)
   int units;       // batch * (h_c / ng) * mb
-  int num_chunks;  // main-kernel grid
+  int num_chunks;  // chunks of the tile list; the main-kernel grid is num_chunks * mb
   int chunk_tiles; // fixed tiles per chunk, 0: derived on the device
   size_t slot_floats;
 };
@@ -1182,15 +1282,18 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
   const int per_cu = std::max(1, std::min((160 * 1024) / smem, 4 / (ng * wpg * ks)));
   plan->tok = tok;
   plan->stages = stages;
+  // the tile list holds each (sequence, group block) once; every chunk of it is
+  // worked on by mb workgroups (one per row block), so the grid is num_chunks * mb
   const int64_t max_tiles = (int64_t)p->max_pages_per_seq * (kPage / tok);
-  const int64_t bound = (int64_t)plan->units * max_tiles;
-  if (bound > 0x3fffffff) return false;
+  const int64_t bound = (int64_t)(plan->units / plan->mb) * max_tiles;
+  if (bound * plan->mb > 0x3fffffff) return false;
   if (p->num_splits > 0) {
     plan->chunk_tiles = (int)((max_tiles + p->num_splits - 1) / p->num_splits);
     plan->num_chunks = (int)std::max<int64_t>(1, (bound + plan->chunk_tiles - 1) / plan->chunk_tiles);
   } else {
     plan->chunk_tiles = 0;
-    plan->num_chunks = (int)std::max<int64_t>(1, std::min<int64_t>(bound, (int64_t)device_cu_count() * per_cu));
+    const int64_t resident = std::max<int64_t>(1, (int64_t)device_cu_count() * per_cu / plan->mb);
+    plan->num_chunks = (int)std::max<int64_t>(1, std::min<int64_t>(bound, resident));
   }
   plan->slot_floats = (size_t)plan->rows * p->d_v + (size_t)32 * ng * wpg * ks;
   return true;
@@ -1203,7 +1306,7 @@ inline bool tuned_supported(const gla_decode_params* p, int is_gta) {
 
 // Workspace: two partial slots per chunk, then per unit the chunk range holding it.
 inline size_t tuned_slots_bytes(const TunedPlan& plan) {
-  return (((size_t)plan.num_chunks * 2 * plan.slot_floats * sizeof(float)) + 255) & ~(size_t)255;
+  return (((size_t)plan.num_chunks * plan.mb * 2 * plan.slot_floats * sizeof(float)) + 255) & ~(size_t)255;
 }
 
 inline size_t tuned_workspace(const gla_decode_params* p, int is_gta) {
@@ -1215,7 +1318,7 @@ inline size_t tuned_workspace(const gla_decode_params* p, int is_gta) {
 template <int DV, int DN, int NG, int WPG, int KS, int TOK, int STAGES>
 inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
   if (ev) (void)hipEventRecord(ev[0], st);
-  hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES>), dim3(plan.num_chunks),
+  hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES>), dim3(plan.num_chunks * plan.mb),
                      dim3(64 * NG * WPG * KS), 0, st, d);
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[1], st);
