@@ -405,10 +405,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
 #endif
   GLA_STAMP(0);
 
-  // ---- plan: this workgroup's chunk [c0, c1) of the flat tile list
-  const int L_first = lane < p.B ? p.seq_lens[lane] : 0;  // lengths of the first 64 sequences, reused below
-  const int n_total = total_tiles<TOK>(p, UPB, lane, L_first);
-  if (n_total <= 0) return;
   // A chunk of the list is worked on by MB workgroups, one per row block of its
   // groups (MB > 1 when a group has more query rows than a workgroup holds).
   // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): the
@@ -426,6 +422,38 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     mb_wg = (int)blockIdx.x % MB;
     chunk_id = (int)blockIdx.x / MB;
   }
+
+  // ---- a guess, made before anything is known about the lengths: if every
+  // sequence filled its page-table row, this chunk would start at page pg of
+  // sequence b_g.  That stretch of the page table is requested right away, next
+  // to the lengths, and used if the plan below lands inside it (always, for a
+  // batch of equal full-length sequences): one dependent memory round trip less
+  // before the first tile can be requested.
+  int pt_b = -1, pt_base = 0;
+  int pt_vec = 0;
+  int L_first;  // lengths of the first 64 sequences (0 beyond the batch), reused by the plan
+  {
+    const int64_t tiles_full = (int64_t)p.max_pages * (int)TPP;
+    const int64_t total_g = (int64_t)p.B * UPB * tiles_full;
+    const int64_t chunk_g = p.chunk_tiles > 0 ? p.chunk_tiles : (total_g + n_chunks - 1) / n_chunks;
+    const int64_t c0_g = min((int64_t)chunk_id * chunk_g, total_g - 1);  // (chunks past the end: any valid row)
+    const int b_g = (int)(c0_g / (UPB * tiles_full));
+    const int pg = (int)((c0_g % tiles_full) / (int)TPP);
+    const int32_t* ptr_pt = p.page_table + (int64_t)b_g * p.max_pages + min(pg + lane, p.max_pages - 1);
+    const int32_t* ptr_len = p.seq_lens + (lane < p.B ? lane : 0);
+    // both requests in flight together, both complete when the statement ends
+    asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %3, off\n\ts_waitcnt vmcnt(0)"
+                 : "=&v"(pt_vec), "=&v"(L_first)
+                 : "v"(ptr_pt), "v"(ptr_len)
+                 : "memory");
+    if (lane >= p.B) L_first = 0;
+    pt_b = b_g;
+    pt_base = pg;
+  }
+
+  // ---- plan: this workgroup's chunk [c0, c1) of the flat tile list
+  const int n_total = total_tiles<TOK>(p, UPB, lane, L_first);
+  if (n_total <= 0) return;
   // Chunk i covers tiles [i * chunk, (i + 1) * chunk): a fixed length if the
   // caller chose a split count, else an equal share of the list.
   const int chunk = p.chunk_tiles > 0 ? p.chunk_tiles : (n_total + n_chunks - 1) / n_chunks;
@@ -462,8 +490,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   unsigned char* const lds_state_w = smem + gl * TT::kGroupBytes + wpos * (SLW * 1024);
   unsigned char* const lds_rope_w = smem + TT::kRopeBase + wave * (RLW * 1024);
 
-  int pt_b = -1, pt_base = 0;
-  int pt_vec = 0;
   uint64_t pre_goff = (uint64_t)pre.ub * NG * st_group_bytes;  // byte offset of the cursor's group block in a page
   const unsigned char* pre_sp = nullptr;  // state / RoPE page of the prefetch cursor
   const unsigned char* pre_rp = nullptr;
@@ -550,8 +576,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
 
   // ---- query fragments of the unit at `cur`: this wave's 32 rows, B operand of
   //      the score MFMAs, lane holds 8 dims of row `col` per contraction step.
-  //      Requested here, ahead of the first tiles, and again whenever the unit
-  //      changes; complete after the next vmcnt wait that covers them.
+  //      Requested at the start of every segment, after the first tiles.
   u32x4_t qn[NKN];  // raw bf16 bits (accumulation VGPRs)
   u32x4_t qr[NKR];
   bool row_valid = false;
@@ -574,8 +599,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
 #pragma unroll
     for (int ks = 0; ks < NKR; ++ks) load_b128_async(qr[ks], qr_ptr + 16 * ks);
   };
-  q_issue();
-  bool q_early = true;
 
   // ---- prologue: fill STAGES-1 stages
 #pragma unroll
@@ -958,12 +981,12 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     const int seg_L = cur.L;
     const int seg_tiles_b = cur.tiles_b;
     const int seg_unit = (cur.b * UPB + cur.ub) * MB + mb_wg;  // index of this (unit, row block)
-    // query fragments (unless already requested ahead of the first tiles); the
-    // wait also covers tile k: loads complete in issue order
-    if (!q_early) q_issue();
-    if (q_early && issued - 1 - k >= STAGES - 2) wait_vmcnt<LPW * (STAGES - 2)>();
-    else wait_vmcnt<0>();
-    q_early = false;
+    // Query fragments of this unit.  The wait follows at once (it also covers the
+    // tiles already requested): the registers the loads write must not be
+    // touched, not even copied, before the data has arrived, and only a wait
+    // right behind the requests guarantees that.
+    q_issue();
+    wait_vmcnt<0>();
     {
 #pragma unroll
       for (int ks = 0; ks < NKN; ++ks) pin_acc(qn[ks]);

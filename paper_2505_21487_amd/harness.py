@@ -10,7 +10,9 @@ class DeviceProblem:
     """Device tensors of one problem: the paged pool holds `num_pages` slots of
     which only the used ones are written."""
 
-    def __init__(self, p, device="cuda:0", pool=None):
+    def __init__(self, p, device="cuda:0", pool=None, poison_unused=False):
+        """poison_unused: fill the whole pool with NaN before the used pages are
+        written (small pools only), so that a read of any other page shows."""
         dev = torch.device(device)
         self.p = p
         self.q_nope = p.q_nope.to(dev)
@@ -18,6 +20,9 @@ class DeviceProblem:
         if pool is None:
             state = torch.empty(p.num_pages, p.h_c, p.page_size, p.d_v, dtype=torch.bfloat16, device=dev)
             rope = torch.empty(p.num_pages, p.page_size, p.d_r, dtype=torch.bfloat16, device=dev)
+            if poison_unused and p.num_pages <= 16384:
+                state.fill_(float("nan"))
+                rope.fill_(float("nan"))
         else:
             state, rope = pool
         n_used = len(p.page_ids)

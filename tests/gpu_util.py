@@ -14,8 +14,21 @@ LSE_MAX_ABS = 1e-3
 
 
 def run_gpu(p, dp=None, **kw):
-    dp = dp or DeviceProblem(p)
-    fn = gla.gta_decode if p.kind == "gta" else gla.gla_decode
+    """One call through the C ABI.  Unused pool pages hold NaN and the workspace
+    is handed over filled with 0xFF bytes (NaN as floats, -1 as ints): a result
+    that depends on anything the call did not write or was not given shows."""
+    dp = dp or DeviceProblem(p, poison_unused=True)
+    is_gta = p.kind == "gta"
+    fn = gla.gta_decode if is_gta else gla.gla_decode
+    if "workspace" not in kw:
+        out_dtype = kw.get("out_dtype", torch.bfloat16)
+        o = torch.empty(p.B, p.T, p.h_q, p.d_v, dtype=out_dtype, device="cuda")
+        l = torch.empty(p.B, p.T, p.h_q, dtype=torch.float32, device="cuda")
+        prm = gla.make_params(*dp.args()[:6], p.scale, out=o, lse=l, workspace=None,
+                              causal=bool(p.causal), num_splits=kw.get("num_splits", 0),
+                              impl=kw.get("impl", gla.GLA_IMPL_AUTO))
+        need = gla.gla_decode_workspace_size(prm, is_gta)
+        kw = dict(kw, workspace=torch.full((max(need, 256),), 0xFF, dtype=torch.uint8, device="cuda"))
     out, lse = fn(*dp.args(), causal=bool(p.causal), **kw)
     torch.cuda.synchronize()
     return out.to(torch.float64).cpu().numpy(), lse.to(torch.float64).cpu().numpy()

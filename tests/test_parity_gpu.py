@@ -113,7 +113,7 @@ def test_generic_kernel_odd_shapes_and_strides():
     p = make_problem("odd", seq_lens=[37, 5, 0, 90], T=3, h_q=6, h_c=3, d_v=96, d_r=32, page_size=16,
                      seed=160, num_pages=64, poison_tail=True)
     check_problem(p, what="odd shapes")
-    dp = DeviceProblem(p)
+    dp = DeviceProblem(p, poison_unused=True)
     # queries as a slice of a wider buffer, output into a strided view
     wide = torch.zeros(p.B, p.T, p.h_q, p.d_n + 40, dtype=torch.bfloat16, device="cuda")
     wide[..., 8:8 + p.d_n] = dp.q_nope
@@ -137,7 +137,7 @@ def test_non_causal():
 def test_repeat_calls_are_bit_identical():
     p = make_problem("determinism", seq_lens=[3000, 1000, 64], h_q=128, h_c=2, d_v=256, seed=180,
                      num_pages=4096)
-    dp = DeviceProblem(p)
+    dp = DeviceProblem(p, poison_unused=True)
     for impl in impls_for(p):
         a = run_gpu(p, dp=dp, impl=impl)
         b = run_gpu(p, dp=dp, impl=impl)
@@ -146,7 +146,7 @@ def test_repeat_calls_are_bit_identical():
 
 def test_workspace_too_small_is_reported():
     p = make_problem("ws", seq_lens=[500], h_q=128, h_c=2, d_v=256, seed=190, num_pages=64)
-    dp = DeviceProblem(p)
+    dp = DeviceProblem(p, poison_unused=True)
     ws = torch.empty(256, dtype=torch.uint8, device="cuda")
     with pytest.raises(gla.GlaError) as e:
         gla.gla_decode(*dp.args(), workspace=ws, num_splits=4, impl=GENERIC)
