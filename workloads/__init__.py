@@ -211,4 +211,11 @@ def config(index: int, *, T: Optional[int] = None, draw: int = 0, batch: Optiona
         lens = uniform_lengths(batch or 128, min(4096, hi), hi, seed + 7)
         return make_problem("gta4_b128", kind="gta", seq_lens=lens, T=T or 1, h_q=32, h_c=4,
                             d_v=128, num_pages=POOL_PAGES, seed=seed, **tbl)
+    if index == 5:
+        # not one of the five stated configurations: the GLA-2 head shape on a ragged
+        # batch of contexts up to 32K, for the q_len sweep (MFMA utilisation vs q_len)
+        hi = max_len or 32768
+        lens = uniform_lengths(batch or 64, min(4096, hi), hi, seed + 7)
+        return make_problem("gla2_ragged_b64", seq_lens=lens, T=T or 1, h_q=128, h_c=2, d_v=256,
+                            num_pages=POOL_PAGES, seed=seed, **tbl)
     raise ValueError(f"no config {index}")
