@@ -153,6 +153,9 @@ def main() -> int:
                     help="untimed calls first; the default outlasts the clock transient of the first ~10 ms of load")
     ap.add_argument("--config", type=int, default=1, help="index into the configuration list")
     ap.add_argument("--q-len", type=int, default=0, help="override query length (1..4)")
+    ap.add_argument("--lens", default="", help="instead of --config: sequence lengths, e.g. 131072 or "
+                    "1024x15,65536 (kernel-latency workloads, see workloads.latency_workload)")
+    ap.add_argument("--shape", default="gla2", help="head shape for --lens: gla2 or mla")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--impl", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -172,14 +175,17 @@ def main() -> int:
     import paper_2505_21487_amd as gla
     from paper_2505_21487_amd import accounting
     from paper_2505_21487_amd.harness import DeviceProblem
-    from workloads import config
+    from workloads import config, latency_workload
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     T = args.q_len or None
-    p0 = config(args.config, T=T, draw=0, page_offset=0)
-    n_used = len(p0.page_ids)
-    p1 = config(args.config, T=T, draw=1, page_offset=n_used)
+    if args.lens:
+        p0 = latency_workload(args.lens, shape=args.shape, T=T or 1, draw=0, page_offset=0)
+        p1 = latency_workload(args.lens, shape=args.shape, T=T or 1, draw=1, page_offset=len(p0.page_ids))
+    else:
+        p0 = config(args.config, T=T, draw=0, page_offset=0)
+        p1 = config(args.config, T=T, draw=1, page_offset=len(p0.page_ids))
     d0 = DeviceProblem(p0, dev)
     d1 = DeviceProblem(p1, dev, pool=(d0.state_cache, d0.rope_cache))
     is_gta = p0.kind == "gta"
@@ -228,7 +234,7 @@ def main() -> int:
         roof = {"bound": "mfma", "achieved": fl / (main_us * 1e-6) / 1e12,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = stored_traffic(args.config, p0.T)
+    roof["traffic"] = None if args.lens else stored_traffic(args.config, p0.T)
     roof["kernel"] = "main (split-KV attention)"
     roof["kernel_us"] = main_us
     roof["combine_us"] = comb_us
@@ -246,7 +252,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"configs[{args.config}] {p0.name}: B={p0.B} q_len={p0.T} "
+        "config": {"workload": f"{'custom' if args.lens else f'configs[{args.config}]'} {p0.name}: B={p0.B} q_len={p0.T} "
                                f"h_q={p0.h_q} h_c={p0.h_c} d_v={p0.d_v} d_rope={p0.d_r} "
                                f"page={p0.page_size} tokens={p0.total_tokens} "
                                f"pool_pages={p0.num_pages}",

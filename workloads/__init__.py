@@ -219,3 +219,33 @@ def config(index: int, *, T: Optional[int] = None, draw: int = 0, batch: Optiona
         return make_problem("gla2_ragged_b64", seq_lens=lens, T=T or 1, h_q=128, h_c=2, d_v=256,
                             num_pages=POOL_PAGES, seed=seed, **tbl)
     raise ValueError(f"no config {index}")
+
+
+def parse_lens(spec: str):
+    """'1024x15,65536' -> [1024] * 15 + [65536]."""
+    out = []
+    for part in spec.split(","):
+        if "x" in part:
+            v, n = part.split("x")
+            out += [int(v)] * int(n)
+        else:
+            out.append(int(part))
+    return out
+
+
+def latency_workload(spec: str, *, shape: str = "gla2", T: int = 1, draw: int = 0,
+                     page_offset: int = 0) -> DecodeProblem:
+    """Kernel-latency workloads in the style of the paper's appendix on kernel
+    execution time: batch 1 at one context length, or a few short sequences plus
+    one long one (imbalanced batch).  shape: 'gla2' (2 x 256 + 64, 128 heads) or
+    'mla' (1 x 512 + 64, 128 heads)."""
+    lens = parse_lens(spec)
+    seed = BASE_SEED + 77 + 1000 * draw
+    tbl = dict(table_seed=BASE_SEED + 577, page_offset=page_offset)
+    if shape == "gla2":
+        return make_problem(f"latency_gla2[{spec}]", seq_lens=lens, T=T, h_q=128, h_c=2, d_v=256,
+                            num_pages=POOL_PAGES, seed=seed, **tbl)
+    if shape == "mla":
+        return make_problem(f"latency_mla[{spec}]", seq_lens=lens, T=T, h_q=128, h_c=1, d_v=512,
+                            num_pages=POOL_PAGES, seed=seed, **tbl)
+    raise ValueError(shape)
