@@ -156,6 +156,7 @@ def main() -> int:
     ap.add_argument("--lens", default="", help="instead of --config: sequence lengths, e.g. 131072 or "
                     "1024x15,65536 (kernel-latency workloads, see workloads.latency_workload)")
     ap.add_argument("--shape", default="gla2", help="head shape for --lens: gla2 or mla")
+    ap.add_argument("--page-size", type=int, default=64, help="16, 32 or 64 tokens per page")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--impl", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -184,8 +185,8 @@ def main() -> int:
         p0 = latency_workload(args.lens, shape=args.shape, T=T or 1, draw=0, page_offset=0)
         p1 = latency_workload(args.lens, shape=args.shape, T=T or 1, draw=1, page_offset=len(p0.page_ids))
     else:
-        p0 = config(args.config, T=T, draw=0, page_offset=0)
-        p1 = config(args.config, T=T, draw=1, page_offset=len(p0.page_ids))
+        p0 = config(args.config, T=T, draw=0, page_offset=0, page_size=args.page_size)
+        p1 = config(args.config, T=T, draw=1, page_offset=len(p0.page_ids), page_size=args.page_size)
     d0 = DeviceProblem(p0, dev)
     d1 = DeviceProblem(p1, dev, pool=(d0.state_cache, d0.rope_cache))
     is_gta = p0.kind == "gta"
@@ -234,7 +235,7 @@ def main() -> int:
         roof = {"bound": "mfma", "achieved": fl / (main_us * 1e-6) / 1e12,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None if args.lens else stored_traffic(args.config, p0.T)
+    roof["traffic"] = None if (args.lens or args.page_size != 64) else stored_traffic(args.config, p0.T)
     roof["kernel"] = "main (split-KV attention)"
     roof["kernel_us"] = main_us
     roof["combine_us"] = comb_us

@@ -24,8 +24,12 @@
  * lse = -inf.
  *
  * The cache is paged: token j of sequence b lives in physical page
- * page_table[b][j / page_size] at slot j % page_size.  Slots at or beyond L_b
- * and table entries at or beyond ceil(L_b / page_size) are never read.
+ * page_table[b][j / page_size] at slot j % page_size.  Table entries at or
+ * beyond ceil(L_b / page_size) are never read (they may hold anything, -1
+ * included); slots at or beyond L_b inside a page the table does hold may be
+ * fetched but never reach a result, whatever they contain (NaN included).
+ * The MFMA kernel runs for page_size 64, 32 and 16; other page sizes take the
+ * generic kernel.
  *
  * Ownership and execution.  Every pointer in the struct is a DEVICE pointer
  * owned by the caller unless stated otherwise; the library allocates no device

@@ -51,7 +51,6 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void global_cvoid_t;
 
-constexpr int kPage = 64;  // page size of the tuned path
 
 // ---- small device helpers -------------------------------------------------
 
@@ -342,9 +341,8 @@ struct TunedTraits {
   static constexpr int kRopeLoads = kRopeBytes / 1024;
   static constexpr int kLoadsPerWave = kStateLoads / (WPG * KS) + kRopeLoads / NWAVES;
   static constexpr int kThreads = 64 * NWAVES;
-  static constexpr int kTilesPerPage = kPage / TOK;
   static constexpr size_t kSlotFloats = (size_t)kRows * DV + 32 * NWAVES;  // partial out + one lse per wave row
-  static_assert(TOK == 32 || TOK == 64, "a tile is a page or half a page");
+  static_assert(TOK == 32, "tiles of 32 tokens: two, one or half of them per page");
   static_assert(STAGES >= 3 && STAGES % 2 == 0, "PV stage + score stage + loading stages; even for the score register swap");
   static_assert(KS == 1 || (KS == 2 && DN == DV), "row slabs are split over 1 or 2 waves; the split is by state dims");
   static_assert(kStateLoads % (WPG * KS) == 0 && kRopeLoads % NWAVES == 0, "tile loads must split evenly over waves");
@@ -378,7 +376,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   constexpr int LPW = TT::kLoadsPerWave;
   constexpr int SLW = TT::kStateLoads / (WPG * KS);  // 1 KiB state blocks per wave and tile
   constexpr int RLW = TT::kRopeLoads / NWAVES;   // 1 KiB RoPE blocks per wave and tile
-  constexpr unsigned TPP = TT::kTilesPerPage;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[TT::kSmemBytes];
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
@@ -433,12 +430,13 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   int pt_vec = 0;
   int L_first;  // lengths of the first 64 sequences (0 beyond the batch), reused by the plan
   {
-    const int64_t tiles_full = (int64_t)p.max_pages * (int)TPP;
+    const int lgP_g = 31 - __builtin_clz((unsigned)p.P);
+    const int64_t tiles_full = (((int64_t)p.max_pages << lgP_g) + TOK - 1) / TOK;
     const int64_t total_g = (int64_t)p.B * UPB * tiles_full;
     const int64_t chunk_g = p.chunk_tiles > 0 ? p.chunk_tiles : (total_g + n_chunks - 1) / n_chunks;
     const int64_t c0_g = min((int64_t)chunk_id * chunk_g, total_g - 1);  // (chunks past the end: any valid row)
     const int b_g = (int)(c0_g / (UPB * tiles_full));
-    const int pg = (int)((c0_g % tiles_full) / (int)TPP);
+    const int pg = (int)(((c0_g % tiles_full) * TOK) >> lgP_g);
     const int32_t* ptr_pt = p.page_table + (int64_t)b_g * p.max_pages + min(pg + lane, p.max_pages - 1);
     const int32_t* ptr_len = p.seq_lens + (lane < p.B ? lane : 0);
     // both requests in flight together, both complete when the statement ends
@@ -485,8 +483,17 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   const unsigned r_lane_w = (unsigned)(r_rl * 128 + ((r_pc ^ (r_rl >> 1) ^ (((wave * RLW) & 1) << 2)) << 4));
   const uint32_t st_page_bytes = (uint32_t)p.st_s[0] * 2u, st_group_bytes = (uint32_t)p.st_s[1] * 2u;
   const uint32_t rp_page_bytes = (uint32_t)p.rp_s[0] * 2u;
-  const unsigned char* const state_w = (const unsigned char*)p.state + gl * (uint64_t)st_group_bytes + wpos * (SLW * 1024);
-  const unsigned char* const rope_w = (const unsigned char*)p.rope + wave * (RLW * 1024);
+  const unsigned char* const state_w = (const unsigned char*)p.state + gl * (uint64_t)st_group_bytes;
+  const unsigned char* const rope_w = (const unsigned char*)p.rope;
+  // Page sizes 64, 32 and 16 tokens: a tile of 32 tokens is half a page, a page
+  // or two pages.  The loads of a wave come in groups of up to four 1 KiB blocks
+  // (at most 16 token rows) and single 1 KiB RoPE blocks (8 token rows); such a
+  // run never straddles a page, so each has one base address, computed by the
+  // wave that issues it from the page id of its own rows.
+  const int lgP = 31 - __builtin_clz((unsigned)p.P);
+  constexpr int NSGW = (SLW + 3) / 4;                 // load groups of the state tile per wave
+  constexpr int GROWS = (SLW < 4 ? SLW : 4) * RPL;    // token rows per load group
+  static_assert(GROWS <= 16 && (16 % GROWS) == 0, "a load group stays inside a 16-token page");
   unsigned char* const lds_state_w = smem + gl * TT::kGroupBytes + wpos * (SLW * 1024);
   unsigned char* const lds_rope_w = smem + TT::kRopeBase + wave * (RLW * 1024);
 
@@ -495,8 +502,8 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   const unsigned char* pre_rp = nullptr;
   bool pre_page_valid = false;
   // addresses of the tile being issued (this wave's share)
-  const unsigned char* dma_s = nullptr;
-  const unsigned char* dma_r = nullptr;
+  const unsigned char* dma_s[NSGW] = {};
+  const unsigned char* dma_r[RLW] = {};
   unsigned char* dma_ls = nullptr;
   unsigned char* dma_lr = nullptr;
   int issued = 0;  // tiles whose loads have been issued
@@ -510,33 +517,59 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   // instead of running them in one stretch with the matrix pipe idle.
   bool prep_active = false, prep_need_page = false;
   unsigned prep_page_idx = 0, prep_tip = 0;
-  auto dma_prepare_0 = [&](int stage) {  // where to, and is a page id needed
+  auto dma_prepare_0 = [&](int stage) {  // where to, and are page ids needed
     dma_ls = lds_state_w + stage * STB;
     dma_lr = lds_rope_w + stage * RTB;
     prep_active = issued < n_tiles;
-    prep_page_idx = (unsigned)pre.j / TPP;
-    prep_tip = (unsigned)pre.j % TPP;  // tile within the page
-    prep_need_page = prep_active && (prep_tip == 0 || !pre_page_valid);
-    if (prep_need_page &&
-        (pre.b != pt_b || (int)prep_page_idx < pt_base || (int)prep_page_idx >= pt_base + 64)) {
+    const unsigned tok0 = (unsigned)pre.j * TOK;
+    prep_page_idx = tok0 >> lgP;                    // first page of the tile
+    prep_tip = (tok0 & ((unsigned)p.P - 1)) / TOK;  // tile within the page (pages of 64)
+    prep_need_page = prep_active && (lgP < 6 || prep_tip == 0 || !pre_page_valid);
+    const int last_idx = (int)((tok0 + TOK - 1) >> lgP);
+    if (prep_need_page && (pre.b != pt_b || (int)prep_page_idx < pt_base || last_idx >= pt_base + 64)) {
       pt_b = pre.b;
       pt_base = (int)prep_page_idx;
       const int idx = min((int)prep_page_idx + lane, p.max_pages - 1);
       pt_vec = load_i32_sync(p.page_table + (int64_t)pre.b * p.max_pages + idx);
     }
   };
-  auto dma_prepare_1 = [&]() {  // page id -> page base addresses
-    if (prep_need_page) {
+  auto dma_prepare_1 = [&]() {  // pages of 64: page id -> page base addresses (kept for the page's second tile)
+    if (prep_need_page && lgP == 6) {
       const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pt_vec, (int)prep_page_idx - pt_base);
       pre_sp = state_w + ((uint64_t)page * st_page_bytes + pre_goff);
       pre_rp = rope_w + (uint64_t)page * rp_page_bytes;
       pre_page_valid = true;
     }
   };
-  auto dma_prepare_2 = [&]() {  // tile addresses; advance the prefetch cursor
+  auto dma_prepare_2 = [&]() {  // base address of every load group; advance the prefetch cursor
     if (!prep_active) return;
-    dma_s = pre_sp + prep_tip * STB;
-    dma_r = pre_rp + prep_tip * RTB;
+    if (lgP == 6) {
+#pragma unroll
+      for (int gi = 0; gi < NSGW; ++gi) dma_s[gi] = pre_sp + prep_tip * STB + (wpos * SLW + 4 * gi) * 1024;
+#pragma unroll
+      for (int ir = 0; ir < RLW; ++ir) dma_r[ir] = pre_rp + prep_tip * RTB + (wave * RLW + ir) * 1024;
+    } else {
+      // Smaller pages: one page lookup per load group.  Rows past the end of the
+      // sequence may lie in a page the table does not hold: they are fetched from
+      // the sequence's last page instead (any finite-or-not data will do, those
+      // rows are masked and zeroed), never through an unused table entry.
+      const unsigned tok0 = (unsigned)pre.j * TOK, pmask = (unsigned)p.P - 1;
+      const int last_page = (pre.L - 1) >> lgP;
+#pragma unroll
+      for (int gi = 0; gi < NSGW; ++gi) {
+        const unsigned tok = tok0 + (unsigned)(wpos * SLW + 4 * gi) * RPL;
+        const int pi = min((int)(tok >> lgP), last_page);
+        const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pt_vec, pi - pt_base);
+        dma_s[gi] = state_w + ((uint64_t)page * st_page_bytes + pre_goff + (uint64_t)(tok & pmask) * ROWB);
+      }
+#pragma unroll
+      for (int ir = 0; ir < RLW; ++ir) {
+        const unsigned tok = tok0 + (unsigned)(wave * RLW + ir) * 8;
+        const int pi = min((int)(tok >> lgP), last_page);
+        const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pt_vec, pi - pt_base);
+        dma_r[ir] = rope_w + ((uint64_t)page * rp_page_bytes + (uint64_t)(tok & pmask) * 128);
+      }
+    }
     ++issued;
     if (++pre.j == pre.tiles_b) {
       pre.j = 0;
@@ -563,13 +596,13 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
 #ifndef GLA_EXPERIMENT_NO_TILE_LOADS
     if constexpr (i < SLW) {
       const unsigned voff = s_lane_w ^ ((unsigned)swz16(i * RPL) << 4);
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_s + (i / 4) * 4096 + voff),
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_s[i / 4] + voff),
                                        (lds_void_t*)(dma_ls + (i / 4) * 4096), 16, (i % 4) * 1024, 0);
     } else {
       constexpr int ir = i - SLW;
       const unsigned voff = r_lane_w ^ ((unsigned)(ir & 1) << 6);
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_r + (ir / 4) * 4096 + voff),
-                                       (lds_void_t*)(dma_lr + (ir / 4) * 4096), 16, (ir % 4) * 1024, 0);
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_r[ir] + voff),
+                                       (lds_void_t*)(dma_lr + ir * 1024), 16, 0, 0);
     }
 #endif
   };
@@ -1311,7 +1344,7 @@ constexpr int tuned_stages(int dv, int ng, int wpg, int ks) {
 }
 
 inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) {
-  if (p->page_size != kPage || p->d_rope != 64) return false;
+  if ((p->page_size != 64 && p->page_size != 32 && p->page_size != 16) || p->d_rope != 64) return false;
   if (!(p->softmax_scale > 0.f)) return false;  // row maxima are taken on the raw dot products
   if (!((!is_gta && (p->d_v == 256 || p->d_v == 512)) || (is_gta && p->d_v == 128))) return false;
   // layout the kernels assume: token rows contiguous, everything 16-byte aligned
@@ -1351,7 +1384,7 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
   plan->stages = stages;
   // the tile list holds each (sequence, group block) once; every chunk of it is
   // worked on by mb workgroups (one per row block), so the grid is num_chunks * mb
-  const int64_t max_tiles = (int64_t)p->max_pages_per_seq * (kPage / tok);
+  const int64_t max_tiles = ((int64_t)p->max_pages_per_seq * p->page_size + tok - 1) / tok;
   const int64_t bound = (int64_t)(plan->units / plan->mb) * max_tiles;
   if (bound * plan->mb > 0x3fffffff) return false;
   if (p->num_splits > 0) {

@@ -37,7 +37,7 @@ TUNED_SHAPES = {("gla", 256), ("gla", 512), ("gta", 128)}   # (kind, d_v) with a
 def impls_for(p):
     ok = tuned_available(p)
     # a shape that has a tuned kernel must really take it: no silent generic-only pass
-    if (p.kind, p.d_v) in TUNED_SHAPES and p.d_r == 64 and p.page_size == 64:
+    if (p.kind, p.d_v) in TUNED_SHAPES and p.d_r == 64 and p.page_size in (16, 32, 64):
         assert ok, "tuned kernel unexpectedly unavailable"
     return [GENERIC, TUNED] if ok else [GENERIC]
 
@@ -96,6 +96,28 @@ def test_gta_small(T):
                      d_v=128, seed=140 + T, num_pages=1024, poison_tail=True, extra_table_cols=1)
     for impl in impls_for(p):
         check_problem(p, impl=impl, what=f"gta T={T} impl={impl}")
+
+
+@pytest.mark.parametrize("page_size", [16, 32])
+@pytest.mark.parametrize("shape", ["gla2", "gla2_T4", "mla", "gta", "gla1_few"])
+def test_small_pages(shape, page_size):
+    """Pages of 32 and 16 tokens (a tile is one page / two pages): every wave
+    looks up the pages of its own rows; the last tile may reach past the last
+    page the table holds."""
+    lens = [0, 1, 15, 16, 17, 31, 33, 63, 64, 65, 130, 700, 1500]
+    kw = dict(seq_lens=lens, page_size=page_size, num_pages=2048, poison_tail=True, extra_table_cols=1)
+    if shape == "gla2":
+        p = make_problem("sp_gla2", T=1, h_q=128, h_c=2, d_v=256, seed=300 + page_size, **kw)
+    elif shape == "gla2_T4":
+        p = make_problem("sp_gla2_T4", T=4, h_q=128, h_c=2, d_v=256, seed=310 + page_size, **kw)
+    elif shape == "mla":
+        p = make_problem("sp_mla", T=1, h_q=128, h_c=1, d_v=512, seed=320 + page_size, **kw)
+    elif shape == "gta":
+        p = make_problem("sp_gta", kind="gta", T=2, h_q=32, h_c=4, d_v=128, seed=330 + page_size, **kw)
+    else:
+        p = make_problem("sp_gla1", T=1, h_q=16, h_c=1, d_v=256, seed=340 + page_size, **kw)
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, what=f"{shape} page {page_size} impl={impl}")
 
 
 def test_peaky_softmax_fp32_and_bf16_out():

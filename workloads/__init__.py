@@ -184,40 +184,44 @@ def uniform_lengths(n: int, lo: int, hi: int, seed: int) -> np.ndarray:
 
 
 def config(index: int, *, T: Optional[int] = None, draw: int = 0, batch: Optional[int] = None,
-           max_len: Optional[int] = None, page_offset: int = 0) -> DecodeProblem:
+           max_len: Optional[int] = None, page_offset: int = 0, page_size: int = 64) -> DecodeProblem:
     """BASELINE configuration `index` (0-based).  `draw` re-draws the values
     (seed offset) while the pool permutation stays that of draw 0, so draws
     placed at disjoint `page_offset`s share one pool; `batch` / `max_len` shrink
-    the problem for quick tests while keeping its head and cache shape."""
+    the problem for quick tests while keeping its head and cache shape; `page_size`
+    other than the stated 64 keeps the pool's byte size (more, smaller pages)."""
     seed = BASE_SEED + index + 1000 * draw
     tbl = dict(table_seed=BASE_SEED + index + 500, page_offset=page_offset)
+    if page_size != 64:
+        tbl["page_size"] = page_size
+    pool = POOL_PAGES * 64 // page_size
     if index == 0:
         return make_problem("tiny_gla2", seq_lens=[256] * (batch or 1), T=T or 1, h_q=16, h_c=2,
                             d_v=256, identity_table=True, seed=seed)
     if index == 1:
         L = min(8192, max_len or 8192)
         return make_problem("gla2_b64_l8192", seq_lens=[L] * (batch or 64), T=T or 1, h_q=128,
-                            h_c=2, d_v=256, num_pages=POOL_PAGES, seed=seed, **tbl)
+                            h_c=2, d_v=256, num_pages=pool, seed=seed, **tbl)
     if index == 2:
         L = min(16384, max_len or 16384)
         return make_problem("gla2_spec_b32_l16384", seq_lens=[L] * (batch or 32), T=T or 2,
-                            h_q=128, h_c=2, d_v=256, num_pages=POOL_PAGES, seed=seed, **tbl)
+                            h_q=128, h_c=2, d_v=256, num_pages=pool, seed=seed, **tbl)
     if index == 3:
         lens = log_uniform_lengths(batch or 128, 512, max_len or 32768, seed + 7)
         return make_problem("mla_ragged_b128", seq_lens=lens, T=T or 1, h_q=128, h_c=1,
-                            d_v=512, num_pages=POOL_PAGES, seed=seed, **tbl)
+                            d_v=512, num_pages=pool, seed=seed, **tbl)
     if index == 4:
         hi = max_len or 32768
         lens = uniform_lengths(batch or 128, min(4096, hi), hi, seed + 7)
         return make_problem("gta4_b128", kind="gta", seq_lens=lens, T=T or 1, h_q=32, h_c=4,
-                            d_v=128, num_pages=POOL_PAGES, seed=seed, **tbl)
+                            d_v=128, num_pages=pool, seed=seed, **tbl)
     if index == 5:
         # not one of the five stated configurations: the GLA-2 head shape on a ragged
         # batch of contexts up to 32K, for the q_len sweep (MFMA utilisation vs q_len)
         hi = max_len or 32768
         lens = uniform_lengths(batch or 64, min(4096, hi), hi, seed + 7)
         return make_problem("gla2_ragged_b64", seq_lens=lens, T=T or 1, h_q=128, h_c=2, d_v=256,
-                            num_pages=POOL_PAGES, seed=seed, **tbl)
+                            num_pages=pool, seed=seed, **tbl)
     raise ValueError(f"no config {index}")
 
 
@@ -244,8 +248,8 @@ def latency_workload(spec: str, *, shape: str = "gla2", T: int = 1, draw: int = 
     tbl = dict(table_seed=BASE_SEED + 577, page_offset=page_offset)
     if shape == "gla2":
         return make_problem(f"latency_gla2[{spec}]", seq_lens=lens, T=T, h_q=128, h_c=2, d_v=256,
-                            num_pages=POOL_PAGES, seed=seed, **tbl)
+                            num_pages=pool, seed=seed, **tbl)
     if shape == "mla":
         return make_problem(f"latency_mla[{spec}]", seq_lens=lens, T=T, h_q=128, h_c=1, d_v=512,
-                            num_pages=POOL_PAGES, seed=seed, **tbl)
+                            num_pages=pool, seed=seed, **tbl)
     raise ValueError(shape)
