@@ -175,6 +175,33 @@ def test_workspace_too_small_is_reported():
     assert e.value.status == gla.GLA_ERR_WORKSPACE_TOO_SMALL
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_seeded_random_shapes(case):
+    """Seeded sweep over head shapes, query lengths, page sizes, length mixes,
+    split counts, masks and output types; every case runs each available
+    implementation against the oracle."""
+    rng = np.random.default_rng(9000 + case)
+    shape = [("gla", 128, 2, 256), ("gla", 64, 2, 256), ("gla", 16, 1, 256), ("gla", 128, 1, 512),
+             ("gla", 32, 1, 512), ("gta", 32, 4, 128), ("gta", 64, 2, 128), ("gta", 8, 1, 128),
+             ("gla", 128, 4, 256), ("gta", 128, 4, 128)][case % 10]
+    kind, h_q, h_c, d_v = shape
+    T = int(rng.integers(1, 5))
+    B = int(rng.integers(1, 8))
+    lens = [int(x) for x in rng.choice([0, 1, 2, 31, 32, 33, 64, 65, 127, 300, 1000, 2500], size=B)]
+    lens[int(rng.integers(B))] = int(rng.integers(1, 3000))
+    page = int(rng.choice([16, 32, 64]))
+    causal = int(rng.integers(0, 2))
+    splits = int(rng.choice([0, 0, 1, 3, 16]))
+    out_dtype = torch.float32 if rng.integers(0, 2) else torch.bfloat16
+    p = make_problem(f"rand{case}", kind=kind, seq_lens=lens, T=T, h_q=h_q, h_c=h_c, d_v=d_v,
+                     page_size=page, num_pages=4096, seed=9100 + case, causal=causal,
+                     poison_tail=True, extra_table_cols=int(rng.integers(0, 3)))
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, num_splits=splits, out_dtype=out_dtype,
+                      what=f"case {case} {kind} h_q={h_q} h_c={h_c} d_v={d_v} T={T} lens={lens} page={page} "
+                           f"causal={causal} splits={splits} {out_dtype} impl={impl}")
+
+
 # ---------------------------------------------------------------- full sizes
 def sample_rows(p, n, seed):
     rng = np.random.default_rng(seed)
