@@ -6,6 +6,28 @@
 
 namespace gla {
 
+// Division of a 32-bit unsigned number by a divisor fixed on the host, as one
+// multiply-high and two shifts:  n / d == (t + ((n - t) >> s1)) >> s2  with
+// t = mulhi(n, m), exact for every n < 2^32 (round-up method: m = floor(2^32 *
+// (2^l - d) / d) + 1 with l = ceil(log2 d), s1 = min(l, 1), s2 = l - s1).
+struct FastDiv {
+  uint32_t m, s1, s2;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f = {0u, 0u, 0u};
+  if (d <= 1) return f;  // t = 0, q = n
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;
+  f.m = (uint32_t)(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+  f.s1 = 1;
+  f.s2 = l - 1;
+  return f;
+}
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv& f) {
+  const uint32_t t = __umulhi(n, f.m);
+  return (t + ((n - t) >> f.s1)) >> f.s2;
+}
+
 // Kernel-argument block: a flattened copy of the caller's parameter struct.
 struct DevParams {
   const uint16_t* q_nope;
@@ -33,6 +55,14 @@ struct DevParams {
   // tuned kernel: flat partition of all key tiles of the batch into chunks
   int32_t num_chunks;       // chunks of the tile list (the main kernel runs one workgroup per chunk and row block)
   int32_t chunk_tiles;      // > 0: fixed tiles per chunk; 0: ceil(total / num_chunks)
+  // tuned kernel: constants of the plan, worked out once on the host
+  int32_t mb;               // row blocks per group (workgroups per chunk)
+  int32_t upb;              // units (group blocks) per sequence
+  int32_t lg_page;          // log2(page size)
+  int32_t xcd_map;          // 1: grid is a multiple of 8 * mb, chunks are laid out per XCD
+  int32_t tiles_full;       // tiles of a sequence that fills its page-table row
+  int32_t chunk_guess;      // chunk length if every sequence did
+  FastDiv fd_mb, fd_chunks, fd_gq, fd_tiles_full, fd_units_full, fd_upb_mb;
 };
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t v) {

@@ -220,12 +220,17 @@ __device__ __forceinline__ float half_swap_sum(float x) {
   return a + b;
 }
 
-__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int o = __shfl_up(v, off, 64);
-    if (lane >= off) v += o;
-  }
+// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves
+// (no LDS round trips): shifts by 1, 2, 4, 8 inside each row of 16 lanes, then
+// the last lane of row 0 / 2 is broadcast into row 1 / 3 and lane 31 into the
+// upper half.  Lanes that receive nothing add zero.
+__device__ __forceinline__ int wave_incl_scan(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);  // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);  // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);  // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);  // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
   return v;
 }
 
@@ -244,21 +249,23 @@ struct TileCursor {
 };
 
 // Total number of tiles of the batch (every wave computes the same value).
+// incl0: inclusive prefix sums of the tile counts of the first 64 sequences.
 template <int TOK>
-__device__ __forceinline__ int total_tiles(const DevParams& p, int UPB, int lane, int L_first) {
-  int acc = tiles_of<TOK>(L_first) * UPB;  // L_first: this lane's length among the first 64 (0 beyond B)
+__device__ __forceinline__ int total_tiles(const DevParams& p, int UPB, int lane, int incl0) {
+  int total = __builtin_amdgcn_readlane(incl0, 63);
   for (int base = 64; base < p.B; base += 64) {
     const int idx = base + lane;
-    acc += idx < p.B ? tiles_of<TOK>(p.seq_lens[idx]) * UPB : 0;
+    const int w = idx < p.B ? tiles_of<TOK>(p.seq_lens[idx]) * UPB : 0;
+    total += __builtin_amdgcn_readlane(wave_incl_scan(w), 63);
   }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-  return uniform(acc);
+  return total;
 }
 
 // Locate flat tile index `pos` (< total): which sequence / unit / tile.
+// L_first / incl0: length and inclusive tile prefix of the first 64 sequences.
 template <int TOK>
-__device__ __forceinline__ TileCursor locate_tile(const DevParams& p, int UPB, int pos, int lane, int L_first) {
+__device__ __forceinline__ TileCursor locate_tile(const DevParams& p, int UPB, int pos, int lane, int L_first,
+                                                  int incl0) {
   TileCursor c = {0, 0, 0, 0, 0};
   int before = 0;
   for (int base = 0; base < p.B; base += 64) {
@@ -266,36 +273,23 @@ __device__ __forceinline__ TileCursor locate_tile(const DevParams& p, int UPB, i
     const int L = base == 0 ? L_first : (idx < p.B ? p.seq_lens[idx] : 0);
     const int tl = tiles_of<TOK>(L);
     const int w = tl * UPB;
-    const int incl = wave_incl_scan(w, lane) + before;
+    const int incl = (base == 0 ? incl0 : wave_incl_scan(w)) + before;
     const int excl = incl - w;
     const unsigned long long hit = __ballot(w > 0 && excl <= pos && pos < incl);
     if (hit) {
       const int src = __ffsll((long long)hit) - 1;
-      const int ex = __shfl(excl, src, 64);
-      c.tiles_b = uniform(__shfl(tl, src, 64));
-      c.L = uniform(__shfl(L, src, 64));
-      c.b = uniform(base + src);
-      const int rem = uniform(pos - ex);
-      c.ub = rem / c.tiles_b;
+      const int ex = __builtin_amdgcn_readlane(excl, src);
+      c.tiles_b = __builtin_amdgcn_readlane(tl, src);
+      c.L = __builtin_amdgcn_readlane(L, src);
+      c.b = base + src;
+      const int rem = pos - ex;
+      c.ub = (int)((unsigned)rem / (unsigned)c.tiles_b);
       c.j = rem - c.ub * c.tiles_b;
       return c;
     }
-    before = uniform(__shfl(incl, 63, 64));
+    before = __builtin_amdgcn_readlane(incl, 63);
   }
   return c;
-}
-
-// Flat index of the first tile of sequence b (sum over earlier sequences).
-template <int TOK>
-__device__ __forceinline__ int tiles_before(const DevParams& p, int UPB, int b, int lane) {
-  int acc = 0;
-  for (int base = 0; base < b; base += 64) {
-    const int idx = base + lane;
-    acc += idx < b ? tiles_of<TOK>(p.seq_lens[idx]) * UPB : 0;
-  }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-  return uniform(acc);
 }
 
 template <int TOK>
@@ -390,8 +384,8 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   const int hi = lane >> 5;   // which half of the contraction slots this lane feeds
 
   const int rows_group = p.g_q * p.T;
-  const int MB = (rows_group + 32 * WPG - 1) / (32 * WPG);  // row blocks per group
-  const int UPB = p.h_c / NG;                               // units (group blocks) per sequence
+  const int MB = p.mb;    // row blocks per group
+  const int UPB = p.upb;  // units (group blocks) per sequence
 #ifdef GLA_EXPERIMENT_TIMESTAMPS
   // experiment build: wall-clock stamps of workgroup phases, 8 per workgroup,
   // written 192 MiB into the workspace (the experiment passes a larger one)
@@ -409,15 +403,16 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   // so that the tiles the first one fetches are L2 hits for the others, and
   // every XCD gets a contiguous run of chunks (same page-table rows, same
   // queries).  Grids that do not divide evenly fall back to a plain order.
-  const int n_chunks = (int)gridDim.x / MB;  // the host launches n_chunks * MB workgroups
+  const int n_chunks = p.num_chunks;  // the host launches n_chunks * MB workgroups
   int chunk_id, mb_wg;
-  if ((int)gridDim.x % (8 * MB) == 0) {
+  if (p.xcd_map) {
     const int xcd = (int)blockIdx.x & 7, n = (int)blockIdx.x >> 3;
-    mb_wg = n % MB;
-    chunk_id = xcd * (n_chunks >> 3) + n / MB;
+    const int q = (int)fast_div((unsigned)n, p.fd_mb);
+    mb_wg = n - q * MB;
+    chunk_id = xcd * (n_chunks >> 3) + q;
   } else {
-    mb_wg = (int)blockIdx.x % MB;
-    chunk_id = (int)blockIdx.x / MB;
+    chunk_id = (int)fast_div(blockIdx.x, p.fd_mb);
+    mb_wg = (int)blockIdx.x - chunk_id * MB;
   }
 
   // ---- a guess, made before anything is known about the lengths: if every
@@ -430,13 +425,12 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   int pt_vec = 0;
   int L_first;  // lengths of the first 64 sequences (0 beyond the batch), reused by the plan
   {
-    const int lgP_g = 31 - __builtin_clz((unsigned)p.P);
-    const int64_t tiles_full = (((int64_t)p.max_pages << lgP_g) + TOK - 1) / TOK;
-    const int64_t total_g = (int64_t)p.B * UPB * tiles_full;
-    const int64_t chunk_g = p.chunk_tiles > 0 ? p.chunk_tiles : (total_g + n_chunks - 1) / n_chunks;
-    const int64_t c0_g = min((int64_t)chunk_id * chunk_g, total_g - 1);  // (chunks past the end: any valid row)
-    const int b_g = (int)(c0_g / (UPB * tiles_full));
-    const int pg = (int)(((c0_g % tiles_full) * TOK) >> lgP_g);
+    // (all products below stay under 2^30: the host refuses larger plans)
+    const unsigned total_g = (unsigned)p.B * (unsigned)UPB * (unsigned)p.tiles_full;
+    const unsigned c0_g = min((unsigned)chunk_id * (unsigned)p.chunk_guess, total_g - 1);  // (chunks past the end: any valid row)
+    const int b_g = (int)fast_div(c0_g, p.fd_units_full);
+    const unsigned j_g = c0_g - fast_div(c0_g, p.fd_tiles_full) * (unsigned)p.tiles_full;
+    const int pg = (int)((j_g * TOK) >> p.lg_page);
     const int32_t* ptr_pt = p.page_table + (int64_t)b_g * p.max_pages + min(pg + lane, p.max_pages - 1);
     const int32_t* ptr_len = p.seq_lens + (lane < p.B ? lane : 0);
     // both requests in flight together, both complete when the statement ends
@@ -450,18 +444,19 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   }
 
   // ---- plan: this workgroup's chunk [c0, c1) of the flat tile list
-  const int n_total = total_tiles<TOK>(p, UPB, lane, L_first);
+  const int incl0 = wave_incl_scan(tiles_of<TOK>(L_first) * UPB);
+  const int n_total = total_tiles<TOK>(p, UPB, lane, incl0);
   if (n_total <= 0) return;
   // Chunk i covers tiles [i * chunk, (i + 1) * chunk): a fixed length if the
   // caller chose a split count, else an equal share of the list.
-  const int chunk = p.chunk_tiles > 0 ? p.chunk_tiles : (n_total + n_chunks - 1) / n_chunks;
+  const int chunk = p.chunk_tiles > 0 ? p.chunk_tiles : (int)fast_div((unsigned)(n_total + n_chunks - 1), p.fd_chunks);
   auto chunk_start = [&](int i) -> int { return (int)min((int64_t)n_total, (int64_t)i * chunk); };
   const int c0 = chunk_start(chunk_id);
   const int c1 = chunk_start(chunk_id + 1);
   if (c0 >= c1) return;  // only chunks past the end of the list are empty: no unit spans them
   const int n_tiles = c1 - c0;
 
-  TileCursor cur = locate_tile<TOK>(p, UPB, c0, lane, L_first);  // compute position
+  TileCursor cur = locate_tile<TOK>(p, UPB, c0, lane, L_first, incl0);  // compute position
   TileCursor pre = cur;                                  // prefetch position
   GLA_STAMP(1);
 
@@ -490,7 +485,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   // (at most 16 token rows) and single 1 KiB RoPE blocks (8 token rows); such a
   // run never straddles a page, so each has one base address, computed by the
   // wave that issues it from the page id of its own rows.
-  const int lgP = 31 - __builtin_clz((unsigned)p.P);
+  const int lgP = p.lg_page;
   constexpr int NSGW = (SLW + 3) / 4;                 // load groups of the state tile per wave
   constexpr int GROWS = (SLW < 4 ? SLW : 4) * RPL;    // token rows per load group
   static_assert(GROWS <= 16 && (16 % GROWS) == 0, "a load group stays inside a 16-token page");
@@ -621,7 +616,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     const int R = (mb * WPG + wg) * 32 + col;
     row_valid = R < rows_group;
     const int Rc = row_valid ? R : rows_group - 1;
-    row_t = Rc / p.g_q;
+    row_t = (int)fast_div((unsigned)Rc, p.fd_gq);
     row_h = g * p.g_q + (Rc - row_t * p.g_q);
     row_b = cur.b;
     const uint16_t* qn_ptr = p.q_nope + row_b * p.qn_s[0] + row_t * p.qn_s[1] + row_h * p.qn_s[2] + kx * DNW + 8 * hi;
@@ -1197,12 +1192,12 @@ __global__ __launch_bounds__(64 * KW) void tuned_combine_kernel(DevParams p) {
   const int w = wv / NDB, db = wv - w * NDB;  // wave of the main kernel and one of its 32-dim blocks
   const int wpos = w % (WPG * KS), kx = wpos % KS;
   const int rows_group = p.g_q * p.T;
-  const int MB = (rows_group + 32 * WPG - 1) / (32 * WPG);
-  const int UPB = (p.h_c / NG) * MB;
+  const int MB = p.mb;
+  const int UPB = p.upb * MB;
   const int unit = blockIdx.x;  // (sequence, group block, row block)
-  const int b = unit / UPB;
+  const int b = (int)fast_div((unsigned)unit, p.fd_upb_mb);
   const int ub = unit - b * UPB;
-  const int gb = ub / MB, mb = ub - gb * MB;
+  const int gb = (int)fast_div((unsigned)ub, p.fd_mb), mb = ub - gb * MB;
   const int L = p.seq_lens[b];
   const int2 span = ((const int2*)p.ws_lse)[unit];  // garbage for units without tiles: not used then
   const bool empty = tiles_of<TOK>(L) == 0;
@@ -1211,7 +1206,7 @@ __global__ __launch_bounds__(64 * KW) void tuned_combine_kernel(DevParams p) {
   const int R = (mb * WPG + wpos / KS) * 32 + col;
   const bool valid = R < rows_group;
   const int Rc = valid ? R : 0;
-  const int t = Rc / p.g_q;
+  const int t = (int)fast_div((unsigned)Rc, p.fd_gq);
   const int h = g * p.g_q + (Rc - t * p.g_q);
   const int r = w * 32 + col;  // this lane's entry among the slot's log-sum-exps
   // Chunk span.x holds the unit's first tile (partial slot 1); every later
@@ -1471,6 +1466,25 @@ inline int tuned_launch(const gla_decode_params* p, int is_gta, DevParams& d, hi
   d.ws_lse = (float*)((char*)p->workspace + tuned_slots_bytes(plan));  // per-unit chunk ranges (int32 pairs)
   d.num_chunks = plan.num_chunks;
   d.chunk_tiles = plan.chunk_tiles;
+  {
+    const int g_q = p->num_q_heads / p->num_groups;
+    int lg = 0;
+    while ((1 << lg) < p->page_size) ++lg;
+    d.mb = plan.mb;
+    d.upb = p->num_groups / plan.ng;
+    d.lg_page = lg;
+    d.xcd_map = (plan.num_chunks * plan.mb) % (8 * plan.mb) == 0 ? 1 : 0;
+    d.tiles_full = (int)(((int64_t)p->max_pages_per_seq * p->page_size + plan.tok - 1) / plan.tok);
+    const int64_t total_full = (int64_t)p->batch * d.upb * d.tiles_full;
+    d.chunk_guess = plan.chunk_tiles > 0 ? plan.chunk_tiles
+                                         : (int)((total_full + plan.num_chunks - 1) / plan.num_chunks);
+    d.fd_mb = make_fastdiv((uint32_t)plan.mb);
+    d.fd_chunks = make_fastdiv((uint32_t)plan.num_chunks);
+    d.fd_gq = make_fastdiv((uint32_t)g_q);
+    d.fd_tiles_full = make_fastdiv((uint32_t)d.tiles_full);
+    d.fd_units_full = make_fastdiv((uint32_t)(d.upb * d.tiles_full));
+    d.fd_upb_mb = make_fastdiv((uint32_t)(d.upb * plan.mb));
+  }
   if (plan.dv == 256 && plan.dn == 256) return launch_tuned_shape<256, 256>(plan, d, st, ev);
   if (plan.dv == 128 && plan.dn == 64) return launch_tuned_shape<128, 64>(plan, d, st, ev);
   if (plan.dv == 512 && plan.dn == 512) return launch_tuned_shape<512, 512>(plan, d, st, ev);
