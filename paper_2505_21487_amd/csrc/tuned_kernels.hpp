@@ -1,19 +1,22 @@
 // Tuned decode-attention path for gfx950: split-KV main kernel on bf16 MFMA
 // with LDS-staged page tiles, plus the merge kernel for its partial results.
 //
-// Work decomposition.  A workgroup has NG * WPG waves: it serves NG groups
-// (latent heads / tied KV heads) at once with WPG waves of 32 query rows each
-// per group, so that the RoPE-key tile, which all groups share, is fetched once
-// for all of them.  A "unit" is (sequence b, group block gb, row block mb): the
-// g_q * T query rows of each group (ordered t-major) are cut into blocks of
-// 32 * WPG rows, the h_c groups into blocks of NG.  A unit owns ceil(L_b / TOK)
-// key tiles of TOK tokens (a page of 64 tokens or half of one); a tile is the
-// NG state tiles of its groups plus one RoPE tile.  All tiles of all units, in unit order,
-// form one flat list that is cut into equal chunks, one workgroup per chunk, so
-// ragged batches balance by construction and at most two units per chunk are
-// left incomplete.  A unit that lies inside one chunk is written straight to
-// the output; one that spans chunks leaves one partial (normalised fp32 output
-// + log-sum-exp) per chunk in the workspace, merged by tuned_combine_kernel.
+// Work decomposition.  A workgroup has NG * WPG * KS waves: it serves NG groups
+// (latent heads / tied KV heads) at once with WPG slabs of 32 query rows per
+// group, so that the RoPE-key tile, which all groups share, is fetched once
+// for all of them; KS = 2 waves share a slab when the state has 512 dims (each
+// takes half of the dims, see the score exchange below).  The g_q * T query
+// rows of a group (ordered t-major) are cut into row blocks of 32 * WPG rows,
+// the h_c groups into blocks of NG.  A "unit" of the work list is (sequence b,
+// group block gb): it owns ceil(L_b / TOK) key tiles of TOK = 32 tokens (half
+// a page, a page or two pages for page sizes 64, 32, 16); a tile is the NG
+// state tiles of its groups plus one RoPE tile.  All tiles of all units, in
+// unit order, form one flat list that is cut into equal chunks, so ragged
+// batches balance by construction and at most two units per chunk are left
+// incomplete.  A chunk is worked on by one workgroup per row block.  A (unit,
+// row block) that lies inside one chunk is written straight to the output; one
+// that spans chunks leaves one partial (normalised fp32 output + log-sum-exp)
+// per chunk in the workspace, merged by tuned_combine_kernel.
 //
 // Inside a workgroup every wave owns 32 query rows and works in the transposed
 // form: S^T = K . Q^T with the key tile as the MFMA A operand (from LDS) and
@@ -1033,10 +1036,8 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       l_run = 0.f;
       // visible keys of this lane's row; padding rows are left unmasked (never stored)
       n_vis = row_valid ? (p.causal ? cur.L - p.T + 1 + row_t : cur.L) : 0x7fffffff;
-      int mn = n_vis;
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) mn = min(mn, __shfl_xor(mn, off, 64));
-      n_vis_min = uniform(mn);
+      // the smallest count of the wave: its first row (lane 0) has the earliest query position
+      n_vis_min = __builtin_amdgcn_readlane(n_vis, 0);
     }
 
     // ---- segment prologue: point the address registers at the stages of tile k
