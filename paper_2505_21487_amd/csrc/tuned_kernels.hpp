@@ -351,7 +351,9 @@ struct TunedTraits {
   static_assert(kSmemBytes <= 160 * 1024, "LDS capacity");
 };
 
-template <int DV, int DN, int DR, int NG, int WPG, int KS, int TOK, int STAGES>
+// PG64: the cache has pages of 64 tokens (a tile is half a page and the
+// small-page address code is compiled out); otherwise pages of 32 or 16.
+template <int DV, int DN, int DR, int NG, int WPG, int KS, int TOK, int STAGES, bool PG64>
 __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParams p) {
   using TT = TunedTraits<DV, DN, DR, NG, WPG, KS, TOK, STAGES>;
   constexpr int NWAVES = NG * WPG * KS;
@@ -433,7 +435,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     const unsigned c0_g = min((unsigned)chunk_id * (unsigned)p.chunk_guess, total_g - 1);  // (chunks past the end: any valid row)
     const int b_g = (int)fast_div(c0_g, p.fd_units_full);
     const unsigned j_g = c0_g - fast_div(c0_g, p.fd_tiles_full) * (unsigned)p.tiles_full;
-    const int pg = (int)((j_g * TOK) >> p.lg_page);
+    const int pg = (int)((j_g * TOK) >> (PG64 ? 6 : p.lg_page));
     const int32_t* ptr_pt = p.page_table + (int64_t)b_g * p.max_pages + min(pg + lane, p.max_pages - 1);
     const int32_t* ptr_len = p.seq_lens + (lane < p.B ? lane : 0);
     // both requests in flight together, both complete when the statement ends
@@ -488,7 +490,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   // (at most 16 token rows) and single 1 KiB RoPE blocks (8 token rows); such a
   // run never straddles a page, so each has one base address, computed by the
   // wave that issues it from the page id of its own rows.
-  const int lgP = p.lg_page;
+  const int lgP = PG64 ? 6 : p.lg_page;
   constexpr int NSGW = (SLW + 3) / 4;                 // load groups of the state tile per wave
   constexpr int GROWS = (SLW < 4 ? SLW : 4) * RPL;    // token rows per load group
   static_assert(GROWS <= 16 && (16 % GROWS) == 0, "a load group stays inside a 16-token page");
@@ -521,7 +523,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     prep_active = issued < n_tiles;
     const unsigned tok0 = (unsigned)pre.j * TOK;
     prep_page_idx = tok0 >> lgP;                    // first page of the tile
-    prep_tip = (tok0 & ((unsigned)p.P - 1)) / TOK;  // tile within the page (pages of 64)
+    prep_tip = (tok0 & ((1u << lgP) - 1)) / TOK;  // tile within the page (pages of 64)
     prep_need_page = prep_active && (lgP < 6 || prep_tip == 0 || !pre_page_valid);
     const int last_idx = (int)((tok0 + TOK - 1) >> lgP);
     if (prep_need_page && (pre.b != pt_b || (int)prep_page_idx < pt_base || last_idx >= pt_base + 64)) {
@@ -551,7 +553,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       // sequence may lie in a page the table does not hold: they are fetched from
       // the sequence's last page instead (any finite-or-not data will do, those
       // rows are masked and zeroed), never through an unused table entry.
-      const unsigned tok0 = (unsigned)pre.j * TOK, pmask = (unsigned)p.P - 1;
+      const unsigned tok0 = (unsigned)pre.j * TOK, pmask = (1u << lgP) - 1;
       const int last_page = (pre.L - 1) >> lgP;
 #pragma unroll
       for (int gi = 0; gi < NSGW; ++gi) {
@@ -1418,8 +1420,11 @@ inline size_t tuned_workspace(const gla_decode_params* p, int is_gta) {
 template <int DV, int DN, int NG, int WPG, int KS, int TOK, int STAGES>
 inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
   if (ev) (void)hipEventRecord(ev[0], st);
-  hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES>), dim3(plan.num_chunks * plan.mb),
-                     dim3(64 * NG * WPG * KS), 0, st, d);
+  const dim3 mgrid(plan.num_chunks * plan.mb), mblock(64 * NG * WPG * KS);
+  if (d.lg_page == 6)
+    hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, true>), mgrid, mblock, 0, st, d);
+  else
+    hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, false>), mgrid, mblock, 0, st, d);
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[1], st);
   // waves per merge task from the expected number of chunks per unit
