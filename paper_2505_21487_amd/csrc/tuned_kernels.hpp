@@ -351,12 +351,20 @@ struct TunedTraits {
   static_assert(kSmemBytes <= 160 * 1024, "LDS capacity");
 };
 
-// PG64: the cache has pages of 64 tokens (a tile is half a page and the
-// small-page address code is compiled out); otherwise pages of 32 or 16.
-template <int DV, int DN, int DR, int NG, int WPG, int KS, int TOK, int STAGES, bool PG64>
+// PM, the page mode, selects the address code of the tile loads:
+//   0: pages of 64 tokens (a tile is half a page: one base address per tile),
+//   1: pages of 32 or 16 tokens (one base address per run of up to 16 rows),
+//   2: pages of 8, 4, 2 or 1 tokens (one address per row and lane, from page ids
+//      that each wave keeps in a window of the page table in LDS).
+constexpr int kPageWindow = 256;  // page-table entries per window (PM == 2)
+template <int DV, int DN, int DR, int NG, int WPG, int KS, int TOK, int STAGES, int PM>
 __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParams p) {
   using TT = TunedTraits<DV, DN, DR, NG, WPG, KS, TOK, STAGES>;
   constexpr int NWAVES = NG * WPG * KS;
+  constexpr bool kLane = PM == 2;
+  constexpr int kWinBase = TT::kSmemBytes;                                     // two windows per wave
+  constexpr int kSmemAll = TT::kSmemBytes + (kLane ? NWAVES * 2 * kPageWindow * 4 : 0);
+  static_assert(kSmemAll <= 160 * 1024, "LDS capacity");
   constexpr int ROWB = TT::kRowBytes;
   constexpr int STB = TT::kStateBytes;   // state tile bytes
   constexpr int RTB = TT::kRopeBytes;    // RoPE tile bytes
@@ -375,7 +383,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   constexpr int LPW = TT::kLoadsPerWave;
   constexpr int SLW = TT::kStateLoads / (WPG * KS);  // 1 KiB state blocks per wave and tile
   constexpr int RLW = TT::kRopeLoads / NWAVES;   // 1 KiB RoPE blocks per wave and tile
-  __shared__ __attribute__((aligned(1024))) unsigned char smem[TT::kSmemBytes];
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kSmemAll];
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
   const int tid = threadIdx.x;
@@ -435,7 +443,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     const unsigned c0_g = min((unsigned)chunk_id * (unsigned)p.chunk_guess, total_g - 1);  // (chunks past the end: any valid row)
     const int b_g = (int)fast_div(c0_g, p.fd_units_full);
     const unsigned j_g = c0_g - fast_div(c0_g, p.fd_tiles_full) * (unsigned)p.tiles_full;
-    const int pg = (int)((j_g * TOK) >> (PG64 ? 6 : p.lg_page));
+    const int pg = (int)((j_g * TOK) >> (PM == 0 ? 6 : p.lg_page));
     const int32_t* ptr_pt = p.page_table + (int64_t)b_g * p.max_pages + min(pg + lane, p.max_pages - 1);
     const int32_t* ptr_len = p.seq_lens + (lane < p.B ? lane : 0);
     // both requests in flight together, both complete when the statement ends
@@ -490,7 +498,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   // (at most 16 token rows) and single 1 KiB RoPE blocks (8 token rows); such a
   // run never straddles a page, so each has one base address, computed by the
   // wave that issues it from the page id of its own rows.
-  const int lgP = PG64 ? 6 : p.lg_page;
+  const int lgP = PM == 0 ? 6 : p.lg_page;
   constexpr int NSGW = (SLW + 3) / 4;                 // load groups of the state tile per wave
   constexpr int GROWS = (SLW < 4 ? SLW : 4) * RPL;    // token rows per load group
   static_assert(GROWS <= 16 && (16 % GROWS) == 0, "a load group stays inside a 16-token page");
@@ -507,6 +515,28 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   unsigned char* dma_ls = nullptr;
   unsigned char* dma_lr = nullptr;
   int issued = 0;  // tiles whose loads have been issued
+  // PM == 2, pages of 8 tokens or fewer: every token row of a load may lie in
+  // its own page, so each lane forms the address of the row it fetches, from
+  // the page id of that row.  The ids come from LDS: every wave keeps two
+  // windows of kPageWindow consecutive page-table entries of the sequence it is
+  // fetching, the one in use and the one after it, requested (direct to LDS)
+  // when the first is entered, so a window has long arrived when the prefetch
+  // cursor reaches it.  Only the first window of a sequence, and windows
+  // entered within a few tiles of their request, are waited for.
+  unsigned char* const win_w = smem + kWinBase + wave * (2 * kPageWindow * 4);
+  int win_b = -1, win_id0 = -1, win_id1 = -1, win_at0 = 0, win_at1 = 0, win_sel = 0;
+  int pg_s[SLW] = {}, pg_r[RLW] = {};  // page id of this lane's row, per load of the prepared tile
+  uint64_t dma_goff = 0;               // group-block offset the prepared tile's addresses use
+  unsigned dma_pmask = 0;
+  auto win_fetch = [&](int slot, int b_seq, int id, int last_page) {
+    // entries [id * kPageWindow, +kPageWindow) of row b_seq, those past the last held page replaced by it
+    const int32_t* row = p.page_table + (int64_t)b_seq * p.max_pages;
+#pragma unroll
+    for (int i = 0; i < kPageWindow / 64; ++i) {
+      const int e = min(id * kPageWindow + i * 64 + lane, last_page);
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(row + e), (lds_void_t*)(win_w + slot * (kPageWindow * 4) + i * 256), 4, 0, 0);
+    }
+  };
 
   // Prepare the loads of the next tile into `stage`.  Once every tile of the
   // chunk has been issued the previous tile's addresses are kept: the loads
@@ -526,7 +556,30 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     prep_tip = (tok0 & ((1u << lgP) - 1)) / TOK;  // tile within the page (pages of 64)
     prep_need_page = prep_active && (lgP < 6 || prep_tip == 0 || !pre_page_valid);
     const int last_idx = (int)((tok0 + TOK - 1) >> lgP);
-    if (prep_need_page && (pre.b != pt_b || (int)prep_page_idx < pt_base || last_idx >= pt_base + 64)) {
+    if constexpr (kLane) {
+      if (prep_active) {
+        const int last_page = (pre.L - 1) >> lgP;
+        const int want = (int)prep_page_idx / kPageWindow;
+        if (pre.b != win_b || (want != win_id0 && want != win_id1)) {
+          win_b = pre.b;
+          win_id0 = want;
+          win_id1 = -1;
+          win_sel = 0;
+          win_fetch(0, pre.b, want, last_page);
+          wait_vmcnt<0>();
+          win_at0 = issued - STAGES;
+        } else {
+          win_sel = want == win_id1 ? 1 : 0;
+          // requested too recently for the rolling waits of the tile loop to have covered it
+          if (issued - (win_sel ? win_at1 : win_at0) < STAGES) wait_vmcnt<0>();
+        }
+        const int nxt = want + 1;
+        if (nxt * kPageWindow <= last_page && (win_sel ? win_id0 : win_id1) != nxt) {
+          if (win_sel) { win_id0 = nxt; win_at0 = issued; } else { win_id1 = nxt; win_at1 = issued; }
+          win_fetch(win_sel ^ 1, pre.b, nxt, last_page);
+        }
+      }
+    } else if (prep_need_page && (pre.b != pt_b || (int)prep_page_idx < pt_base || last_idx >= pt_base + 64)) {
       pt_b = pre.b;
       pt_base = (int)prep_page_idx;
       const int idx = min((int)prep_page_idx + lane, p.max_pages - 1);
@@ -543,7 +596,25 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   };
   auto dma_prepare_2 = [&]() {  // base address of every load group; advance the prefetch cursor
     if (!prep_active) return;
-    if (lgP == 6) {
+    if constexpr (kLane) {
+      const unsigned tok0 = (unsigned)pre.j * TOK;
+      const int last_page = (pre.L - 1) >> lgP;
+      const unsigned char* const win = win_w + win_sel * (kPageWindow * 4);
+#pragma unroll
+      for (int i = 0; i < SLW; ++i) {
+        const unsigned rho = (unsigned)((wpos * SLW + i) * RPL + s_rl);
+        const int e = min((int)((tok0 + rho) >> lgP), last_page);
+        pg_s[i] = *reinterpret_cast<const int*>(win + (e & (kPageWindow - 1)) * 4);
+      }
+#pragma unroll
+      for (int ir = 0; ir < RLW; ++ir) {
+        const unsigned rho = (unsigned)((wave * RLW + ir) * 8 + r_rl);
+        const int e = min((int)((tok0 + rho) >> lgP), last_page);
+        pg_r[ir] = *reinterpret_cast<const int*>(win + (e & (kPageWindow - 1)) * 4);
+      }
+      dma_goff = pre_goff;
+      dma_pmask = (1u << lgP) - 1;
+    } else if (lgP == 6) {
 #pragma unroll
       for (int gi = 0; gi < NSGW; ++gi) dma_s[gi] = pre_sp + prep_tip * STB + (wpos * SLW + 4 * gi) * 1024;
 #pragma unroll
@@ -594,7 +665,24 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   auto dma_load = [&](auto ic) {
     constexpr int i = decltype(ic)::value;
 #ifndef GLA_EXPERIMENT_NO_TILE_LOADS
-    if constexpr (i < SLW) {
+    if constexpr (kLane) {
+      // address of this lane's row: page base + row within the page + the chunk
+      // of the row whose swizzled home is this lane's LDS slot
+      if constexpr (i < SLW) {
+        const unsigned voff = s_lane_w ^ ((unsigned)swz16(i * RPL) << 4);
+        const unsigned rho = (unsigned)((wpos * SLW + i) * RPL + s_rl);
+        const unsigned off = (rho & dma_pmask) * ROWB + (voff & (ROWB - 1));
+        const unsigned char* src = state_w + ((uint64_t)(uint32_t)pg_s[i] * st_page_bytes + dma_goff + off);
+        __builtin_amdgcn_global_load_lds((global_cvoid_t*)src, (lds_void_t*)(dma_ls + i * 1024), 16, 0, 0);
+      } else {
+        constexpr int ir = i - SLW;
+        const unsigned voff = r_lane_w ^ ((unsigned)(ir & 1) << 6);
+        const unsigned rho = (unsigned)((wave * RLW + ir) * 8 + r_rl);
+        const unsigned off = (rho & dma_pmask) * 128 + (voff & 127);
+        const unsigned char* src = rope_w + ((uint64_t)(uint32_t)pg_r[ir] * rp_page_bytes + off);
+        __builtin_amdgcn_global_load_lds((global_cvoid_t*)src, (lds_void_t*)(dma_lr + ir * 1024), 16, 0, 0);
+      }
+    } else if constexpr (i < SLW) {
       const unsigned voff = s_lane_w ^ ((unsigned)swz16(i * RPL) << 4);
       __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_s[i / 4] + voff),
                                        (lds_void_t*)(dma_ls + (i / 4) * 4096), 16, (i % 4) * 1024, 0);
@@ -1332,9 +1420,10 @@ inline bool aligned16(const void* ptr) { return ((uintptr_t)ptr & 15u) == 0; }
 // wave stay countable by the 6-bit vmcnt.
 constexpr int kTok = 32;
 constexpr int kMinChunkTiles = 4;
-constexpr int tuned_stages(int dv, int ng, int wpg, int ks) {
+constexpr int tuned_stages(int dv, int ng, int wpg, int ks, bool lane = false) {
   const int stage_bytes = ng * kTok * dv * 2 + kTok * 128;
-  const int mailboxes = ks > 1 ? ng * wpg * ks * 4096 : 0;
+  // besides the tiles: score mailboxes (ks > 1), page-id windows (pages of 8 tokens or fewer)
+  const int mailboxes = (ks > 1 ? ng * wpg * ks * 4096 : 0) + (lane ? ng * wpg * ks * 2 * kPageWindow * 4 : 0);
   const int loads_per_wave = (kTok * dv * 2 / 1024) / (wpg * ks) + (kTok * 128 / 1024) / (ng * wpg * ks);
   int st = 8;
   while (st > 4 && (st * stage_bytes + mailboxes > 160 * 1024 || loads_per_wave * (st - 2) > 63)) st -= 2;
@@ -1342,7 +1431,9 @@ constexpr int tuned_stages(int dv, int ng, int wpg, int ks) {
 }
 
 inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) {
-  if ((p->page_size != 64 && p->page_size != 32 && p->page_size != 16) || p->d_rope != 64) return false;
+  const int ps = p->page_size;
+  if (ps < 1 || ps > 64 || (ps & (ps - 1)) || p->d_rope != 64) return false;  // 64, 32, ..., 1 tokens
+  const bool lane = ps < 16;  // addresses per row and lane
   if (!(p->softmax_scale > 0.f)) return false;  // row maxima are taken on the raw dot products
   if (!((!is_gta && (p->d_v == 256 || p->d_v == 512)) || (is_gta && p->d_v == 128))) return false;
   // layout the kernels assume: token rows contiguous, everything 16-byte aligned
@@ -1374,9 +1465,11 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
   plan->rows = 32 * ng * wpg;
   plan->mb = (rows_group + 32 * wpg - 1) / (32 * wpg);
   plan->units = p->batch * (p->num_groups / ng) * plan->mb;
-  const int tok = kTok, stages = tuned_stages(p->d_v, ng, wpg, ks);
+  const int tok = kTok, stages = tuned_stages(p->d_v, ng, wpg, ks, lane);
   // co-resident workgroups per CU: one wave per SIMD, 160 KiB of LDS
-  const int smem = stages * (ng * tok * p->d_v * 2 + tok * 128) + (ks > 1 ? ng * wpg * ks * 4096 : 0);
+  const int smem = stages * (ng * tok * p->d_v * 2 + tok * 128) + (ks > 1 ? ng * wpg * ks * 4096 : 0) +
+                   (lane ? ng * wpg * ks * 2 * kPageWindow * 4 : 0);
+  if (smem > 160 * 1024) return false;  // (512-dim latent, two row slabs, small pages: no room for the page-id windows)
   const int per_cu = std::max(1, std::min((160 * 1024) / smem, 4 / (ng * wpg * ks)));
   plan->tok = tok;
   plan->stages = stages;
@@ -1417,14 +1510,23 @@ inline size_t tuned_workspace(const gla_decode_params* p, int is_gta) {
   return tuned_slots_bytes(plan) + (size_t)plan.units * 2 * sizeof(int32_t);
 }
 
-template <int DV, int DN, int NG, int WPG, int KS, int TOK, int STAGES>
+template <int DV, int DN, int NG, int WPG, int KS, int TOK>
 inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
+  constexpr int STAGES = tuned_stages(DV, NG, WPG, KS), STAGES_LANE = tuned_stages(DV, NG, WPG, KS, true);
+  constexpr bool kLaneFits = STAGES_LANE * (NG * TOK * DV * 2 + TOK * 128) + (KS > 1 ? NG * WPG * KS * 4096 : 0) +
+                             NG * WPG * KS * 2 * kPageWindow * 4 <= 160 * 1024;
   if (ev) (void)hipEventRecord(ev[0], st);
   const dim3 mgrid(plan.num_chunks * plan.mb), mblock(64 * NG * WPG * KS);
-  if (d.lg_page == 6)
-    hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, true>), mgrid, mblock, 0, st, d);
-  else
-    hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, false>), mgrid, mblock, 0, st, d);
+  if (d.lg_page == 6) {
+    hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, 0>), mgrid, mblock, 0, st, d);
+  } else if (d.lg_page >= 4) {
+    hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, 1>), mgrid, mblock, 0, st, d);
+  } else {
+    if constexpr (kLaneFits)
+      hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES_LANE, 2>), mgrid, mblock, 0, st, d);
+    else
+      return GLA_ERR_UNSUPPORTED_SHAPE;  // (the planner does not choose this variant for small pages)
+  }
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[1], st);
   // waves per merge task from the expected number of chunks per unit
@@ -1445,19 +1547,19 @@ template <int DV, int DN>
 inline int launch_tuned_shape(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
   if constexpr (DV > 256) {
     switch (plan.ng * 100 + plan.wpg * 10 + plan.ks) {
-      case 112: return launch_tuned_variant<DV, DN, 1, 1, 2, kTok, tuned_stages(DV, 1, 1, 2)>(plan, d, st, ev);
-      case 122: return launch_tuned_variant<DV, DN, 1, 2, 2, kTok, tuned_stages(DV, 1, 2, 2)>(plan, d, st, ev);
+      case 112: return launch_tuned_variant<DV, DN, 1, 1, 2, kTok>(plan, d, st, ev);
+      case 122: return launch_tuned_variant<DV, DN, 1, 2, 2, kTok>(plan, d, st, ev);
       default: return GLA_ERR_UNSUPPORTED_SHAPE;
     }
   } else {
     switch (plan.ng * 100 + plan.wpg * 10 + plan.ks) {
-      case 111: return launch_tuned_variant<DV, DN, 1, 1, 1, kTok, tuned_stages(DV, 1, 1, 1)>(plan, d, st, ev);
-      case 121: return launch_tuned_variant<DV, DN, 1, 2, 1, kTok, tuned_stages(DV, 1, 2, 1)>(plan, d, st, ev);
-      case 141: return launch_tuned_variant<DV, DN, 1, 4, 1, kTok, tuned_stages(DV, 1, 4, 1)>(plan, d, st, ev);
-      case 211: return launch_tuned_variant<DV, DN, 2, 1, 1, kTok, tuned_stages(DV, 2, 1, 1)>(plan, d, st, ev);
-      case 221: return launch_tuned_variant<DV, DN, 2, 2, 1, kTok, tuned_stages(DV, 2, 2, 1)>(plan, d, st, ev);
+      case 111: return launch_tuned_variant<DV, DN, 1, 1, 1, kTok>(plan, d, st, ev);
+      case 121: return launch_tuned_variant<DV, DN, 1, 2, 1, kTok>(plan, d, st, ev);
+      case 141: return launch_tuned_variant<DV, DN, 1, 4, 1, kTok>(plan, d, st, ev);
+      case 211: return launch_tuned_variant<DV, DN, 2, 1, 1, kTok>(plan, d, st, ev);
+      case 221: return launch_tuned_variant<DV, DN, 2, 2, 1, kTok>(plan, d, st, ev);
       case 411:
-        if constexpr (DV <= 128) return launch_tuned_variant<DV, DN, 4, 1, 1, kTok, tuned_stages(DV, 4, 1, 1)>(plan, d, st, ev);
+        if constexpr (DV <= 128) return launch_tuned_variant<DV, DN, 4, 1, 1, kTok>(plan, d, st, ev);
         else return GLA_ERR_UNSUPPORTED_SHAPE;
       default: return GLA_ERR_UNSUPPORTED_SHAPE;
     }

@@ -12,7 +12,7 @@ class DeviceProblem:
 
     def __init__(self, p, device="cuda:0", pool=None, poison_unused=False):
         """poison_unused: fill the whole pool with NaN before the used pages are
-        written (small pools only), so that a read of any other page shows."""
+        written (pools of up to a million tokens only), so that a read of any other page shows."""
         dev = torch.device(device)
         self.p = p
         self.q_nope = p.q_nope.to(dev)
@@ -20,7 +20,7 @@ class DeviceProblem:
         if pool is None:
             state = torch.empty(p.num_pages, p.h_c, p.page_size, p.d_v, dtype=torch.bfloat16, device=dev)
             rope = torch.empty(p.num_pages, p.page_size, p.d_r, dtype=torch.bfloat16, device=dev)
-            if poison_unused and p.num_pages <= 16384:
+            if poison_unused and p.num_pages * p.page_size <= 16384 * 64:
                 state.fill_(float("nan"))
                 rope.fill_(float("nan"))
         else:

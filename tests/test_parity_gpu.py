@@ -37,8 +37,11 @@ TUNED_SHAPES = {("gla", 256), ("gla", 512), ("gta", 128)}   # (kind, d_v) with a
 def impls_for(p):
     ok = tuned_available(p)
     # a shape that has a tuned kernel must really take it: no silent generic-only pass
-    if (p.kind, p.d_v) in TUNED_SHAPES and p.d_r == 64 and p.page_size in (16, 32, 64):
-        assert ok, "tuned kernel unexpectedly unavailable"
+    if (p.kind, p.d_v) in TUNED_SHAPES and p.d_r == 64 and p.page_size in (1, 2, 4, 8, 16, 32, 64):
+        # (one exception: a 512-dim latent with more than 32 query rows per group has no
+        # LDS left for the page-id windows that pages of 8 tokens or fewer need)
+        if not (p.page_size < 16 and p.d_v == 512 and (p.h_q // p.h_c) * p.T > 32):
+            assert ok, "tuned kernel unexpectedly unavailable"
     return [GENERIC, TUNED] if ok else [GENERIC]
 
 
@@ -120,6 +123,31 @@ def test_small_pages(shape, page_size):
         check_problem(p, impl=impl, what=f"{shape} page {page_size} impl={impl}")
 
 
+@pytest.mark.parametrize("page_size", [8, 4, 2, 1])
+@pytest.mark.parametrize("shape", ["gla2", "gla2_T4", "mla_few", "gta", "gla1_few"])
+def test_tiny_pages(shape, page_size):
+    """Pages of 8, 4, 2 and 1 tokens: every row of a load may sit in its own
+    page, each lane forms its row's address from page ids kept in LDS windows of
+    256 table entries.  Sequences long enough to cross several windows, run
+    both with the automatic split and as one chunk per sequence (windows
+    requested ahead and used many tiles later)."""
+    lens = [0, 1, 7, 8, 9, 31, 33, 64, 65, 255, 257, 700, 1500, 3000]
+    kw = dict(seq_lens=lens, page_size=page_size, num_pages=8192, poison_tail=True, extra_table_cols=1)
+    if shape == "gla2":
+        p = make_problem("tp_gla2", T=1, h_q=128, h_c=2, d_v=256, seed=400 + page_size, **kw)
+    elif shape == "gla2_T4":
+        p = make_problem("tp_gla2_T4", T=4, h_q=128, h_c=2, d_v=256, seed=410 + page_size, **kw)
+    elif shape == "mla_few":
+        p = make_problem("tp_mla", T=2, h_q=16, h_c=1, d_v=512, seed=420 + page_size, **kw)
+    elif shape == "gta":
+        p = make_problem("tp_gta", kind="gta", T=2, h_q=32, h_c=4, d_v=128, seed=430 + page_size, **kw)
+    else:
+        p = make_problem("tp_gla1", T=1, h_q=16, h_c=1, d_v=256, seed=440 + page_size, **kw)
+    for impl in impls_for(p):
+        for splits in ((0, 1) if impl == TUNED else (0,)):
+            check_problem(p, impl=impl, num_splits=splits, what=f"{shape} page {page_size} impl={impl} splits={splits}")
+
+
 def test_peaky_softmax_fp32_and_bf16_out():
     """Queries scaled x6: the softmax concentrates on a few keys, outputs are
     O(1) and the running-max rescaling is exercised."""
@@ -175,7 +203,7 @@ def test_workspace_too_small_is_reported():
     assert e.value.status == gla.GLA_ERR_WORKSPACE_TOO_SMALL
 
 
-@pytest.mark.parametrize("case", range(24))
+@pytest.mark.parametrize("case", range(34))
 def test_seeded_random_shapes(case):
     """Seeded sweep over head shapes, query lengths, page sizes, length mixes,
     split counts, masks and output types; every case runs each available
@@ -189,12 +217,12 @@ def test_seeded_random_shapes(case):
     B = int(rng.integers(1, 8))
     lens = [int(x) for x in rng.choice([0, 1, 2, 31, 32, 33, 64, 65, 127, 300, 1000, 2500], size=B)]
     lens[int(rng.integers(B))] = int(rng.integers(1, 3000))
-    page = int(rng.choice([16, 32, 64]))
+    page = int(rng.choice([16, 32, 64])) if case < 24 else int(rng.choice([1, 2, 4, 8]))
     causal = int(rng.integers(0, 2))
     splits = int(rng.choice([0, 0, 1, 3, 16]))
     out_dtype = torch.float32 if rng.integers(0, 2) else torch.bfloat16
     p = make_problem(f"rand{case}", kind=kind, seq_lens=lens, T=T, h_q=h_q, h_c=h_c, d_v=d_v,
-                     page_size=page, num_pages=4096, seed=9100 + case, causal=causal,
+                     page_size=page, num_pages=4096 if page >= 16 else 32768, seed=9100 + case, causal=causal,
                      poison_tail=True, extra_table_cols=int(rng.integers(0, 3)))
     for impl in impls_for(p):
         check_problem(p, impl=impl, num_splits=splits, out_dtype=out_dtype,
