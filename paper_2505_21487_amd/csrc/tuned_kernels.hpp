@@ -1454,7 +1454,10 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
   // A latent of 512 dims needs two waves per row slab: 32 rows x 512 fp32
   // output accumulators alone would fill a wave's accumulation registers.
   const int ks = p->d_v > 256 ? 2 : 1;
-  const int wpg = rows_group <= 32 ? 1 : ((rows_group <= 64 || ks == 2) ? 2 : 4);
+  // (a 512-dim latent with small pages: one row slab per workgroup, because the
+  // tile ring and the score mailboxes of two slabs leave no LDS for the page-id
+  // windows; the row blocks of a group then run as separate workgroups)
+  const int wpg = (rows_group <= 32 || (ks == 2 && lane)) ? 1 : ((rows_group <= 64 || ks == 2) ? 2 : 4);
   int ng = 4 / (wpg * ks);
   while (ng > 1 && (p->num_groups % ng || 4 * (ng * 32 * p->d_v * 2 + 32 * 128) > 160 * 1024)) ng >>= 1;
   plan->dv = p->d_v;

@@ -38,10 +38,7 @@ def impls_for(p):
     ok = tuned_available(p)
     # a shape that has a tuned kernel must really take it: no silent generic-only pass
     if (p.kind, p.d_v) in TUNED_SHAPES and p.d_r == 64 and p.page_size in (1, 2, 4, 8, 16, 32, 64):
-        # (one exception: a 512-dim latent with more than 32 query rows per group has no
-        # LDS left for the page-id windows that pages of 8 tokens or fewer need)
-        if not (p.page_size < 16 and p.d_v == 512 and (p.h_q // p.h_c) * p.T > 32):
-            assert ok, "tuned kernel unexpectedly unavailable"
+        assert ok, "tuned kernel unexpectedly unavailable"
     return [GENERIC, TUNED] if ok else [GENERIC]
 
 
@@ -124,7 +121,7 @@ def test_small_pages(shape, page_size):
 
 
 @pytest.mark.parametrize("page_size", [8, 4, 2, 1])
-@pytest.mark.parametrize("shape", ["gla2", "gla2_T4", "mla_few", "gta", "gla1_few"])
+@pytest.mark.parametrize("shape", ["gla2", "gla2_T4", "mla", "mla_few", "gta", "gla1_few"])
 def test_tiny_pages(shape, page_size):
     """Pages of 8, 4, 2 and 1 tokens: every row of a load may sit in its own
     page, each lane forms its row's address from page ids kept in LDS windows of
@@ -137,8 +134,10 @@ def test_tiny_pages(shape, page_size):
         p = make_problem("tp_gla2", T=1, h_q=128, h_c=2, d_v=256, seed=400 + page_size, **kw)
     elif shape == "gla2_T4":
         p = make_problem("tp_gla2_T4", T=4, h_q=128, h_c=2, d_v=256, seed=410 + page_size, **kw)
+    elif shape == "mla":
+        p = make_problem("tp_mla", T=1, h_q=128, h_c=1, d_v=512, seed=415 + page_size, **kw)
     elif shape == "mla_few":
-        p = make_problem("tp_mla", T=2, h_q=16, h_c=1, d_v=512, seed=420 + page_size, **kw)
+        p = make_problem("tp_mla_few", T=2, h_q=16, h_c=1, d_v=512, seed=420 + page_size, **kw)
     elif shape == "gta":
         p = make_problem("tp_gta", kind="gta", T=2, h_q=32, h_c=4, d_v=128, seed=430 + page_size, **kw)
     else:
