@@ -156,7 +156,7 @@ def main() -> int:
     ap.add_argument("--lens", default="", help="instead of --config: sequence lengths, e.g. 131072 or "
                     "1024x15,65536 (kernel-latency workloads, see workloads.latency_workload)")
     ap.add_argument("--shape", default="gla2", help="head shape for --lens: gla2 or mla")
-    ap.add_argument("--page-size", type=int, default=64, help="16, 32 or 64 tokens per page")
+    ap.add_argument("--page-size", type=int, default=64, help="tokens per page: a power of two, 1 to 64")
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--impl", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -28,8 +28,9 @@
  * beyond ceil(L_b / page_size) are never read (they may hold anything, -1
  * included); slots at or beyond L_b inside a page the table does hold may be
  * fetched but never reach a result, whatever they contain (NaN included).
- * The MFMA kernel runs for page_size 64, 32 and 16; other page sizes take the
- * generic kernel.
+ * The MFMA kernel runs for every power-of-two page_size from 64 down to 1
+ * (paper Section 4.2 for the small ones); other page sizes take the generic
+ * kernel.
  *
  * Ownership and execution.  Every pointer in the struct is a DEVICE pointer
  * owned by the caller unless stated otherwise; the library allocates no device

@@ -493,7 +493,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   const uint32_t rp_page_bytes = (uint32_t)p.rp_s[0] * 2u;
   const unsigned char* const state_w = (const unsigned char*)p.state + gl * (uint64_t)st_group_bytes;
   const unsigned char* const rope_w = (const unsigned char*)p.rope;
-  // Page sizes 64, 32 and 16 tokens: a tile of 32 tokens is half a page, a page
+  // Page sizes 64, 32 and 16 tokens (PM 0 and 1): a tile of 32 tokens is half a page, a page
   // or two pages.  The loads of a wave come in groups of up to four 1 KiB blocks
   // (at most 16 token rows) and single 1 KiB RoPE blocks (8 token rows); such a
   // run never straddles a page, so each has one base address, computed by the
