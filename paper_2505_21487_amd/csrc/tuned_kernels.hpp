@@ -9,8 +9,9 @@
 // rows of a group (ordered t-major) are cut into row blocks of 32 * WPG rows,
 // the h_c groups into blocks of NG.  A "unit" of the work list is (sequence b,
 // group block gb): it owns ceil(L_b / TOK) key tiles of TOK = 32 tokens (half
-// a page, a page or two pages for page sizes 64, 32, 16); a tile is the NG
-// state tiles of its groups plus one RoPE tile.  All tiles of all units, in
+// a page, a page, two pages ... 32 pages for page sizes 64, 32, 16 ... 1; the
+// address code comes in three forms, see the page modes of the main kernel);
+// a tile is the NG state tiles of its groups plus one RoPE tile.  All tiles of all units, in
 // unit order, form one flat list that is cut into equal chunks, so ragged
 // batches balance by construction and at most two units per chunk are left
 // incomplete.  A chunk is worked on by one workgroup per row block.  A (unit,
