@@ -248,3 +248,14 @@ def test_full_size_configs_on_sampled_rows(index, T):
     b_long = int(np.argmax(p.seq_lens))
     sel += [(b_long, t, h) for t in range(p.T) for h in (0, p.h_q - 1)]
     check_problem(p, sel=sel, what=f"cfg{index} T={T}")
+
+
+@pytest.mark.parametrize("index,T,page_size", [(1, 1, 1), (2, 2, 8), (4, 1, 2)])
+def test_full_size_small_pages_on_sampled_rows(index, T, page_size):
+    """Full-size configurations with the same pool cut into small pages (the
+    per-lane address path, page-id windows crossed hundreds of times)."""
+    p = config(index, T=T, page_size=page_size)
+    sel = sample_rows(p, 64, 2000 + index)
+    b_long = int(np.argmax(p.seq_lens))
+    sel += [(b_long, t, h) for t in range(p.T) for h in (0, p.h_q - 1)]
+    check_problem(p, sel=sel, what=f"cfg{index} T={T} page {page_size}")
