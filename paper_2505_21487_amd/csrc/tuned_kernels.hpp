@@ -35,1572 +35,12 @@
 // The operation itself is the absorbed-form attention of the paper (Sections
 // 2.1, 3.3.1, 3.3.2): score = scale * (q_nope . state[:DN] + q_rope . rope_key),
 // softmax over the visible keys, output = weights . state[:DV].
+//
+// Files: tuned_device.hpp (device helpers), tuned_main_kernel.hpp, tuned_combine_kernel.hpp,
+// tuned_host.hpp (plan and launches).
 #pragma once
 
-#include "../../include/gla_decode.h"
-
-#include <cstdio>
-#include <cstdlib>
-#include <type_traits>
-
-#include "common.hpp"
-
-namespace gla {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void global_cvoid_t;
-
-
-// ---- small device helpers -------------------------------------------------
-
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<I + 1, N>(f);
-  }
-}
-
-__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-// Workgroup barrier that waits for this wave's LDS traffic only: outstanding
-// global->LDS tile loads of later pipeline stages stay in flight.
-__device__ __forceinline__ void lds_barrier() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-// Hand-issued LDS reads.  The result registers are valid only after a matching
-// lds_wait on them; LDS returns data in issue order, so "at most N reads still
-// outstanding" identifies which reads have completed.
-template <int OFF>
-__device__ __forceinline__ void lds_read_b128(u32x4_t& dst, unsigned addr) {
-  static_assert(OFF >= 0 && OFF < 65536, "ds offset field");
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
-}
-// Transposing read: within each block of 16 lanes, lanes 4r..4r+3 address row r
-// (4 x b16 each) of a 4 x 16 matrix; lane i receives column i (4 x b16).
-template <int OFF>
-__device__ __forceinline__ void lds_read_tr16_b64(u32x2_t& dst, unsigned addr) {
-  static_assert(OFF >= 0 && OFF < 65536, "ds offset field");
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
-}
-template <int OFF>
-__device__ __forceinline__ void lds_write_b128(unsigned addr, const u32x4_t& v) {
-  static_assert(OFF >= 0 && OFF < 65536, "ds offset field");
-  asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(addr), "v"(v), "n"(OFF) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void lds_wait(u32x4_t& x) {
-  static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
-  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(N));
-}
-template <int N>
-__device__ __forceinline__ void lds_wait2(u32x2_t& x, u32x2_t& y) {
-  static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
-  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x), "+v"(y) : "n"(N));
-}
-
-// MFMA 32x32x16 bf16 issued as inline asm so that every operand's register file
-// is fixed: score accumulators live in architectural VGPRs (the vector ALU
-// reads them), output accumulators and query fragments in accumulation VGPRs.
-// The compiler does not see these as matrix instructions, so the wait states
-// the hardware needs around them are provided by hand where the surrounding
-// code does not already guarantee them:
-//   * a vector-ALU write of an MFMA source needs 2 wait states before the MFMA;
-//   * an MFMA result needs 12 wait states before anything but a dependent MFMA
-//     on the same accumulator reads it (back-to-back accumulation needs none).
-__device__ __forceinline__ void mfma_first_v(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b_acc) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b_acc));
-}
-__device__ __forceinline__ void mfma_acc_v(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b_acc) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b_acc));
-}
-__device__ __forceinline__ void mfma_acc_a(f32x16_t& acc, const u32x4_t& a, const u32x4_t& b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
-template <int N>
-__device__ __forceinline__ void wait_states() {
-  static_assert(N >= 1 && N <= 16, "s_nop covers 1..16 wait states");
-  asm volatile("s_nop %0" ::"n"(N - 1));
-}
-
-// Vector-ALU pieces of the softmax, issued by hand so that they stay exactly
-// where they are written between the MFMAs they overlap with.  One statement
-// per pipeline slot: x_q = s_q * sc2 - m ; p_{q-1} = 2^{x_{q-1}} ; sum += p_{q-2} ;
-// on odd q-2 also pack (p_{q-3}, p_{q-2}) to bf16.  Inside a statement no
-// instruction reads the result of the one before it (v_exp_f32 is a
-// transcendental: its result must not be consumed by the next instruction).
-__device__ __forceinline__ void sm_ops_f(float& x, float s, float sc2, float neg_m) {
-  asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(x) : "v"(s), "v"(sc2), "v"(neg_m));
-}
-__device__ __forceinline__ void sm_ops_fe(float& x, float s, float sc2, float neg_m, float& p1, float x1) {
-  asm volatile("v_fma_f32 %0, %2, %3, %4\n\tv_exp_f32 %1, %5"
-               : "=&v"(x), "=v"(p1) : "v"(s), "v"(sc2), "v"(neg_m), "v"(x1));
-}
-__device__ __forceinline__ void sm_ops_fea(float& x, float s, float sc2, float neg_m, float& p1, float x1,
-                                           float& sum, float p2) {
-  asm volatile("v_fma_f32 %0, %3, %4, %5\n\tv_exp_f32 %1, %6\n\tv_add_f32 %2, %2, %7"
-               : "=&v"(x), "=&v"(p1), "+v"(sum) : "v"(s), "v"(sc2), "v"(neg_m), "v"(x1), "v"(p2));
-}
-__device__ __forceinline__ void sm_ops_feac(float& x, float s, float sc2, float neg_m, float& p1, float x1,
-                                            float& sum, float p2, uint32_t& pk, float p3) {
-  asm volatile("v_fma_f32 %0, %4, %5, %6\n\tv_exp_f32 %1, %7\n\tv_add_f32 %2, %2, %8\n\tv_cvt_pk_bf16_f32 %3, %9, %8"
-               : "=&v"(x), "=&v"(p1), "+v"(sum), "=&v"(pk)
-               : "v"(s), "v"(sc2), "v"(neg_m), "v"(x1), "v"(p2), "v"(p3));
-}
-__device__ __forceinline__ void sm_ops_ea(float& p1, float x1, float& sum, float p2) {
-  asm volatile("v_exp_f32 %0, %2\n\tv_add_f32 %1, %1, %3" : "=&v"(p1), "+v"(sum) : "v"(x1), "v"(p2));
-}
-__device__ __forceinline__ void sm_ops_eac(float& p1, float x1, float& sum, float p2, uint32_t& pk, float p3) {
-  asm volatile("v_exp_f32 %0, %3\n\tv_add_f32 %1, %1, %4\n\tv_cvt_pk_bf16_f32 %2, %5, %4"
-               : "=&v"(p1), "+v"(sum), "=&v"(pk) : "v"(x1), "v"(p2), "v"(p3));
-}
-__device__ __forceinline__ void sm_ops_a(float& sum, float p2) {
-  asm volatile("s_nop 0\n\tv_add_f32 %0, %0, %1" : "+v"(sum) : "v"(p2));
-}
-__device__ __forceinline__ void sm_ops_ac(float& sum, float p2, uint32_t& pk, float p3) {
-  asm volatile("s_nop 0\n\tv_add_f32 %0, %0, %2\n\tv_cvt_pk_bf16_f32 %1, %3, %2" : "+v"(sum), "=&v"(pk) : "v"(p2), "v"(p3));
-}
-__device__ __forceinline__ void asm_max3(float& m, float a, float b) {
-  asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(m) : "v"(a), "v"(b));
-}
-// 16-byte global load straight into an accumulation VGPR tuple (no staging in
-// architectural VGPRs); complete after the next wait_vmcnt<0>().
-__device__ __forceinline__ void load_b128_async(u32x4_t& dst, const void* ptr) {
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(dst) : "v"(ptr) : "memory");
-}
-
-// A 32-bit global load that is complete when the statement ends.  Used for the
-// rare bookkeeping reads inside the tile loop (page ids, next sequence length):
-// being opaque to the compiler's memory-counter tracking, it cannot make the
-// compiler place a "wait for every outstanding load" in the steady-state path,
-// which would drain the tile prefetch ring on every iteration.
-__device__ __forceinline__ int load_i32_sync(const int32_t* ptr) {
-  int v;
-  asm volatile("global_load_dword %0, %1, off\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(ptr) : "memory");
-  return v;
-}
-
-// Register-class pins (no instruction is emitted).  MFMA accumulators and the
-// query fragments, which are only ever MFMA operands inside the tile loop, are
-// kept in the accumulation half of the unified register file; everything the
-// vector ALU touches stays in the architectural half.  Without the pins the
-// allocator shuttles the output accumulators between the halves every tile.
-template <class V>
-__device__ __forceinline__ void pin_acc(V& x) { asm volatile("" : "+a"(x)); }
-template <class V>
-__device__ __forceinline__ void pin_arch(V& x) { asm volatile("" : "+v"(x)); }
-
-// max / sum over the two half-waves (lane and lane ^ 32).  v_permlane32_swap
-// exchanges the upper half of its first register with the lower half of its
-// second, so afterwards the pair holds (lower, lower) and (upper, upper).
-// Issued as inline asm: the compiler's builtin folds the two results of a swap
-// of a value with itself into one.  The s_nop covers the wait states this
-// instruction needs after a vector-ALU write of its operands.
-__device__ __forceinline__ void half_swap(float x, float& a, float& b) {
-  a = x;
-  b = x;
-  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
-}
-__device__ __forceinline__ float half_swap_max(float x) {
-  float a, b;
-  half_swap(x, a, b);
-  return fmaxf(a, b);
-}
-__device__ __forceinline__ float half_swap_sum(float x) {
-  float a, b;
-  half_swap(x, a, b);
-  return a + b;
-}
-
-// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves
-// (no LDS round trips): shifts by 1, 2, 4, 8 inside each row of 16 lanes, then
-// the last lane of row 0 / 2 is broadcast into row 1 / 3 and lane 31 into the
-// upper half.  Lanes that receive nothing add zero.
-__device__ __forceinline__ int wave_incl_scan(int v) {
-  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);  // row_shr:1
-  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);  // row_shr:2
-  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);  // row_shr:4
-  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);  // row_shr:8
-  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
-  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
-  return v;
-}
-
-template <int TOK>
-__device__ __forceinline__ int tiles_of(int L) {
-  return L > 0 ? (L + TOK - 1) / TOK : 0;
-}
-
-// Position in the flat tile list.
-struct TileCursor {
-  int b;        // sequence
-  int ub;       // unit within the sequence (group block)
-  int j;        // tile within the unit
-  int tiles_b;  // tiles per unit of this sequence
-  int L;        // its length
-};
-
-// Total number of tiles of the batch (every wave computes the same value).
-// incl0: inclusive prefix sums of the tile counts of the first 64 sequences.
-template <int TOK>
-__device__ __forceinline__ int total_tiles(const DevParams& p, int UPB, int lane, int incl0) {
-  int total = __builtin_amdgcn_readlane(incl0, 63);
-  for (int base = 64; base < p.B; base += 64) {
-    const int idx = base + lane;
-    const int w = idx < p.B ? tiles_of<TOK>(p.seq_lens[idx]) * UPB : 0;
-    total += __builtin_amdgcn_readlane(wave_incl_scan(w), 63);
-  }
-  return total;
-}
-
-// Locate flat tile index `pos` (< total): which sequence / unit / tile.
-// L_first / incl0: length and inclusive tile prefix of the first 64 sequences.
-template <int TOK>
-__device__ __forceinline__ TileCursor locate_tile(const DevParams& p, int UPB, int pos, int lane, int L_first,
-                                                  int incl0) {
-  TileCursor c = {0, 0, 0, 0, 0};
-  int before = 0;
-  for (int base = 0; base < p.B; base += 64) {
-    const int idx = base + lane;
-    const int L = base == 0 ? L_first : (idx < p.B ? p.seq_lens[idx] : 0);
-    const int tl = tiles_of<TOK>(L);
-    const int w = tl * UPB;
-    const int incl = (base == 0 ? incl0 : wave_incl_scan(w)) + before;
-    const int excl = incl - w;
-    const unsigned long long hit = __ballot(w > 0 && excl <= pos && pos < incl);
-    if (hit) {
-      const int src = __ffsll((long long)hit) - 1;
-      const int ex = __builtin_amdgcn_readlane(excl, src);
-      c.tiles_b = __builtin_amdgcn_readlane(tl, src);
-      c.L = __builtin_amdgcn_readlane(L, src);
-      c.b = base + src;
-      const int rem = pos - ex;
-      c.ub = (int)((unsigned)rem / (unsigned)c.tiles_b);
-      c.j = rem - c.ub * c.tiles_b;
-      return c;
-    }
-    before = __builtin_amdgcn_readlane(incl, 63);
-  }
-  return c;
-}
-
-template <int TOK>
-__device__ __forceinline__ void advance(const DevParams& p, int UPB, TileCursor& c) {
-  if (++c.j < c.tiles_b) return;
-  c.j = 0;
-  if (++c.ub < UPB) return;
-  c.ub = 0;
-  do {
-    ++c.b;
-    c.L = c.b < p.B ? uniform(load_i32_sync(p.seq_lens + c.b)) : 0;
-    c.tiles_b = tiles_of<TOK>(c.L);
-  } while (c.b < p.B && c.tiles_b == 0);
-}
-
-// 16-byte-chunk swizzles of the LDS tiles.  State rows are DV*2 bytes; within
-// every aligned run of 16 chunks the chunk index is XORed with a 4-bit key of
-// the token so that (a) 16 consecutive tokens reading the same logical chunk
-// (score MFMA operand reads) and (b) 4 consecutive tokens reading the same 64
-// bytes (transposing value reads) both spread over all LDS banks.  The key is
-// a bit permutation, hence XOR-linear in the token index.
-__host__ __device__ constexpr int swz16(int t) { return ((t & 3) << 2) | ((t >> 2) & 3); }
-// RoPE rows are 128 bytes (8 chunks): two tokens share a 256-byte bank row.
-__host__ __device__ constexpr int swz8(int t) { return (t >> 1) & 7; }
-
-template <int DV, int DN, int DR, int NG, int WPG, int KS, int TOK, int STAGES>
-struct TunedTraits {
-  static constexpr int NWAVES = NG * WPG * KS;
-  static constexpr int kRows = 32 * NG * WPG;  // query rows of a unit, all groups together
-  static constexpr int kRowBytes = DV * 2;
-  static constexpr int kStateBytes = TOK * kRowBytes;
-  static constexpr int kRopeBytes = TOK * DR * 2;
-  // LDS layout: for each of the NG groups its STAGES state tiles, then the
-  // STAGES RoPE tiles, so that stepping to the next stage is one add for every
-  // operand address and each wave's group is a constant folded into its bases.
-  static constexpr int kGroupBytes = STAGES * kStateBytes;
-  static constexpr int kRopeBase = NG * kGroupBytes;
-  static constexpr int kTileBytes = STAGES * (NG * kStateBytes + kRopeBytes);
-  // KS > 1: one 4 KiB mailbox per wave for the partial scores the KS waves of a row slab exchange
-  static constexpr int kXchgBase = kTileBytes;
-  static constexpr int kSmemBytes = kTileBytes + (KS > 1 ? NWAVES * 4096 : 0);
-  static constexpr int kStateLoads = kStateBytes / 1024;  // wave-wide 16 B/lane loads per group tile
-  static constexpr int kRopeLoads = kRopeBytes / 1024;
-  static constexpr int kLoadsPerWave = kStateLoads / (WPG * KS) + kRopeLoads / NWAVES;
-  static constexpr int kThreads = 64 * NWAVES;
-  static constexpr size_t kSlotFloats = (size_t)kRows * DV + 32 * NWAVES;  // partial out + one lse per wave row
-  static_assert(TOK == 32, "tiles of 32 tokens: two, one or half of them per page");
-  static_assert(STAGES >= 3 && STAGES % 2 == 0, "PV stage + score stage + loading stages; even for the score register swap");
-  static_assert(KS == 1 || (KS == 2 && DN == DV), "row slabs are split over 1 or 2 waves; the split is by state dims");
-  static_assert(kStateLoads % (WPG * KS) == 0 && kRopeLoads % NWAVES == 0, "tile loads must split evenly over waves");
-  static_assert(((kStateLoads / (WPG * KS)) & (kStateLoads / (WPG * KS) - 1)) == 0, "per-wave state blocks: power of two (swizzle keys combine by XOR)");
-  static_assert(KS == 1 || ((DN / KS * 2) % 256 == 0 && (DV / KS * 2) % 256 == 0), "a wave's share of a state row starts on a swizzle-run boundary");
-  static_assert(kLoadsPerWave * (STAGES - 2) <= 63, "vmcnt range");
-  static_assert(DR == 64, "RoPE key tile layout assumes 64 dims");
-  static_assert(kRowBytes >= 256 && (kRowBytes & (kRowBytes - 1)) == 0 && kRowBytes <= 1024, "state row bytes");
-  static_assert(kSmemBytes <= 160 * 1024, "LDS capacity");
-};
-
-// PM, the page mode, selects the address code of the tile loads:
-//   0: pages of 64 tokens (a tile is half a page: one base address per tile),
-//   1: pages of 32 or 16 tokens (one base address per run of up to 16 rows),
-//   2: pages of 8, 4, 2 or 1 tokens (one address per row and lane, from page ids
-//      that each wave keeps in a window of the page table in LDS).
-constexpr int kPageWindow = 256;  // page-table entries per window (PM == 2)
-template <int DV, int DN, int DR, int NG, int WPG, int KS, int TOK, int STAGES, int PM>
-__global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParams p) {
-  using TT = TunedTraits<DV, DN, DR, NG, WPG, KS, TOK, STAGES>;
-  constexpr int NWAVES = NG * WPG * KS;
-  constexpr bool kLane = PM == 2;
-  constexpr int kWinBase = TT::kSmemBytes;                                     // two windows per wave
-  constexpr int kSmemAll = TT::kSmemBytes + (kLane ? NWAVES * 2 * kPageWindow * 4 : 0);
-  static_assert(kSmemAll <= 160 * 1024, "LDS capacity");
-  constexpr int ROWB = TT::kRowBytes;
-  constexpr int STB = TT::kStateBytes;   // state tile bytes
-  constexpr int RTB = TT::kRopeBytes;    // RoPE tile bytes
-  constexpr int NTB = TOK / 32;          // 32-token blocks per tile
-  // With KS = 2 the two waves of a row slab each take half of the state dims
-  // (for the scores and for the output) and half of the RoPE dims, and add up
-  // their partial scores through LDS; everything below is per wave.
-  constexpr int DVW = DV / KS, DNW = DN / KS, DRW = DR / KS;
-  constexpr int NKN = DNW / 16;          // contraction steps over the state dims
-  constexpr int NKR = DRW / 16;          // ... over the RoPE dims
-  constexpr int NDB = DVW / 32;          // 32-dim output blocks
-  constexpr int NE = 16 * NTB;           // scores per lane per tile
-  constexpr int NS = (NKN + NKR) * NTB;  // score MFMAs per tile
-  constexpr int NP = (TOK / 16) * NDB;   // value MFMAs per tile
-  constexpr int NB = NP + TOK / 16;      // ... plus the row-sum MFMAs
-  constexpr int LPW = TT::kLoadsPerWave;
-  constexpr int SLW = TT::kStateLoads / (WPG * KS);  // 1 KiB state blocks per wave and tile
-  constexpr int RLW = TT::kRopeLoads / NWAVES;   // 1 KiB RoPE blocks per wave and tile
-  __shared__ __attribute__((aligned(1024))) unsigned char smem[kSmemAll];
-  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = uniform(tid >> 6);
-  const int gl = wave / (WPG * KS);    // this wave's group within the unit's group block
-  const int wpos = wave % (WPG * KS);  // position among the waves of that group
-  const int wg = wpos / KS;            // this wave's 32-row slab within the group's row block
-  const int kx = wpos % KS;            // which share of the state / RoPE dims this wave works on
-  const int col = lane & 31;  // query row inside the wave's 32-row slab == MFMA column
-  const int hi = lane >> 5;   // which half of the contraction slots this lane feeds
-
-  const int rows_group = p.g_q * p.T;
-  const int MB = p.mb;    // row blocks per group
-  const int UPB = p.upb;  // units (group blocks) per sequence
-#ifdef GLA_EXPERIMENT_TIMESTAMPS
-  // experiment build: wall-clock stamps of workgroup phases, 8 per workgroup,
-  // written 192 MiB into the workspace (the experiment passes a larger one)
-  long long* const stamps = (long long*)((char*)p.ws_out + (192ll << 20)) + (size_t)blockIdx.x * 8;
-#define GLA_STAMP(i) do { if (tid == 0) stamps[i] = (long long)wall_clock64(); } while (0)
-#else
-#define GLA_STAMP(i) do { } while (0)
-#endif
-  GLA_STAMP(0);
-
-  // A chunk of the list is worked on by MB workgroups, one per row block of its
-  // groups (MB > 1 when a group has more query rows than a workgroup holds).
-  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): the
-  // MB workgroups of a chunk are placed on ONE XCD, where they run side by side
-  // so that the tiles the first one fetches are L2 hits for the others, and
-  // every XCD gets a contiguous run of chunks (same page-table rows, same
-  // queries).  Grids that do not divide evenly fall back to a plain order.
-  const int n_chunks = p.num_chunks;  // the host launches n_chunks * MB workgroups
-  int chunk_id, mb_wg;
-  if (p.xcd_map) {
-    const int xcd = (int)blockIdx.x & 7, n = (int)blockIdx.x >> 3;
-    const int q = (int)fast_div((unsigned)n, p.fd_mb);
-    mb_wg = n - q * MB;
-    chunk_id = xcd * (n_chunks >> 3) + q;
-  } else {
-    chunk_id = (int)fast_div(blockIdx.x, p.fd_mb);
-    mb_wg = (int)blockIdx.x - chunk_id * MB;
-  }
-
-  // ---- a guess, made before anything is known about the lengths: if every
-  // sequence filled its page-table row, this chunk would start at page pg of
-  // sequence b_g.  That stretch of the page table is requested right away, next
-  // to the lengths, and used if the plan below lands inside it (always, for a
-  // batch of equal full-length sequences): one dependent memory round trip less
-  // before the first tile can be requested.
-  int pt_b = -1, pt_base = 0;
-  int pt_vec = 0;
-  int L_first;  // lengths of the first 64 sequences (0 beyond the batch), reused by the plan
-  {
-    // (all products below stay under 2^30: the host refuses larger plans)
-    const unsigned total_g = (unsigned)p.B * (unsigned)UPB * (unsigned)p.tiles_full;
-    const unsigned c0_g = min((unsigned)chunk_id * (unsigned)p.chunk_guess, total_g - 1);  // (chunks past the end: any valid row)
-    const int b_g = (int)fast_div(c0_g, p.fd_units_full);
-    const unsigned j_g = c0_g - fast_div(c0_g, p.fd_tiles_full) * (unsigned)p.tiles_full;
-    const int pg = (int)((j_g * TOK) >> (PM == 0 ? 6 : p.lg_page));
-    const int32_t* ptr_pt = p.page_table + (int64_t)b_g * p.max_pages + min(pg + lane, p.max_pages - 1);
-    const int32_t* ptr_len = p.seq_lens + (lane < p.B ? lane : 0);
-    // both requests in flight together, both complete when the statement ends
-    asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %3, off\n\ts_waitcnt vmcnt(0)"
-                 : "=&v"(pt_vec), "=&v"(L_first)
-                 : "v"(ptr_pt), "v"(ptr_len)
-                 : "memory");
-    if (lane >= p.B) L_first = 0;
-    pt_b = b_g;
-    pt_base = pg;
-  }
-
-  // ---- plan: this workgroup's chunk [c0, c1) of the flat tile list
-  const int incl0 = wave_incl_scan(tiles_of<TOK>(L_first) * UPB);
-  const int n_total = total_tiles<TOK>(p, UPB, lane, incl0);
-  if (n_total <= 0) return;
-  // Chunk i covers tiles [i * chunk, (i + 1) * chunk): a fixed length if the
-  // caller chose a split count, else an equal share of the list.
-  const int chunk = p.chunk_tiles > 0 ? p.chunk_tiles : (int)fast_div((unsigned)(n_total + n_chunks - 1), p.fd_chunks);
-  auto chunk_start = [&](int i) -> int { return (int)min((int64_t)n_total, (int64_t)i * chunk); };
-  const int c0 = chunk_start(chunk_id);
-  const int c1 = chunk_start(chunk_id + 1);
-  if (c0 >= c1) return;  // only chunks past the end of the list are empty: no unit spans them
-  const int n_tiles = c1 - c0;
-
-  TileCursor cur = locate_tile<TOK>(p, UPB, c0, lane, L_first, incl0);  // compute position
-  TileCursor pre = cur;                                  // prefetch position
-  GLA_STAMP(1);
-
-  // ---- tile loads, global -> LDS, 16 B per lane, 1 KiB per wave instruction.
-  // The LDS side is linear in the lane index, so each lane fetches the global
-  // chunk whose swizzled home is its LDS slot.  Wave w moves the contiguous
-  // 1 KiB blocks [wg*SLW, (wg+1)*SLW) of its own group's state tile and blocks
-  // [w*RLW, (w+1)*RLW) of the RoPE tile; block i of a wave sits at  i*1024 + (lane_part ^ key(i) << 4)
-  // past the wave's start, i.e. one XOR per load, and four loads share one
-  // pair of base addresses through the instruction's immediate offset (which
-  // the hardware adds to the global and to the LDS address alike).  Page ids
-  // are fetched 64 at a time, one per lane, and broadcast from the owning lane.
-  constexpr int RPL = 1024 / ROWB;  // state rows per wave load
-  constexpr int CPR = ROWB / 16;    // 16 B chunks per state row
-  const int s_rl = lane / CPR, s_pc = lane % CPR;
-  const unsigned s_lane_w =
-      (unsigned)(s_rl * ROWB + ((s_pc & ~15) << 4) + (((s_pc & 15) ^ swz16(s_rl) ^ swz16(wpos * SLW * RPL)) << 4));
-  const int r_rl = lane >> 3, r_pc = lane & 7;
-  const unsigned r_lane_w = (unsigned)(r_rl * 128 + ((r_pc ^ (r_rl >> 1) ^ (((wave * RLW) & 1) << 2)) << 4));
-  const uint32_t st_page_bytes = (uint32_t)p.st_s[0] * 2u, st_group_bytes = (uint32_t)p.st_s[1] * 2u;
-  const uint32_t rp_page_bytes = (uint32_t)p.rp_s[0] * 2u;
-  const unsigned char* const state_w = (const unsigned char*)p.state + gl * (uint64_t)st_group_bytes;
-  const unsigned char* const rope_w = (const unsigned char*)p.rope;
-  // Page sizes 64, 32 and 16 tokens (PM 0 and 1): a tile of 32 tokens is half a page, a page
-  // or two pages.  The loads of a wave come in groups of up to four 1 KiB blocks
-  // (at most 16 token rows) and single 1 KiB RoPE blocks (8 token rows); such a
-  // run never straddles a page, so each has one base address, computed by the
-  // wave that issues it from the page id of its own rows.
-  const int lgP = PM == 0 ? 6 : p.lg_page;
-  constexpr int NSGW = (SLW + 3) / 4;                 // load groups of the state tile per wave
-  constexpr int GROWS = (SLW < 4 ? SLW : 4) * RPL;    // token rows per load group
-  static_assert(GROWS <= 16 && (16 % GROWS) == 0, "a load group stays inside a 16-token page");
-  unsigned char* const lds_state_w = smem + gl * TT::kGroupBytes + wpos * (SLW * 1024);
-  unsigned char* const lds_rope_w = smem + TT::kRopeBase + wave * (RLW * 1024);
-
-  uint64_t pre_goff = (uint64_t)pre.ub * NG * st_group_bytes;  // byte offset of the cursor's group block in a page
-  const unsigned char* pre_sp = nullptr;  // state / RoPE page of the prefetch cursor
-  const unsigned char* pre_rp = nullptr;
-  bool pre_page_valid = false;
-  // addresses of the tile being issued (this wave's share)
-  const unsigned char* dma_s[NSGW] = {};
-  const unsigned char* dma_r[RLW] = {};
-  unsigned char* dma_ls = nullptr;
-  unsigned char* dma_lr = nullptr;
-  int issued = 0;  // tiles whose loads have been issued
-  // PM == 2, pages of 8 tokens or fewer: every token row of a load may lie in
-  // its own page, so each lane forms the address of the row it fetches, from
-  // the page id of that row.  The ids come from LDS: every wave keeps two
-  // windows of kPageWindow consecutive page-table entries of the sequence it is
-  // fetching, the one in use and the one after it, requested (direct to LDS)
-  // when the first is entered, so a window has long arrived when the prefetch
-  // cursor reaches it.  Only the first window of a sequence, and windows
-  // entered within a few tiles of their request, are waited for.
-  unsigned char* const win_w = smem + kWinBase + wave * (2 * kPageWindow * 4);
-  int win_b = -1, win_id0 = -1, win_id1 = -1, win_at0 = 0, win_at1 = 0, win_sel = 0;
-  int pg_s[SLW] = {}, pg_r[RLW] = {};  // page id of this lane's row, per load of the prepared tile
-  uint64_t dma_goff = 0;               // group-block offset the prepared tile's addresses use
-  unsigned dma_pmask = 0;
-  auto win_fetch = [&](int slot, int b_seq, int id, int last_page) {
-    // entries [id * kPageWindow, +kPageWindow) of row b_seq, those past the last held page replaced by it
-    const int32_t* row = p.page_table + (int64_t)b_seq * p.max_pages;
-#pragma unroll
-    for (int i = 0; i < kPageWindow / 64; ++i) {
-      const int e = min(id * kPageWindow + i * 64 + lane, last_page);
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(row + e), (lds_void_t*)(win_w + slot * (kPageWindow * 4) + i * 256), 4, 0, 0);
-    }
-  };
-
-  // Prepare the loads of the next tile into `stage`.  Once every tile of the
-  // chunk has been issued the previous tile's addresses are kept: the loads
-  // then re-read lines that are still in L2 into a stage nobody reads, which
-  // keeps the steady-state loop free of branches around the load instructions.
-  // The preparation is scalar work (a few dozen instructions).  It is cut in
-  // three pieces so that the tile loop can place them between value MFMAs
-  // instead of running them in one stretch with the matrix pipe idle.
-  bool prep_active = false, prep_need_page = false;
-  unsigned prep_page_idx = 0, prep_tip = 0;
-  auto dma_prepare_0 = [&](int stage) {  // where to, and are page ids needed
-    dma_ls = lds_state_w + stage * STB;
-    dma_lr = lds_rope_w + stage * RTB;
-    prep_active = issued < n_tiles;
-    const unsigned tok0 = (unsigned)pre.j * TOK;
-    prep_page_idx = tok0 >> lgP;                    // first page of the tile
-    prep_tip = (tok0 & ((1u << lgP) - 1)) / TOK;  // tile within the page (pages of 64)
-    prep_need_page = prep_active && (lgP < 6 || prep_tip == 0 || !pre_page_valid);
-    const int last_idx = (int)((tok0 + TOK - 1) >> lgP);
-    if constexpr (kLane) {
-      if (prep_active) {
-        const int last_page = (pre.L - 1) >> lgP;
-        const int want = (int)prep_page_idx / kPageWindow;
-        if (pre.b != win_b || (want != win_id0 && want != win_id1)) {
-          win_b = pre.b;
-          win_id0 = want;
-          win_id1 = -1;
-          win_sel = 0;
-          win_fetch(0, pre.b, want, last_page);
-          wait_vmcnt<0>();
-          win_at0 = issued - STAGES;
-        } else {
-          win_sel = want == win_id1 ? 1 : 0;
-          // requested too recently for the rolling waits of the tile loop to have covered it
-          if (issued - (win_sel ? win_at1 : win_at0) < STAGES) wait_vmcnt<0>();
-        }
-        const int nxt = want + 1;
-        if (nxt * kPageWindow <= last_page && (win_sel ? win_id0 : win_id1) != nxt) {
-          if (win_sel) { win_id0 = nxt; win_at0 = issued; } else { win_id1 = nxt; win_at1 = issued; }
-          win_fetch(win_sel ^ 1, pre.b, nxt, last_page);
-        }
-      }
-    } else if (prep_need_page && (pre.b != pt_b || (int)prep_page_idx < pt_base || last_idx >= pt_base + 64)) {
-      pt_b = pre.b;
-      pt_base = (int)prep_page_idx;
-      const int idx = min((int)prep_page_idx + lane, p.max_pages - 1);
-      pt_vec = load_i32_sync(p.page_table + (int64_t)pre.b * p.max_pages + idx);
-    }
-  };
-  auto dma_prepare_1 = [&]() {  // pages of 64: page id -> page base addresses (kept for the page's second tile)
-    if (prep_need_page && lgP == 6) {
-      const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pt_vec, (int)prep_page_idx - pt_base);
-      pre_sp = state_w + ((uint64_t)page * st_page_bytes + pre_goff);
-      pre_rp = rope_w + (uint64_t)page * rp_page_bytes;
-      pre_page_valid = true;
-    }
-  };
-  auto dma_prepare_2 = [&]() {  // base address of every load group; advance the prefetch cursor
-    if (!prep_active) return;
-    if constexpr (kLane) {
-      const unsigned tok0 = (unsigned)pre.j * TOK;
-      const int last_page = (pre.L - 1) >> lgP;
-      const unsigned char* const win = win_w + win_sel * (kPageWindow * 4);
-#pragma unroll
-      for (int i = 0; i < SLW; ++i) {
-        const unsigned rho = (unsigned)((wpos * SLW + i) * RPL + s_rl);
-        const int e = min((int)((tok0 + rho) >> lgP), last_page);
-        pg_s[i] = *reinterpret_cast<const int*>(win + (e & (kPageWindow - 1)) * 4);
-      }
-#pragma unroll
-      for (int ir = 0; ir < RLW; ++ir) {
-        const unsigned rho = (unsigned)((wave * RLW + ir) * 8 + r_rl);
-        const int e = min((int)((tok0 + rho) >> lgP), last_page);
-        pg_r[ir] = *reinterpret_cast<const int*>(win + (e & (kPageWindow - 1)) * 4);
-      }
-      dma_goff = pre_goff;
-      dma_pmask = (1u << lgP) - 1;
-    } else if (lgP == 6) {
-#pragma unroll
-      for (int gi = 0; gi < NSGW; ++gi) dma_s[gi] = pre_sp + prep_tip * STB + (wpos * SLW + 4 * gi) * 1024;
-#pragma unroll
-      for (int ir = 0; ir < RLW; ++ir) dma_r[ir] = pre_rp + prep_tip * RTB + (wave * RLW + ir) * 1024;
-    } else {
-      // Smaller pages: one page lookup per load group.  Rows past the end of the
-      // sequence may lie in a page the table does not hold: they are fetched from
-      // the sequence's last page instead (any finite-or-not data will do, those
-      // rows are masked and zeroed), never through an unused table entry.
-      const unsigned tok0 = (unsigned)pre.j * TOK, pmask = (1u << lgP) - 1;
-      const int last_page = (pre.L - 1) >> lgP;
-#pragma unroll
-      for (int gi = 0; gi < NSGW; ++gi) {
-        const unsigned tok = tok0 + (unsigned)(wpos * SLW + 4 * gi) * RPL;
-        const int pi = min((int)(tok >> lgP), last_page);
-        const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pt_vec, pi - pt_base);
-        dma_s[gi] = state_w + ((uint64_t)page * st_page_bytes + pre_goff + (uint64_t)(tok & pmask) * ROWB);
-      }
-#pragma unroll
-      for (int ir = 0; ir < RLW; ++ir) {
-        const unsigned tok = tok0 + (unsigned)(wave * RLW + ir) * 8;
-        const int pi = min((int)(tok >> lgP), last_page);
-        const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pt_vec, pi - pt_base);
-        dma_r[ir] = rope_w + ((uint64_t)page * rp_page_bytes + (uint64_t)(tok & pmask) * 128);
-      }
-    }
-    ++issued;
-    if (++pre.j == pre.tiles_b) {
-      pre.j = 0;
-      pre_page_valid = false;
-      if (++pre.ub == UPB) {
-        pre.ub = 0;
-        do {
-          ++pre.b;
-          pre.L = pre.b < p.B ? uniform(load_i32_sync(p.seq_lens + pre.b)) : 0;
-          pre.tiles_b = tiles_of<TOK>(pre.L);
-        } while (pre.b < p.B && pre.tiles_b == 0);
-      }
-      pre_goff = (uint64_t)pre.ub * NG * st_group_bytes;
-    }
-  };
-  auto dma_prepare = [&](int stage) {
-    dma_prepare_0(stage);
-    dma_prepare_1();
-    dma_prepare_2();
-  };
-  // i-th of this wave's LPW loads of the prepared tile
-  auto dma_load = [&](auto ic) {
-    constexpr int i = decltype(ic)::value;
-#ifndef GLA_EXPERIMENT_NO_TILE_LOADS
-    if constexpr (kLane) {
-      // address of this lane's row: page base + row within the page + the chunk
-      // of the row whose swizzled home is this lane's LDS slot
-      if constexpr (i < SLW) {
-        const unsigned voff = s_lane_w ^ ((unsigned)swz16(i * RPL) << 4);
-        const unsigned rho = (unsigned)((wpos * SLW + i) * RPL + s_rl);
-        const unsigned off = (rho & dma_pmask) * ROWB + (voff & (ROWB - 1));
-        const unsigned char* src = state_w + ((uint64_t)(uint32_t)pg_s[i] * st_page_bytes + dma_goff + off);
-        __builtin_amdgcn_global_load_lds((global_cvoid_t*)src, (lds_void_t*)(dma_ls + i * 1024), 16, 0, 0);
-      } else {
-        constexpr int ir = i - SLW;
-        const unsigned voff = r_lane_w ^ ((unsigned)(ir & 1) << 6);
-        const unsigned rho = (unsigned)((wave * RLW + ir) * 8 + r_rl);
-        const unsigned off = (rho & dma_pmask) * 128 + (voff & 127);
-        const unsigned char* src = rope_w + ((uint64_t)(uint32_t)pg_r[ir] * rp_page_bytes + off);
-        __builtin_amdgcn_global_load_lds((global_cvoid_t*)src, (lds_void_t*)(dma_lr + ir * 1024), 16, 0, 0);
-      }
-    } else if constexpr (i < SLW) {
-      const unsigned voff = s_lane_w ^ ((unsigned)swz16(i * RPL) << 4);
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_s[i / 4] + voff),
-                                       (lds_void_t*)(dma_ls + (i / 4) * 4096), 16, (i % 4) * 1024, 0);
-    } else {
-      constexpr int ir = i - SLW;
-      const unsigned voff = r_lane_w ^ ((unsigned)(ir & 1) << 6);
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_r[ir] + voff),
-                                       (lds_void_t*)(dma_lr + ir * 1024), 16, 0, 0);
-    }
-#endif
-  };
-
-  // ---- query fragments of the unit at `cur`: this wave's 32 rows, B operand of
-  //      the score MFMAs, lane holds 8 dims of row `col` per contraction step.
-  //      Requested at the start of every segment, after the first tiles.
-  u32x4_t qn[NKN];  // raw bf16 bits (accumulation VGPRs)
-  u32x4_t qr[NKR];
-  bool row_valid = false;
-  int row_b = 0, row_t = 0, row_h = 0;
-  auto q_issue = [&]() {
-    const int gb = cur.ub;
-    const int mb = mb_wg;
-    const int g = gb * NG + gl;
-    const int R = (mb * WPG + wg) * 32 + col;
-    row_valid = R < rows_group;
-    const int Rc = row_valid ? R : rows_group - 1;
-    row_t = (int)fast_div((unsigned)Rc, p.fd_gq);
-    row_h = g * p.g_q + (Rc - row_t * p.g_q);
-    row_b = cur.b;
-    const uint16_t* qn_ptr = p.q_nope + row_b * p.qn_s[0] + row_t * p.qn_s[1] + row_h * p.qn_s[2] + kx * DNW + 8 * hi;
-    const uint16_t* qr_ptr = p.q_rope + row_b * p.qr_s[0] + row_t * p.qr_s[1] + row_h * p.qr_s[2] + kx * DRW + 8 * hi;
-    // padding rows re-read the last valid row: their columns are computed and never stored
-#pragma unroll
-    for (int ks = 0; ks < NKN; ++ks) load_b128_async(qn[ks], qn_ptr + 16 * ks);
-#pragma unroll
-    for (int ks = 0; ks < NKR; ++ks) load_b128_async(qr[ks], qr_ptr + 16 * ks);
-  };
-
-  // ---- prologue: fill STAGES-1 stages
-#pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s) {
-    if (issued < n_tiles) {
-      dma_prepare(s);
-      static_for<0, LPW>(dma_load);
-    }
-  }
-
-  GLA_STAMP(2);
-  // ---- lane-constant LDS read addresses (stage 0; other stages are immediates)
-  // score operand (K rows, 16 B): token = 32*tb + col, logical chunk = 2*ks + hi
-  const int sw_col = swz16(col);
-  unsigned k_off[8], ka[8];  // index: ks & 7; ka: working copy pointing at a stage
-#pragma unroll
-  for (int e = 0; e < 8; ++e)
-    k_off[e] = lds_base + (unsigned)(gl * TT::kGroupBytes + col * ROWB + kx * (DNW * 2) + ((((2 * e) | hi) ^ sw_col) << 4));
-  unsigned r_off[NKR], ra[NKR];
-#pragma unroll
-  for (int e = 0; e < NKR; ++e)
-    r_off[e] = lds_base + (unsigned)(TT::kRopeBase + col * 128 + (((kx * (DRW / 8) + ((2 * e) | hi)) ^ swz8(col)) << 4));
-  // value operand (transposing 8 B reads): 16-lane block bk = lane / 16 covers
-  // 4 tokens x 16 dims; lane 4r+q of the block addresses token r, dims 4q..4q+3.
-  const int i16 = lane & 15;
-  const int tr_r = i16 >> 2, tr_q = i16 & 3;
-  const int dh = (lane >> 4) & 1;
-  unsigned v_off[4][2], va[4][2];  // [db & 3][a]
-#pragma unroll
-  for (int d4 = 0; d4 < 4; ++d4)
-#pragma unroll
-    for (int a = 0; a < 2; ++a) {
-      const int key = (tr_r << 2) | (2 * a + hi);           // swz16 of token 8a + 4hi + r
-      const int lc = (4 * d4 + 2 * dh + (tr_q >> 1)) ^ key;  // chunk within the 16-chunk run
-      v_off[d4][a] = lds_base + (unsigned)(gl * TT::kGroupBytes + (4 * hi + tr_r) * ROWB + kx * (DVW * 2) + (lc << 4) + (tr_q & 1) * 8);
-    }
-
-  float sc2 = p.scale * 1.4426950408889634f;  // scores in base-2 units (scale > 0)
-  pin_arch(sc2);
-  u32x4_t ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 x 8
-  pin_arch(ones_bits);  // a live register, never re-materialised right in front of an MFMA
-
-  // ---- per-unit state
-  f32x16_t o[NDB];
-  f32x16_t o_one;   // every row: sum of the bf16-rounded weights (V block of ones)
-  float m_ref = -INFINITY, l_run = 0.f;
-  int n_vis = 0, n_vis_min = 0;
-
-  // ---- building blocks of the tile pipeline ---------------------------------------
-  // The blocks take a stage parameter SG: SG >= 0 folds a compile-time stage into
-  // the immediate offsets; SG < 0 (what the loop uses) means the stage has been
-  // added to the address registers ka / ra / va by the caller.
-
-  // zero the value rows at or beyond the sequence end in a freshly landed tile:
-  // those slots may hold anything (NaN included) and 0-weight x garbage must not leak
-  auto zero_tail = [&](int stage, int tile_j, int L) {
-    const int tok0 = tile_j * TOK;
-    if (tok0 + TOK > L) {
-      const int valid = L - tok0;
-#pragma unroll
-      for (int g2 = 0; g2 < NG; ++g2) {
-        unsigned char* sb = smem + g2 * TT::kGroupBytes + stage * STB;
-        for (int off = valid * ROWB + tid * 16; off < STB; off += TT::kThreads * 16)
-          *(u32x4_t*)(sb + off) = u32x4_t{0, 0, 0, 0};
-      }
-    }
-  };
-
-  // score operand ring: RS slots, all RS reads in flight, waited for in groups of 4
-  constexpr int RS = 8;
-  u32x4_t kfrag[RS];
-  auto s_issue = [&](auto sgc, auto ic) {
-    constexpr int SG = decltype(sgc)::value;
-    constexpr int i = decltype(ic)::value;
-    constexpr int ks = i / NTB, tb = i % NTB;
-    constexpr int so = SG < 0 ? 0 : SG * STB, ro = SG < 0 ? 0 : SG * RTB;
-    u32x4_t& f = kfrag[i % RS];
-    if constexpr (ks < NKN) lds_read_b128<so + tb * 32 * ROWB + ((2 * ks) & ~15) * 16>(f, ka[ks & 7]);
-    else lds_read_b128<ro + tb * 32 * 128>(f, ra[ks - NKN]);
-  };
-  auto s_wait = [&](auto ic) {  // before step i (i % 4 == 0): fragments i .. i+3 have arrived
-    constexpr int i = decltype(ic)::value;
-    constexpr int issued_r = (i + RS < NS ? i + RS : NS);
-    constexpr int need = (i + 4 < NS ? i + 4 : NS);
-    u32x4_t &f0 = kfrag[i % RS], &f1 = kfrag[(i + 1) % RS], &f2 = kfrag[(i + 2) % RS], &f3 = kfrag[(i + 3) % RS];
-    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(f0), "+v"(f1), "+v"(f2), "+v"(f3) : "n"(issued_r - need));
-  };
-  auto s_mfma = [&](auto sgc, auto ic, f32x16_t (&acc)[NTB]) {
-    constexpr int i = decltype(ic)::value;
-    constexpr int ks = i / NTB, tb = i % NTB;
-    if constexpr (ks == 0) mfma_first_v(acc[tb], kfrag[i % RS], qn[0]);
-    else if constexpr (ks < NKN) mfma_acc_v(acc[tb], kfrag[i % RS], qn[ks]);
-    else mfma_acc_v(acc[tb], kfrag[i % RS], qr[ks - NKN]);
-    if constexpr (i + RS < NS) s_issue(sgc, std::integral_constant<int, i + RS>{});
-  };
-
-  // value operand ring: VRS fragments of two transposing reads each, waited for in pairs
-  constexpr int VRS = 6;
-  u32x2_t vlo[VRS], vhi[VRS];
-  auto v_issue = [&](auto sgc, auto ic) {
-    constexpr int SG = decltype(sgc)::value;
-    constexpr int i = decltype(ic)::value;
-    constexpr int st = i / NDB, db = i % NDB;
-    constexpr int base = (SG < 0 ? 0 : SG * STB) + st * 16 * ROWB + (db >> 2) * 256;
-    u32x2_t &l = vlo[i % VRS], &h = vhi[i % VRS];
-    lds_read_tr16_b64<base>(l, va[db & 3][0]);
-    lds_read_tr16_b64<base + 8 * ROWB>(h, va[db & 3][1]);
-  };
-  auto v_wait = [&](auto ic) {  // before step i (i even): fragments i, i+1 have arrived
-    constexpr int i = decltype(ic)::value;
-    constexpr int issued_f = (i + VRS < NP ? i + VRS : NP);
-    constexpr int need = (i + 2 < NP ? i + 2 : NP);
-    u32x2_t &l0 = vlo[i % VRS], &h0 = vhi[i % VRS], &l1 = vlo[(i + 1) % VRS], &h1 = vhi[(i + 1) % VRS];
-    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(l0), "+v"(h0), "+v"(l1), "+v"(h1) : "n"(2 * (issued_f - need)));
-  };
-  uint32_t pkw[TOK / 16][4];  // bf16 weight pairs: B operands of the 16-token contraction steps
-  auto v_mfma = [&](auto sgc, auto ic) {
-    constexpr int i = decltype(ic)::value;
-    if constexpr (i < NP) {
-      constexpr int st = i / NDB, db = i % NDB;
-      const u32x4_t a4 = {vlo[i % VRS][0], vlo[i % VRS][1], vhi[i % VRS][0], vhi[i % VRS][1]};
-      const u32x4_t b4 = {pkw[st][0], pkw[st][1], pkw[st][2], pkw[st][3]};
-      mfma_acc_a(o[db], a4, b4);
-      if constexpr (i + VRS < NP) v_issue(sgc, std::integral_constant<int, i + VRS>{});
-    } else {
-      const u32x4_t b4 = {pkw[i - NP][0], pkw[i - NP][1], pkw[i - NP][2], pkw[i - NP][3]};
-      mfma_acc_a(o_one, ones_bits, b4);
-    }
-  };
-
-  // softmax of one tile: three-deep software pipeline over its NE scores
-  float neg_m = 0.f, lsum = 0.f;
-  float sx[NE + 1], sp[NE + 1];
-  auto sm_slot = [&](auto qc, f32x16_t (&sc)[NTB]) {
-    constexpr int q = decltype(qc)::value;
-    constexpr int e = q - 2;  // element whose weight is summed (and maybe packed) in this slot
-    constexpr bool pack = e >= 1 && (e & 1) == 1;
-    constexpr int pi = e >= 0 ? (e / 16) * 2 + ((e % 16) >> 3) : 0, pj = e >= 0 ? (e & 7) >> 1 : 0;
-    if constexpr (q == 0) {
-      sm_ops_f(sx[0], sc[0][0], sc2, neg_m);
-    } else if constexpr (q == 1) {
-      sm_ops_fe(sx[1], sc[1 / 16][1 % 16], sc2, neg_m, sp[0], sx[0]);
-    } else if constexpr (q < NE) {
-      if constexpr (pack) sm_ops_feac(sx[q], sc[q / 16][q % 16], sc2, neg_m, sp[q - 1], sx[q - 1], lsum, sp[e], pkw[pi][pj], sp[e - 1]);
-      else sm_ops_fea(sx[q], sc[q / 16][q % 16], sc2, neg_m, sp[q - 1], sx[q - 1], lsum, sp[e]);
-    } else if constexpr (q == NE) {
-      if constexpr (pack) sm_ops_eac(sp[q - 1], sx[q - 1], lsum, sp[e], pkw[pi][pj], sp[e - 1]);
-      else sm_ops_ea(sp[q - 1], sx[q - 1], lsum, sp[e]);
-    } else {
-      if constexpr (pack) sm_ops_ac(lsum, sp[e], pkw[pi][pj], sp[e - 1]);
-      else sm_ops_a(lsum, sp[e]);
-    }
-  };
-  constexpr int NQ = NE + 2;                            // pipeline slots
-  constexpr int S0 = NS >= 16 ? 4 : (NS >= 8 ? 2 : 1);  // score steps that overlap the row-max search
-  // Without a score exchange between waves (KS == 1) the masking and the row max
-  // of a tile are computed one phase early, under the value MFMAs of the tile
-  // before it, where the vector ALU is otherwise idle.
-  constexpr bool kEarlyMax = KS == 1;
-  constexpr int SA = kEarlyMax ? 0 : S0;                // first score step that carries softmax slots
-  constexpr int IW = ((NS - 1) / 4) * 4;                // step of the last wait for score operands
-  constexpr int VPRE = VRS < NP ? VRS : NP;             // value operands requested ahead of [B]
-  constexpr int MXS = 4;                                // [B] steps over which the row-max chain is spread
-  static_assert(2 + MXS <= NB, "row-max steps fit into [B]");
-  float mx_carry = -INFINITY;                           // kEarlyMax: lane-local max of the next tile's scores
-  auto mask_tile = [&](f32x16_t (&sc)[NTB], int tile_j) {
-    const int tile_tok0 = tile_j * TOK;
-    if (tile_tok0 + TOK > n_vis_min) {
-      const int lim = n_vis - tile_tok0 - 4 * hi;  // element (tb, i) is visible iff its constant < lim
-#pragma unroll
-      for (int tb = 0; tb < NTB; ++tb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          sc[tb][i] = (32 * tb + 8 * (i >> 2) + (i & 3)) < lim ? sc[tb][i] : -INFINITY;
-    }
-  };
-
-  // KS = 2: the two waves of a row slab hold partial scores (each over its share
-  // of the contraction dims).  Each posts its 16 values per lane in its own
-  // mailbox; after the next workgroup barrier it adds its partner's to its own
-  // (both get bit-identical sums: a + b == b + a), and a second barrier lets
-  // the mailboxes be overwritten.
-  const unsigned xchg_mine = lds_base + (unsigned)(TT::kXchgBase + wave * 4096 + lane * 16);
-  const unsigned xchg_peer = lds_base + (unsigned)(TT::kXchgBase + (wave ^ 1) * 4096 + lane * 16);
-  auto xchg_post = [&](f32x16_t (&sc)[NTB]) {
-    if constexpr (KS > 1) {
-      static_assert(NTB == 1, "mailbox holds one 32-token block");
-      // MFMA results are read by the LDS stores below.  The wait is tied to the
-      // accumulator so that no copy of it can be scheduled ahead of the wait.
-      asm volatile("s_nop 15" : "+v"(sc[0]));
-      static_for<0, 4>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        // (vector elements go through scalars: a bit cast applied directly to an
-        // element of a vector reads the vector's first element)
-        const float f0 = sc[0][4 * i], f1 = sc[0][4 * i + 1], f2 = sc[0][4 * i + 2], f3 = sc[0][4 * i + 3];
-        const u32x4_t v = {__builtin_bit_cast(uint32_t, f0), __builtin_bit_cast(uint32_t, f1),
-                           __builtin_bit_cast(uint32_t, f2), __builtin_bit_cast(uint32_t, f3)};
-        lds_write_b128<i * 1024>(xchg_mine, v);
-      });
-    }
-  };
-  u32x4_t xin[4];
-  auto xchg_fetch = [&]() {  // issue the reads of the partner's mailbox
-    if constexpr (KS > 1) static_for<0, 4>([&](auto ic) { lds_read_b128<decltype(ic)::value * 1024>(xin[decltype(ic)::value], xchg_peer); });
-  };
-  auto xchg_add = [&](f32x16_t (&sc)[NTB]) {  // call with exactly the RS score-operand reads issued after xchg_fetch
-    if constexpr (KS > 1) {
-      asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(xin[0]), "+v"(xin[1]), "+v"(xin[2]), "+v"(xin[3]) : "n"(RS < NS ? RS : NS));
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const uint32_t u = xin[i >> 2][i & 3];
-        sc[0][i] += __builtin_bit_cast(float, u);
-      }
-      asm volatile("s_barrier" ::: "memory");
-    }
-  };
-  // One tile: [A] softmax of tile k (scores in s_rd) under the score MFMAs of
-  // tile k+1 (into s_wr), then [B] value MFMAs of tile k under the loads of tile
-  // k + STAGES - 1.  k: chunk-local tile index, tile_j: index in the unit, PSG /
-  // SSG: stage of tile k / of tile k+1 (or -1, see above), pv_stage: stage of tile k.
-#ifdef GLA_EXPERIMENT_PHASE_CLOCKS
-  // experiment build: core-clock time of wave 0 spent in the phases of the tile loop
-  long long ph_acc[4] = {0, 0, 0, 0};
-  long long ph_t = 0;
-  int ph_n = 0;
-#define GLA_PHASE(i) do { const long long t_ = (long long)clock64(); ph_acc[i] += t_ - ph_t; ph_t = t_; } while (0)
-#else
-#define GLA_PHASE(i) do { } while (0)
-#endif
-  auto tile_iter = [&](f32x16_t (&s_rd)[NTB], f32x16_t (&s_wr)[NTB], int k, int tile_j, bool has_next, int seg_L) {
-#ifdef GLA_EXPERIMENT_PHASE_CLOCKS
-    ph_t = (long long)clock64();
-    ++ph_n;
-#endif
-    constexpr std::integral_constant<int, -1> psgc{}, ssgc{};  // stages live in the address registers
-    const int pv_stage = k % STAGES;
-    // ---- tile k+1 landed?  (also: every wave is done with tile k-1, so its stage is free)
-    if (has_next) {
-      if (issued - 2 - k >= STAGES - 3) wait_vmcnt<LPW * (STAGES - 3)>();
-      else wait_vmcnt<0>();
-    }
-    lds_barrier();
-    GLA_PHASE(0);
-    if (has_next) zero_tail((pv_stage + 1) % STAGES, tile_j + 1, seg_L);
-
-#ifdef GLA_EXPERIMENT_NO_COMPUTE
-    dma_prepare((pv_stage + STAGES - 1) % STAGES);
-    static_for<0, LPW>(dma_load);
-    (void)s_rd; (void)s_wr; (void)tile_j;
-    return;
-#endif
-    // ---- [A] first score steps of tile k+1 (without a next tile they read
-    //          whatever is in that stage and the result is dropped), under the
-    //          masking and row-max search of tile k
-    xchg_fetch();
-    static_for<0, (RS < NS ? RS : NS)>([&](auto ic) { s_issue(ssgc, ic); });
-    xchg_add(s_rd);
-    float mx;
-    if constexpr (kEarlyMax) {
-      // masking and row max of tile k were done while the previous tile's value
-      // MFMAs ran (or in the segment prologue): only the cross-half step is left
-      mx = half_swap_max(mx_carry) * sc2;
-    } else {
-      mask_tile(s_rd, tile_j);
-      mx = -INFINITY;
-      pin_arch(mx);
-      static_for<0, S0>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        if constexpr (i % 4 == 0) s_wait(ic);
-        constexpr int e0 = (i * NE) / S0, e1 = ((i + 1) * NE) / S0;
-        static_for<e0 / 2, e1 / 2>([&](auto jc) {
-          constexpr int e = 2 * decltype(jc)::value;
-          asm_max3(mx, s_rd[e / 16][e % 16], s_rd[(e + 1) / 16][(e + 1) % 16]);
-        });
-        s_mfma(ssgc, ic, s_wr);
-        __builtin_amdgcn_sched_barrier(0);
-      });
-      mx = half_swap_max(mx) * sc2;
-    }
-    // lazy reference update: keep the old reference while the row max stays
-    // within 2^8 of it (weights then stay <= 256, exact enough in fp32 / bf16)
-    const bool bump = mx > m_ref + 8.0f;
-    if (__ballot(bump)) {
-      wait_states<16>();  // output accumulators are about to be read by the vector ALU
-      const float m_new = bump ? mx : m_ref;
-      const float alpha = bump ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.0f;  // m_ref = -inf -> 0
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < NDB; ++db) {  // one 16-register block at a time through the vector ALU
-        f32x16_t t = o[db];
-        pin_arch(t);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) t[i] *= alpha;
-        o[db] = t;
-        pin_acc(o[db]);
-      }
-      {
-        f32x16_t t = o_one;
-        pin_arch(t);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) t[i] *= alpha;
-        o_one = t;
-        pin_acc(o_one);
-      }
-      m_ref = m_new;
-    }
-    neg_m = m_ref == -INFINITY ? 0.f : -m_ref;
-    lsum = 0.f;
-    pin_arch(neg_m);
-    pin_arch(lsum);
-    GLA_PHASE(1);
-    // ---- [A] (remaining) score steps of tile k+1 under the exponentials of tile k.
-    //          Once the last score operands have been waited for, the first value
-    //          operands of [B] are requested so that they arrive under these MFMAs.
-    static_for<SA, NS>([&](auto ic) {
-      constexpr int i = decltype(ic)::value;
-      if constexpr (i % 4 == 0) s_wait(ic);
-      constexpr int q0 = ((i - SA) * NQ) / (NS - SA), q1 = ((i - SA + 1) * NQ) / (NS - SA);
-      static_for<q0, q1>([&](auto qc) { sm_slot(qc, s_rd); });
-      s_mfma(ssgc, ic, s_wr);
-      if constexpr (i >= IW)
-        static_for<((i - IW) * VPRE) / (NS - IW), ((i - IW + 1) * VPRE) / (NS - IW)>([&](auto jc) { v_issue(psgc, jc); });
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    l_run += lsum;
-    xchg_post(s_wr);
-    GLA_PHASE(2);
-
-    // ---- [B] O^T += V^T . P^T for tile k under the loads of the tile that reuses
-    //          the stage of tile k-1.  Contraction slot (hi, j) of step st is token
-    //          16*st + 8*(j/4) + 4*hi + j%4, matching the score accumulator layout.
-    //          The address registers move on to the next stages in the gaps.
-    const bool s_wrap = (pv_stage + 2) % STAGES == 0, v_wrap = (pv_stage + 1) % STAGES == 0;
-    const int k_step = s_wrap ? -(STAGES - 1) * STB : STB, r_step = s_wrap ? -(STAGES - 1) * RTB : RTB;
-    const int v_step = v_wrap ? -(STAGES - 1) * STB : STB;
-    wait_states<2>();  // the last weights were packed by the vector ALU just above
-    static_for<0, NB>([&](auto ic) {
-      constexpr int i = decltype(ic)::value;
-      if constexpr (i < NP && i % 2 == 0) v_wait(ic);
-      v_mfma(psgc, ic);
-      if constexpr (kEarlyMax) {  // masking and lane-local row max of tile k+1 (its scores are complete)
-        if constexpr (i == 1) {
-          if (has_next) mask_tile(s_wr, tile_j + 1);
-          mx_carry = -INFINITY;
-          pin_arch(mx_carry);
-        } else if constexpr (i >= 2 && i < 2 + MXS) {
-          static_for<((i - 2) * (NE / 2)) / MXS, ((i - 1) * (NE / 2)) / MXS>([&](auto jc) {
-            constexpr int e = 2 * decltype(jc)::value;
-            asm_max3(mx_carry, s_wr[e / 16][e % 16], s_wr[(e + 1) / 16][(e + 1) % 16]);
-          });
-        }
-      }
-      // preparation of the next loads in the first steps, the loads themselves after it
-      if constexpr (i == 0) dma_prepare_0((pv_stage + STAGES - 1) % STAGES);
-      else if constexpr (i == 1) dma_prepare_1();
-      else if constexpr (i == 2) dma_prepare_2();
-      else static_for<((i - 3) * LPW) / (NB - 3), ((i - 2) * LPW) / (NB - 3)>(dma_load);
-      // score addresses: next used in the next tile's [A]
-      static_for<(i * (8 + NKR)) / NB, ((i + 1) * (8 + NKR)) / NB>([&](auto ec) {
-        constexpr int e = decltype(ec)::value;
-        if constexpr (e < 8) ka[e] += k_step;
-        else ra[e - 8] += r_step;
-      });
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    // value addresses: every read of this tile has been issued
-#pragma unroll
-    for (int d4 = 0; d4 < 4; ++d4)
-#pragma unroll
-      for (int a = 0; a < 2; ++a) va[d4][a] += v_step;
-    GLA_PHASE(3);
-  };
-  // the two score register sets: tile t of a segment reads the one tile t-1 wrote
-  f32x16_t s_even[NTB], s_odd[NTB];
-  int k = 0;  // chunk-local index of the tile at `cur`
-  while (k < n_tiles) {
-    // ================= segment: the tiles of cur's unit that lie in this chunk
-    const int seg_n = min(n_tiles - k, cur.tiles_b - cur.j);
-    const int seg_j0 = cur.j;
-    const int seg_L = cur.L;
-    const int seg_tiles_b = cur.tiles_b;
-    const int seg_unit = (cur.b * UPB + cur.ub) * MB + mb_wg;  // index of this (unit, row block)
-    // Query fragments of this unit.  The wait follows at once (it also covers the
-    // tiles already requested): the registers the loads write must not be
-    // touched, not even copied, before the data has arrived, and only a wait
-    // right behind the requests guarantees that.
-    q_issue();
-    wait_vmcnt<0>();
-    {
-#pragma unroll
-      for (int ks = 0; ks < NKN; ++ks) pin_acc(qn[ks]);
-#pragma unroll
-      for (int ks = 0; ks < NKR; ++ks) pin_acc(qr[ks]);
-#pragma unroll
-      for (int db = 0; db < NDB; ++db) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-        pin_acc(o[db]);
-      }
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o_one[i] = 0.f;
-      pin_acc(o_one);
-      m_ref = -INFINITY;
-      l_run = 0.f;
-      // visible keys of this lane's row; padding rows are left unmasked (never stored)
-      n_vis = row_valid ? (p.causal ? cur.L - p.T + 1 + row_t : cur.L) : 0x7fffffff;
-      // the smallest count of the wave: its first row (lane 0) has the earliest query position
-      n_vis_min = __builtin_amdgcn_readlane(n_vis, 0);
-    }
-
-    // ---- segment prologue: point the address registers at the stages of tile k
-    //      (value reads) and, after its scores are done, of tile k+1 (score reads)
-    lds_barrier();
-    zero_tail(k % STAGES, seg_j0, seg_L);
-    {
-      const int ss = k % STAGES;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) ka[e] = k_off[e] + ss * STB;
-#pragma unroll
-      for (int e = 0; e < NKR; ++e) ra[e] = r_off[e] + ss * RTB;
-#pragma unroll
-      for (int d4 = 0; d4 < 4; ++d4)
-#pragma unroll
-        for (int a = 0; a < 2; ++a) va[d4][a] = v_off[d4][a] + ss * STB;
-      constexpr std::integral_constant<int, -1> rt{};
-      static_for<0, (RS < NS ? RS : NS)>([&](auto ic) { s_issue(rt, ic); });
-      static_for<0, NS>([&](auto ic) {
-        if constexpr (decltype(ic)::value % 4 == 0) s_wait(ic);
-        s_mfma(rt, ic, s_even);
-      });
-      const bool wrap = (ss + 1) % STAGES == 0;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) ka[e] += wrap ? -(STAGES - 1) * STB : STB;
-#pragma unroll
-      for (int e = 0; e < NKR; ++e) ra[e] += wrap ? -(STAGES - 1) * RTB : RTB;
-    }
-    // the scores are read by the vector ALU next; the wait is tied to them so
-    // that no read can be scheduled ahead of it
-    asm volatile("s_nop 15" : "+v"(s_even[0]));
-    if constexpr (kEarlyMax) {
-      mask_tile(s_even, seg_j0);
-      mx_carry = -INFINITY;
-      pin_arch(mx_carry);
-      static_for<0, NE / 2>([&](auto jc) {
-        constexpr int e = 2 * decltype(jc)::value;
-        asm_max3(mx_carry, s_even[e / 16][e % 16], s_even[(e + 1) / 16][(e + 1) % 16]);
-      });
-    }
-    xchg_post(s_even);
-    if (k == 0) GLA_STAMP(3);
-
-    // two tiles per trip so that the two score register sets swap roles without copies
-    for (int t = 0; t < seg_n; t += 2) {
-      tile_iter(s_even, s_odd, k, seg_j0 + t, t + 1 < seg_n, seg_L);
-      if (k == 0) GLA_STAMP(7);
-      ++k;
-      if (t + 1 < seg_n) {
-        tile_iter(s_odd, s_even, k, seg_j0 + t + 1, t + 2 < seg_n, seg_L);
-        ++k;
-      }
-    }
-    for (int i = 0; i < seg_n; ++i) advance<TOK>(p, UPB, cur);
-    GLA_STAMP(4);
-
-    // ================= end of segment: write the unit's result or its partial
-    wait_states<16>();  // output accumulators: last MFMA -> vector ALU reads
-    {
-      const bool unit_done = seg_j0 + seg_n == (seg_L + TOK - 1) / TOK;
-      const bool complete = unit_done && seg_j0 == 0;
-      const float l_tot = half_swap_sum(l_run);
-      f32x16_t one_t = o_one;
-      pin_arch(one_t);
-      const float r_tot = one_t[0];
-      const float inv = r_tot > 0.f ? 1.0f / r_tot : 0.f;
-#ifdef GLA_EXPERIMENT_NO_STORES
-      if (inv != 12345.678f) continue;  // experiment build: results are computed and dropped
-#endif
-      const float lse = l_tot > 0.f ? (m_ref + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
-      const int lr = wave * 32 + col;
-      const int64_t ob = row_b * p.out_s[0] + row_t * p.out_s[1] + row_h * p.out_s[2];
-      // partial: slot 1 if the unit's first tile is in this chunk, slot 0 if it began earlier
-      float* slot = p.ws_out + (((size_t)chunk_id * MB + mb_wg) * 2 + (seg_j0 == 0 ? 1 : 0)) * TT::kSlotFloats;
-      if (seg_j0 == 0 && tid == 0) {
-        // tell the merge kernel which chunks hold this unit: it starts here and
-        // ends in the chunk of its last tile
-        const int s_u = c0 + (k - seg_n);
-        int2 span;
-        span.x = chunk_id;
-        span.y = (s_u + seg_tiles_b - 1) / chunk;
-        ((int2*)p.ws_lse)[seg_unit] = span;
-      }
-      if (hi == 0) {
-        if (!complete) slot[(size_t)TT::kRows * DV + lr] = lse;
-        else if (row_valid && kx == 0) p.lse[((int64_t)row_b * p.T + row_t) * p.h_q + row_h] = lse;
-      }
-#pragma unroll
-      for (int db = 0; db < NDB; ++db) {  // one 16-register block at a time
-        f32x16_t t16 = o[db];
-        pin_arch(t16);
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int dim = kx * DVW + 32 * db + 8 * q4 + 4 * hi;
-          const f32x4_t v = {t16[4 * q4] * inv, t16[4 * q4 + 1] * inv, t16[4 * q4 + 2] * inv, t16[4 * q4 + 3] * inv};
-          if (!complete) {
-            // fragment order: one contiguous 1 KiB block per (wave, db, q4), lane-linear
-            *(f32x4_t*)(slot + (size_t)((wave * NDB + db) * 4 + q4) * 256 + lane * 4) = v;
-          } else if (row_valid) {
-            if (p.out_fp32) {
-              *(f32x4_t*)((float*)p.out + ob + dim) = v;
-            } else {
-              u32x2_t pk;
-              pk[0] = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
-              pk[1] = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
-              *(u32x2_t*)((uint16_t*)p.out + ob + dim) = pk;
-            }
-          }
-        }
-      }
-    }
-    GLA_STAMP(5);
-  }
-  GLA_STAMP(6);
-#ifdef GLA_EXPERIMENT_PHASE_CLOCKS
-  if (tid == 0) {
-    long long* const out_ph = (long long*)((char*)p.ws_out + (194ll << 20)) + (size_t)blockIdx.x * 8;
-    for (int i = 0; i < 4; ++i) out_ph[i] = ph_acc[i];
-    out_ph[4] = ph_n;
-  }
-#endif
-}
-#undef GLA_STAMP
-#undef GLA_PHASE
-
-// Merge of the partial results of units that span several chunks, and zero fill
-// of units without any key:  lse = ln sum_s exp(lse_s),
-// out = sum_s exp(lse_s - lse) out_s.  The main kernel leaves, per unit, the
-// range of chunks that hold it, and stores partial outputs in the register
-// order of its waves (one contiguous 1 KiB block per wave, 32-dim block and
-// quarter), so a task here is one (32-row slab, 32-dim block) of a unit and
-// every access of a partial is a full 1 KiB line run.  The KW waves of a
-// workgroup share one task: wave j merges chunks first + j, first + j + KW, ...
-// around its own reference, and the KW results are merged once more through
-// LDS (long single sequences are cut into hundreds of chunks).
-// Grid (units, NG * WPG * DV / 32), KW waves per workgroup.
-template <int DV, int NG, int WPG, int KS, int TOK, int KW>
-__global__ __launch_bounds__(64 * KW) void tuned_combine_kernel(DevParams p) {
-  constexpr int NWAVES = NG * WPG * KS;
-  constexpr int NDB = DV / KS / 32;  // 32-dim blocks per wave of the main kernel
-  constexpr int kRows = 32 * NG * WPG;
-  constexpr size_t kSlotFloats = (size_t)kRows * DV + 32 * NWAVES;
-  static_assert(KW == 1 || KW == 4 || KW == 16, "waves per task");
-  __shared__ float red_m[KW][64], red_z[KW][64];
-  __shared__ f32x4_t red_a[KW][4][64];
-  const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
-  const int col = lane & 31, hi = lane >> 5;
-#ifdef GLA_EXPERIMENT_TIMESTAMPS
-  if (tid == 0)
-    ((long long*)((char*)p.ws_out + (193ll << 20)))[blockIdx.y * gridDim.x + blockIdx.x] = (long long)wall_clock64();
-#endif
-  const int wv = blockIdx.y;
-  const int w = wv / NDB, db = wv - w * NDB;  // wave of the main kernel and one of its 32-dim blocks
-  const int wpos = w % (WPG * KS), kx = wpos % KS;
-  const int rows_group = p.g_q * p.T;
-  const int MB = p.mb;
-  const int UPB = p.upb * MB;
-  const int unit = blockIdx.x;  // (sequence, group block, row block)
-  const int b = (int)fast_div((unsigned)unit, p.fd_upb_mb);
-  const int ub = unit - b * UPB;
-  const int gb = (int)fast_div((unsigned)ub, p.fd_mb), mb = ub - gb * MB;
-  const int L = p.seq_lens[b];
-  const int2 span = ((const int2*)p.ws_lse)[unit];  // garbage for units without tiles: not used then
-  const bool empty = tiles_of<TOK>(L) == 0;
-  if (!empty && span.x == span.y) return;  // written directly by the main kernel (whole workgroup leaves)
-  const int g = gb * NG + w / (WPG * KS);
-  const int R = (mb * WPG + wpos / KS) * 32 + col;
-  const bool valid = R < rows_group;
-  const int Rc = valid ? R : 0;
-  const int t = (int)fast_div((unsigned)Rc, p.fd_gq);
-  const int h = g * p.g_q + (Rc - t * p.g_q);
-  const int r = w * 32 + col;  // this lane's entry among the slot's log-sum-exps
-  // Chunk span.x holds the unit's first tile (partial slot 1); every later
-  // chunk sees a unit that began before it (slot 0).
-  const int k_first = empty ? 0 : span.x, k_last = empty ? -1 : span.y;
-  auto slot_of = [&](int k) { return (((size_t)k * MB + mb) * 2 + (k == k_first)) * kSlotFloats; };
-  const float* const lse0 = p.ws_out + (size_t)kRows * DV + r;
-  const float* const frag0 = p.ws_out + (size_t)((w * NDB + db) * 4) * 256 + lane * 4;
-
-  // this wave's share: reference = its own maximum
-  float m = -INFINITY;
-#pragma unroll 4
-  for (int k = k_first + kw; k <= k_last; k += KW) m = fmaxf(m, lse0[slot_of(k)]);
-  float z = 0.f;
-  f32x4_t acc[4];
-#pragma unroll
-  for (int q4 = 0; q4 < 4; ++q4) acc[q4] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  if (m != -INFINITY) {
-#pragma unroll 2
-    for (int k = k_first + kw; k <= k_last; k += KW) {
-      const size_t so = slot_of(k);
-      const float ls = lse0[so];
-      // a slot marked "no key" may hold anything: its values are dropped, not multiplied by zero
-      const bool live = ls != -INFINITY;
-      const float wgt = live ? expf(ls - m) : 0.f;
-      z += wgt;
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const f32x4_t v = *(const f32x4_t*)(frag0 + so + q4 * 256);
-        acc[q4] += wgt * (live ? v : f32x4_t{0.f, 0.f, 0.f, 0.f});
-      }
-    }
-  }
-  // merge of the KW shares; wave q4 < 4 then finishes quarter q4 of the block
-  float lse;
-  f32x4_t res;
-  int q_mine;
-  if constexpr (KW == 1) {
-    lse = m == -INFINITY ? -INFINITY : m + logf(z);
-    const float inv = z > 0.f ? 1.0f / z : 0.f;
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) acc[q4] *= inv;
-    q_mine = -1;  // all four quarters, below
-    res = acc[0];
-  } else {
-    red_m[kw][lane] = m;
-    red_z[kw][lane] = z;
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) red_a[kw][q4][lane] = acc[q4];
-    __syncthreads();
-    if (kw >= 4) return;
-    q_mine = kw;
-    float mm = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < KW; ++j) mm = fmaxf(mm, red_m[j][lane]);
-    float zz = 0.f;
-    res = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    if (mm != -INFINITY) {
-#pragma unroll
-      for (int j = 0; j < KW; ++j) {
-        const float mj = red_m[j][lane];
-        const float e = mj == -INFINITY ? 0.f : expf(mj - mm);
-        zz += e * red_z[j][lane];
-        res += e * red_a[j][q_mine][lane];
-      }
-    }
-    lse = mm == -INFINITY ? -INFINITY : mm + logf(zz);
-    res *= zz > 0.f ? 1.0f / zz : 0.f;
-  }
-  if (!valid) return;
-  if (db == 0 && hi == 0 && kx == 0 && q_mine <= 0) p.lse[((int64_t)b * p.T + t) * p.h_q + h] = lse;
-  const int64_t ob = b * p.out_s[0] + t * p.out_s[1] + h * p.out_s[2];
-#pragma unroll
-  for (int q4 = 0; q4 < 4; ++q4) {
-    if (q_mine >= 0 && q4 != q_mine) continue;
-    const f32x4_t v = q_mine >= 0 ? res : acc[q4];
-    const int dim = kx * (DV / KS) + 32 * db + 8 * q4 + 4 * hi;
-    if (p.out_fp32) {
-      *(f32x4_t*)((float*)p.out + ob + dim) = v;
-    } else {
-      u32x2_t pk;
-      pk[0] = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
-      pk[1] = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
-      *(u32x2_t*)((uint16_t*)p.out + ob + dim) = pk;
-    }
-  }
-}
-
-// ---- host side ---------------------------------------------------------------
-
-struct TunedPlan {
-  int dv, dn;      // state dims (value / score)
-  int ng, wpg, ks; // groups per workgroup, row slabs per group, waves per row slab
-  int tok, stages; // tile tokens and pipeline depth of the chosen instantiation
-  int rows;        // 32 * ng * wpg
-  int mb;          // row blocks per (sequence, group)
-  int units;       // batch * (h_c / ng) * mb
-  int num_chunks;  // chunks of the tile list; the main-kernel grid is num_chunks * mb
-  int chunk_tiles; // fixed tiles per chunk, 0: derived on the device
-  size_t slot_floats;
-};
-
-inline int device_cu_count() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      cus = n;
-    else
-      cus = 256;  // MI355X
-  }
-  return cus;
-}
-
-inline bool aligned16(const void* ptr) { return ((uintptr_t)ptr & 15u) == 0; }
-
-// Tile tokens and pipeline depth of the instantiation for a shape: the deepest
-// even ring (at most 8 stages) that fits the LDS and whose loads in flight per
-// wave stay countable by the 6-bit vmcnt.
-constexpr int kTok = 32;
-constexpr int kMinChunkTiles = 4;
-constexpr int tuned_stages(int dv, int ng, int wpg, int ks, bool lane = false) {
-  const int stage_bytes = ng * kTok * dv * 2 + kTok * 128;
-  // besides the tiles: score mailboxes (ks > 1), page-id windows (pages of 8 tokens or fewer)
-  const int mailboxes = (ks > 1 ? ng * wpg * ks * 4096 : 0) + (lane ? ng * wpg * ks * 2 * kPageWindow * 4 : 0);
-  const int loads_per_wave = (kTok * dv * 2 / 1024) / (wpg * ks) + (kTok * 128 / 1024) / (ng * wpg * ks);
-  int st = 8;
-  while (st > 4 && (st * stage_bytes + mailboxes > 160 * 1024 || loads_per_wave * (st - 2) > 63)) st -= 2;
-  return st;
-}
-
-inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) {
-  const int ps = p->page_size;
-  if (ps < 1 || ps > 64 || (ps & (ps - 1)) || p->d_rope != 64) return false;  // 64, 32, ..., 1 tokens
-  const bool lane = ps < 16;  // addresses per row and lane
-  if (!(p->softmax_scale > 0.f)) return false;  // row maxima are taken on the raw dot products
-  if (!((!is_gta && (p->d_v == 256 || p->d_v == 512)) || (is_gta && p->d_v == 128))) return false;
-  // layout the kernels assume: token rows contiguous, everything 16-byte aligned
-  if (p->state_stride[2] != p->d_v || p->rope_stride[1] != p->d_rope) return false;
-  if (p->state_stride[0] % 8 || p->state_stride[1] % 8 || p->rope_stride[0] % 8) return false;
-  if (p->state_stride[0] < 0 || p->state_stride[1] < 0 || p->rope_stride[0] < 0 ||
-      p->state_stride[0] >= (1ll << 30) || p->state_stride[1] >= (1ll << 30) || p->rope_stride[0] >= (1ll << 30))
-    return false;  // page / group strides are handled as 32-bit byte counts
-  if (p->num_pages >= (1ll << 31)) return false;
-  for (int i = 0; i < 3; ++i)
-    if (p->q_nope_stride[i] % 8 || p->q_rope_stride[i] % 8 || p->out_stride[i] % 4) return false;
-  if (p->q_nope && !(aligned16(p->q_nope) && aligned16(p->q_rope) && aligned16(p->state_cache) &&
-                     aligned16(p->rope_cache) && aligned16(p->out)))
-    return false;
-  const int rows_group = (p->num_q_heads / p->num_groups) * p->q_len;
-  // waves per group from the rows of a group, then as many groups per workgroup
-  // as four waves allow (they share one RoPE-key tile)
-  // A latent of 512 dims needs two waves per row slab: 32 rows x 512 fp32
-  // output accumulators alone would fill a wave's accumulation registers.
-  const int ks = p->d_v > 256 ? 2 : 1;
-  // (a 512-dim latent with small pages: one row slab per workgroup, because the
-  // tile ring and the score mailboxes of two slabs leave no LDS for the page-id
-  // windows; the row blocks of a group then run as separate workgroups)
-  const int wpg = (rows_group <= 32 || (ks == 2 && lane)) ? 1 : ((rows_group <= 64 || ks == 2) ? 2 : 4);
-  int ng = 4 / (wpg * ks);
-  while (ng > 1 && (p->num_groups % ng || 4 * (ng * 32 * p->d_v * 2 + 32 * 128) > 160 * 1024)) ng >>= 1;
-  plan->dv = p->d_v;
-  plan->dn = p->d_nope;
-  plan->ng = ng;
-  plan->wpg = wpg;
-  plan->ks = ks;
-  plan->rows = 32 * ng * wpg;
-  plan->mb = (rows_group + 32 * wpg - 1) / (32 * wpg);
-  plan->units = p->batch * (p->num_groups / ng) * plan->mb;
-  const int tok = kTok, stages = tuned_stages(p->d_v, ng, wpg, ks, lane);
-  // co-resident workgroups per CU: one wave per SIMD, 160 KiB of LDS
-  const int smem = stages * (ng * tok * p->d_v * 2 + tok * 128) + (ks > 1 ? ng * wpg * ks * 4096 : 0) +
-                   (lane ? ng * wpg * ks * 2 * kPageWindow * 4 : 0);
-  if (smem > 160 * 1024) return false;  // (512-dim latent, two row slabs, small pages: no room for the page-id windows)
-  const int per_cu = std::max(1, std::min((160 * 1024) / smem, 4 / (ng * wpg * ks)));
-  plan->tok = tok;
-  plan->stages = stages;
-  // the tile list holds each (sequence, group block) once; every chunk of it is
-  // worked on by mb workgroups (one per row block), so the grid is num_chunks * mb
-  const int64_t max_tiles = ((int64_t)p->max_pages_per_seq * p->page_size + tok - 1) / tok;
-  const int64_t bound = (int64_t)(plan->units / plan->mb) * max_tiles;
-  if (bound * plan->mb > 0x3fffffff) return false;
-  if (p->num_splits > 0) {
-    plan->chunk_tiles = (int)((max_tiles + p->num_splits - 1) / p->num_splits);
-    plan->num_chunks = (int)std::max<int64_t>(1, (bound + plan->chunk_tiles - 1) / plan->chunk_tiles);
-  } else {
-    plan->chunk_tiles = 0;
-    // one chunk per resident workgroup, but no chunk shorter than kMinChunkTiles
-    // (by the upper bound on the list length): a partial costs as much memory
-    // traffic as three or four tiles, and every extra chunk is one more to merge
-    const int64_t resident = std::max<int64_t>(1, (int64_t)device_cu_count() * per_cu / plan->mb);
-    const int64_t by_length = std::max<int64_t>(1, bound / kMinChunkTiles);
-    plan->num_chunks = (int)std::max<int64_t>(1, std::min<int64_t>(by_length, resident));
-  }
-  plan->slot_floats = (size_t)plan->rows * p->d_v + (size_t)32 * ng * wpg * ks;
-  return true;
-}
-
-inline bool tuned_supported(const gla_decode_params* p, int is_gta) {
-  TunedPlan plan;
-  return tuned_plan(p, is_gta, &plan);
-}
-
-// Workspace: two partial slots per chunk, then per unit the chunk range holding it.
-inline size_t tuned_slots_bytes(const TunedPlan& plan) {
-  return (((size_t)plan.num_chunks * plan.mb * 2 * plan.slot_floats * sizeof(float)) + 255) & ~(size_t)255;
-}
-
-inline size_t tuned_workspace(const gla_decode_params* p, int is_gta) {
-  TunedPlan plan;
-  if (!tuned_plan(p, is_gta, &plan)) return 0;
-  return tuned_slots_bytes(plan) + (size_t)plan.units * 2 * sizeof(int32_t);
-}
-
-template <int DV, int DN, int NG, int WPG, int KS, int TOK>
-inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
-  constexpr int STAGES = tuned_stages(DV, NG, WPG, KS), STAGES_LANE = tuned_stages(DV, NG, WPG, KS, true);
-  constexpr bool kLaneFits = STAGES_LANE * (NG * TOK * DV * 2 + TOK * 128) + (KS > 1 ? NG * WPG * KS * 4096 : 0) +
-                             NG * WPG * KS * 2 * kPageWindow * 4 <= 160 * 1024;
-  if (ev) (void)hipEventRecord(ev[0], st);
-  const dim3 mgrid(plan.num_chunks * plan.mb), mblock(64 * NG * WPG * KS);
-  if (d.lg_page == 6) {
-    hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, 0>), mgrid, mblock, 0, st, d);
-  } else if (d.lg_page >= 4) {
-    hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, 1>), mgrid, mblock, 0, st, d);
-  } else {
-    if constexpr (kLaneFits)
-      hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES_LANE, 2>), mgrid, mblock, 0, st, d);
-    else
-      return GLA_ERR_UNSUPPORTED_SHAPE;  // (the planner does not choose this variant for small pages)
-  }
-  if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
-  if (ev) (void)hipEventRecord(ev[1], st);
-  // waves per merge task from the expected number of chunks per unit
-  const int64_t span_est = (plan.num_chunks + std::max(1, plan.units / plan.mb) - 1) / std::max(1, plan.units / plan.mb) + 1;
-  const dim3 cgrid(plan.units, NG * WPG * (DV / 32));
-  if (span_est <= 2)
-    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 1>), cgrid, dim3(64), 0, st, d);
-  else if (span_est <= 12)
-    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 4>), cgrid, dim3(256), 0, st, d);
-  else
-    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 16>), cgrid, dim3(1024), 0, st, d);
-  if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
-  if (ev) (void)hipEventRecord(ev[2], st);
-  return GLA_OK;
-}
-
-template <int DV, int DN>
-inline int launch_tuned_shape(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
-  if constexpr (DV > 256) {
-    switch (plan.ng * 100 + plan.wpg * 10 + plan.ks) {
-      case 112: return launch_tuned_variant<DV, DN, 1, 1, 2, kTok>(plan, d, st, ev);
-      case 122: return launch_tuned_variant<DV, DN, 1, 2, 2, kTok>(plan, d, st, ev);
-      default: return GLA_ERR_UNSUPPORTED_SHAPE;
-    }
-  } else {
-    switch (plan.ng * 100 + plan.wpg * 10 + plan.ks) {
-      case 111: return launch_tuned_variant<DV, DN, 1, 1, 1, kTok>(plan, d, st, ev);
-      case 121: return launch_tuned_variant<DV, DN, 1, 2, 1, kTok>(plan, d, st, ev);
-      case 141: return launch_tuned_variant<DV, DN, 1, 4, 1, kTok>(plan, d, st, ev);
-      case 211: return launch_tuned_variant<DV, DN, 2, 1, 1, kTok>(plan, d, st, ev);
-      case 221: return launch_tuned_variant<DV, DN, 2, 2, 1, kTok>(plan, d, st, ev);
-      case 411:
-        if constexpr (DV <= 128) return launch_tuned_variant<DV, DN, 4, 1, 1, kTok>(plan, d, st, ev);
-        else return GLA_ERR_UNSUPPORTED_SHAPE;
-      default: return GLA_ERR_UNSUPPORTED_SHAPE;
-    }
-  }
-}
-
-inline int tuned_launch(const gla_decode_params* p, int is_gta, DevParams& d, hipStream_t st,
-                        hipEvent_t* ev) {
-  TunedPlan plan;
-  if (!tuned_plan(p, is_gta, &plan)) return GLA_ERR_UNSUPPORTED_SHAPE;
-  d.ws_out = (float*)p->workspace;
-  d.ws_lse = (float*)((char*)p->workspace + tuned_slots_bytes(plan));  // per-unit chunk ranges (int32 pairs)
-  d.num_chunks = plan.num_chunks;
-  d.chunk_tiles = plan.chunk_tiles;
-  {
-    const int g_q = p->num_q_heads / p->num_groups;
-    int lg = 0;
-    while ((1 << lg) < p->page_size) ++lg;
-    d.mb = plan.mb;
-    d.upb = p->num_groups / plan.ng;
-    d.lg_page = lg;
-    d.xcd_map = (plan.num_chunks * plan.mb) % (8 * plan.mb) == 0 ? 1 : 0;
-    d.tiles_full = (int)(((int64_t)p->max_pages_per_seq * p->page_size + plan.tok - 1) / plan.tok);
-    const int64_t total_full = (int64_t)p->batch * d.upb * d.tiles_full;
-    d.chunk_guess = plan.chunk_tiles > 0 ? plan.chunk_tiles
-                                         : (int)((total_full + plan.num_chunks - 1) / plan.num_chunks);
-    d.fd_mb = make_fastdiv((uint32_t)plan.mb);
-    d.fd_chunks = make_fastdiv((uint32_t)plan.num_chunks);
-    d.fd_gq = make_fastdiv((uint32_t)g_q);
-    d.fd_tiles_full = make_fastdiv((uint32_t)d.tiles_full);
-    d.fd_units_full = make_fastdiv((uint32_t)(d.upb * d.tiles_full));
-    d.fd_upb_mb = make_fastdiv((uint32_t)(d.upb * plan.mb));
-  }
-  if (plan.dv == 256 && plan.dn == 256) return launch_tuned_shape<256, 256>(plan, d, st, ev);
-  if (plan.dv == 128 && plan.dn == 64) return launch_tuned_shape<128, 64>(plan, d, st, ev);
-  if (plan.dv == 512 && plan.dn == 512) return launch_tuned_shape<512, 512>(plan, d, st, ev);
-  return GLA_ERR_UNSUPPORTED_SHAPE;
-}
-
-}  // namespace gla
+#include "tuned_device.hpp"
+#include "tuned_main_kernel.hpp"
+#include "tuned_combine_kernel.hpp"
+#include "tuned_host.hpp"
