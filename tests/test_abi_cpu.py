@@ -76,6 +76,28 @@ def test_unsupported_shape_when_tuned_is_forced():
     assert gla.gla_decode_select_impl(p) == gla.GLA_IMPL_GENERIC
 
 
+@pytest.mark.parametrize("page_size,tuned", [(64, True), (32, True), (16, True), (8, True), (4, True), (2, True),
+                                             (1, True), (128, False), (48, False), (3, False)])
+def test_page_sizes_the_tuned_kernel_takes(page_size, tuned):
+    """Power-of-two pages up to 64 tokens have an MFMA instantiation for the three
+    head shapes; anything else runs the generic kernel."""
+    for kw, is_gta in ((dict(num_q_heads=128, num_groups=2, d_v=256, d_nope=256), False),
+                       (dict(num_q_heads=128, num_groups=1, d_v=512, d_nope=512), False),
+                       (dict(num_q_heads=32, num_groups=4, d_v=128, d_nope=64), True)):
+        p = good(page_size=page_size, max_pages_per_seq=4096 // max(1, min(page_size, 64)), num_pages=100000, **kw)
+        # dense layouts (strides take part in the choice; pointers stay null)
+        h_q, h_c, d_v, d_n = kw["num_q_heads"], kw["num_groups"], kw["d_v"], kw["d_nope"]
+        p.state_stride[:] = (h_c * page_size * d_v, page_size * d_v, d_v)
+        p.rope_stride[:] = (page_size * 64, 64)
+        p.q_nope_stride[:] = (h_q * d_n, h_q * d_n, d_n)
+        p.q_rope_stride[:] = (h_q * 64, h_q * 64, 64)
+        p.out_stride[:] = (h_q * d_v, h_q * d_v, d_v)
+        p.softmax_scale = 0.05
+        want = gla.GLA_IMPL_TUNED if tuned else gla.GLA_IMPL_GENERIC
+        assert gla.gla_decode_select_impl(p, is_gta) == want
+        assert gla.gla_decode_workspace_size(p, is_gta) > 0
+
+
 def test_empty_batch_is_ok():
     p = good(batch=0)
     assert gla.load_library().gla_decode(ctypes.byref(p)) == gla.GLA_OK
