@@ -168,7 +168,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); nothing here uses a second "
-              "GPU, see DESIGN.md for how the path would shard", file=sys.stderr)
+              "GPU (sharded over several GPUs, each would run this same kernel on its share of the heads)", file=sys.stderr)
         return 2
 
     import numpy as np
