@@ -182,8 +182,9 @@ def main() -> int:
     dev = "cuda:0"
     T = args.q_len or None
     if args.lens:
-        p0 = latency_workload(args.lens, shape=args.shape, T=T or 1, draw=0, page_offset=0)
-        p1 = latency_workload(args.lens, shape=args.shape, T=T or 1, draw=1, page_offset=len(p0.page_ids))
+        p0 = latency_workload(args.lens, shape=args.shape, T=T or 1, draw=0, page_offset=0, page_size=args.page_size)
+        p1 = latency_workload(args.lens, shape=args.shape, T=T or 1, draw=1, page_offset=len(p0.page_ids),
+                              page_size=args.page_size)
     else:
         p0 = config(args.config, T=T, draw=0, page_offset=0, page_size=args.page_size)
         p1 = config(args.config, T=T, draw=1, page_offset=len(p0.page_ids), page_size=args.page_size)

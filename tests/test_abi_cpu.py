@@ -166,3 +166,20 @@ def test_counted_flops_per_byte_approach_the_papers_intensity():
     by = accounting.cache_bytes(L, 1, 512, 0)
     assert abs(fl / by - 256) < 1e-6
     assert accounting.duplication_factor(2, 64, 128) == 1 and accounting.duplication_factor(4, 64, 128) == 2
+
+
+# ---- the seeded workload generators the GPU tests and the benchmark draw from
+@pytest.mark.parametrize("page_size", [64, 16, 1])
+def test_workload_generators_build_consistent_problems(page_size):
+    import workloads
+    for p in (workloads.config(1, batch=2, max_len=300, page_size=page_size),
+              workloads.config(4, batch=3, max_len=5000, page_size=page_size),
+              workloads.latency_workload("100x2,700", shape="gla2", page_size=page_size),
+              workloads.latency_workload("333", shape="mla", T=2, page_size=page_size)):
+        assert p.page_size == page_size and p.num_pages == workloads.POOL_PAGES * 64 // page_size
+        used = sum(-(-L // page_size) for L in p.seq_lens)
+        assert len(p.page_ids) == used == len(set(int(x) for x in p.page_ids))
+        for b, L in enumerate(p.seq_lens):          # every held table entry names a materialised page
+            n = -(-L // page_size)
+            assert set(int(x) for x in p.table_pool[b, :n]) <= set(int(x) for x in p.page_ids)
+    assert workloads.parse_lens("1024x15,65536") == [1024] * 15 + [65536]

@@ -238,7 +238,7 @@ def parse_lens(spec: str):
 
 
 def latency_workload(spec: str, *, shape: str = "gla2", T: int = 1, draw: int = 0,
-                     page_offset: int = 0) -> DecodeProblem:
+                     page_offset: int = 0, page_size: int = 64) -> DecodeProblem:
     """Kernel-latency workloads in the style of the paper's appendix on kernel
     execution time: batch 1 at one context length, or a few short sequences plus
     one long one (imbalanced batch).  shape: 'gla2' (2 x 256 + 64, 128 heads) or
@@ -246,6 +246,9 @@ def latency_workload(spec: str, *, shape: str = "gla2", T: int = 1, draw: int = 
     lens = parse_lens(spec)
     seed = BASE_SEED + 77 + 1000 * draw
     tbl = dict(table_seed=BASE_SEED + 577, page_offset=page_offset)
+    if page_size != 64:
+        tbl["page_size"] = page_size
+    pool = POOL_PAGES * 64 // page_size
     if shape == "gla2":
         return make_problem(f"latency_gla2[{spec}]", seq_lens=lens, T=T, h_q=128, h_c=2, d_v=256,
                             num_pages=pool, seed=seed, **tbl)
