@@ -15,24 +15,30 @@ namespace gla {
 // every access of a partial is a full 1 KiB line run.  The KW waves of a
 // workgroup share one task: wave j merges chunks first + j, first + j + KW, ...
 // around its own reference, and the KW results are merged once more through
-// LDS (long single sequences are cut into hundreds of chunks).
-// Grid (units, NG * WPG * DV / 32), KW waves per workgroup.
-template <int DV, int NG, int WPG, int KS, int TOK, int KW>
+// LDS (long single sequences are cut into hundreds of chunks).  With QS = 4
+// (very few units, each spread over very many chunks: few tasks) a task is cut
+// once more into the four quarters of its 32-dim block, one workgroup each,
+// so that four times as many compute units pull the partials.
+// Grid (units, NG * WPG * DV / 32 * QS), KW waves per workgroup.
+template <int DV, int NG, int WPG, int KS, int TOK, int KW, int QS>
 __global__ __launch_bounds__(64 * KW) void tuned_combine_kernel(DevParams p) {
   constexpr int NWAVES = NG * WPG * KS;
   constexpr int NDB = DV / KS / 32;  // 32-dim blocks per wave of the main kernel
   constexpr int kRows = 32 * NG * WPG;
   constexpr size_t kSlotFloats = (size_t)kRows * DV + 32 * NWAVES;
   static_assert(KW == 1 || KW == 4 || KW == 16, "waves per task");
+  static_assert(QS == 1 || (QS == 4 && KW > 1), "workgroups per task");
+  constexpr int NQ4 = 4 / QS;  // quarters of the block per workgroup
   __shared__ float red_m[KW][64], red_z[KW][64];
-  __shared__ f32x4_t red_a[KW][4][64];
+  __shared__ f32x4_t red_a[KW][NQ4][64];
   const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
   const int col = lane & 31, hi = lane >> 5;
 #ifdef GLA_EXPERIMENT_TIMESTAMPS
   if (tid == 0)
     ((long long*)((char*)p.ws_out + (193ll << 20)))[blockIdx.y * gridDim.x + blockIdx.x] = (long long)wall_clock64();
 #endif
-  const int wv = blockIdx.y;
+  const int wv = blockIdx.y / QS;
+  const int q_base = QS == 1 ? 0 : (int)blockIdx.y % QS;  // first quarter this workgroup handles
   const int w = wv / NDB, db = wv - w * NDB;  // wave of the main kernel and one of its 32-dim blocks
   const int wpos = w % (WPG * KS), kx = wpos % KS;
   const int rows_group = p.g_q * p.T;
@@ -65,9 +71,9 @@ __global__ __launch_bounds__(64 * KW) void tuned_combine_kernel(DevParams p) {
 #pragma unroll 4
   for (int k = k_first + kw; k <= k_last; k += KW) m = fmaxf(m, lse0[slot_of(k)]);
   float z = 0.f;
-  f32x4_t acc[4];
+  f32x4_t acc[NQ4];
 #pragma unroll
-  for (int q4 = 0; q4 < 4; ++q4) acc[q4] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int q4 = 0; q4 < NQ4; ++q4) acc[q4] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   if (m != -INFINITY) {
 #pragma unroll 2
     for (int k = k_first + kw; k <= k_last; k += KW) {
@@ -78,8 +84,8 @@ __global__ __launch_bounds__(64 * KW) void tuned_combine_kernel(DevParams p) {
       const float wgt = live ? expf(ls - m) : 0.f;
       z += wgt;
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const f32x4_t v = *(const f32x4_t*)(frag0 + so + q4 * 256);
+      for (int q4 = 0; q4 < NQ4; ++q4) {
+        const f32x4_t v = *(const f32x4_t*)(frag0 + so + (q_base + q4) * 256);
         acc[q4] += wgt * (live ? v : f32x4_t{0.f, 0.f, 0.f, 0.f});
       }
     }
@@ -92,17 +98,17 @@ __global__ __launch_bounds__(64 * KW) void tuned_combine_kernel(DevParams p) {
     lse = m == -INFINITY ? -INFINITY : m + logf(z);
     const float inv = z > 0.f ? 1.0f / z : 0.f;
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) acc[q4] *= inv;
+    for (int q4 = 0; q4 < NQ4; ++q4) acc[q4] *= inv;
     q_mine = -1;  // all four quarters, below
     res = acc[0];
   } else {
     red_m[kw][lane] = m;
     red_z[kw][lane] = z;
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) red_a[kw][q4][lane] = acc[q4];
+    for (int q4 = 0; q4 < NQ4; ++q4) red_a[kw][q4][lane] = acc[q4];
     __syncthreads();
-    if (kw >= 4) return;
-    q_mine = kw;
+    if (kw >= NQ4) return;
+    q_mine = q_base + kw;
     float mm = -INFINITY;
 #pragma unroll
     for (int j = 0; j < KW; ++j) mm = fmaxf(mm, red_m[j][lane]);
@@ -114,7 +120,7 @@ __global__ __launch_bounds__(64 * KW) void tuned_combine_kernel(DevParams p) {
         const float mj = red_m[j][lane];
         const float e = mj == -INFINITY ? 0.f : expf(mj - mm);
         zz += e * red_z[j][lane];
-        res += e * red_a[j][q_mine][lane];
+        res += e * red_a[j][kw][lane];
       }
     }
     lse = mm == -INFINITY ? -INFINITY : mm + logf(zz);
@@ -126,7 +132,7 @@ __global__ __launch_bounds__(64 * KW) void tuned_combine_kernel(DevParams p) {
 #pragma unroll
   for (int q4 = 0; q4 < 4; ++q4) {
     if (q_mine >= 0 && q4 != q_mine) continue;
-    const f32x4_t v = q_mine >= 0 ? res : acc[q4];
+    const f32x4_t v = q_mine >= 0 ? res : acc[q4 < NQ4 ? q4 : 0];
     const int dim = kx * (DV / KS) + 32 * db + 8 * q4 + 4 * hi;
     if (p.out_fp32) {
       *(f32x4_t*)((float*)p.out + ob + dim) = v;
