@@ -20,7 +20,7 @@ namespace gla {
 // once more into the four quarters of its 32-dim block, one workgroup each,
 // so that four times as many compute units pull the partials.
 // Grid (units, NG * WPG * DV / 32 * QS), KW waves per workgroup.
-template <int DV, int NG, int WPG, int KS, int TOK, int KW, int QS>
+template <int DV, int NG, int WPG, int KS, int TOK, int KW, int QS, int U>
 __global__ __launch_bounds__(64 * KW) void tuned_combine_kernel(DevParams p) {
   constexpr int NWAVES = NG * WPG * KS;
   constexpr int NDB = DV / KS / 32;  // 32-dim blocks per wave of the main kernel
@@ -66,29 +66,59 @@ __global__ __launch_bounds__(64 * KW) void tuned_combine_kernel(DevParams p) {
   const float* const lse0 = p.ws_out + (size_t)kRows * DV + r;
   const float* const frag0 = p.ws_out + (size_t)((w * NDB + db) * 4) * 256 + lane * 4;
 
-  // this wave's share: reference = its own maximum
+  // This wave's share, in one pass: a running (reference, sum of weights,
+  // weighted sum), the reference being the running maximum; the sums are
+  // rescaled when it moves.  Full groups of U chunks are requested together
+  // (their loads do not depend on one another: a long chunk list is bound by
+  // memory latency, not bandwidth; U is small where lists are short, since the
+  // registers it takes cost resident waves), the rest one at a time.
   float m = -INFINITY;
-#pragma unroll 4
-  for (int k = k_first + kw; k <= k_last; k += KW) m = fmaxf(m, lse0[slot_of(k)]);
   float z = 0.f;
   f32x4_t acc[NQ4];
 #pragma unroll
   for (int q4 = 0; q4 < NQ4; ++q4) acc[q4] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  if (m != -INFINITY) {
-#pragma unroll 2
-    for (int k = k_first + kw; k <= k_last; k += KW) {
-      const size_t so = slot_of(k);
-      const float ls = lse0[so];
-      // a slot marked "no key" may hold anything: its values are dropped, not multiplied by zero
-      const bool live = ls != -INFINITY;
-      const float wgt = live ? expf(ls - m) : 0.f;
-      z += wgt;
+  auto rebase = [&](float m_new) {  // m_new > -inf
+    const float keep = m == -INFINITY ? 0.f : expf(m - m_new);
+    z *= keep;
 #pragma unroll
-      for (int q4 = 0; q4 < NQ4; ++q4) {
-        const f32x4_t v = *(const f32x4_t*)(frag0 + so + (q_base + q4) * 256);
-        acc[q4] += wgt * (live ? v : f32x4_t{0.f, 0.f, 0.f, 0.f});
-      }
+    for (int q4 = 0; q4 < NQ4; ++q4) acc[q4] *= keep;
+    m = m_new;
+  };
+  auto fold = [&](float ls, const f32x4_t (&v)[NQ4]) {  // m is at least ls
+    // a slot marked "no key" may hold anything: its values are dropped, not multiplied by zero
+    const bool live = ls != -INFINITY;
+    const float wgt = live ? expf(ls - m) : 0.f;
+    z += wgt;
+#pragma unroll
+    for (int q4 = 0; q4 < NQ4; ++q4) acc[q4] += wgt * (live ? v[q4] : f32x4_t{0.f, 0.f, 0.f, 0.f});
+  };
+  int k = k_first + kw;
+  for (; k + (U - 1) * KW <= k_last; k += U * KW) {
+    float ls[U];
+    f32x4_t v[U][NQ4];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t so = slot_of(k + u * KW);
+      ls[u] = lse0[so];
+#pragma unroll
+      for (int q4 = 0; q4 < NQ4; ++q4) v[u][q4] = *(const f32x4_t*)(frag0 + so + (q_base + q4) * 256);
     }
+    float m_new = m;
+#pragma unroll
+    for (int u = 0; u < U; ++u) m_new = fmaxf(m_new, ls[u]);
+    if (m_new == -INFINITY) continue;
+    if (m_new != m) rebase(m_new);
+#pragma unroll
+    for (int u = 0; u < U; ++u) fold(ls[u], v[u]);
+  }
+  for (; k <= k_last; k += KW) {
+    const size_t so = slot_of(k);
+    const float ls = lse0[so];
+    f32x4_t v[NQ4];
+#pragma unroll
+    for (int q4 = 0; q4 < NQ4; ++q4) v[q4] = *(const f32x4_t*)(frag0 + so + (q_base + q4) * 256);
+    if (ls > m) rebase(ls);
+    if (m != -INFINITY) fold(ls, v);
   }
   // merge of the KW shares; wave q4 < 4 then finishes quarter q4 of the block
   float lse;

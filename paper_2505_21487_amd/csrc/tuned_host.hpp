@@ -160,13 +160,15 @@ inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, hipStream_t
   const int64_t span_est = (plan.num_chunks + std::max(1, plan.units / plan.mb) - 1) / std::max(1, plan.units / plan.mb) + 1;
   const dim3 cgrid(plan.units, NG * WPG * (DV / 32));
   if (span_est <= 2)
-    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 1, 1>), cgrid, dim3(64), 0, st, d);
+    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 1, 1, 2>), cgrid, dim3(64), 0, st, d);
   else if (span_est <= 12)
-    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 4, 1>), cgrid, dim3(256), 0, st, d);
+    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 4, 1, 2>), cgrid, dim3(256), 0, st, d);
+  else if (span_est <= 64)  // (a wave folds eight chunks per round trip: four waves do for fairly long lists)
+    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 4, 1, 8>), cgrid, dim3(256), 0, st, d);
   else if ((int64_t)cgrid.x * cgrid.y * 4 > 4 * device_cu_count())
-    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 16, 1>), cgrid, dim3(1024), 0, st, d);
+    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 16, 1, 4>), cgrid, dim3(1024), 0, st, d);
   else  // few tasks: each cut into quarters (see the kernel)
-    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 16, 4>), dim3(cgrid.x, cgrid.y * 4), dim3(1024), 0, st, d);
+    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 16, 4, 4>), dim3(cgrid.x, cgrid.y * 4), dim3(1024), 0, st, d);
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[2], st);
   return GLA_OK;
