@@ -44,6 +44,12 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Workgroup barrier alone: LDS reads of this wave that are in flight stay in
+// flight (used where the barrier only orders tile loads against other waves).
+__device__ __forceinline__ void bare_barrier() {
+  asm volatile("s_barrier" ::: "memory");
+}
+
 // Hand-issued LDS reads.  The result registers are valid only after a matching
 // lds_wait on them; LDS returns data in issue order, so "at most N reads still
 // outstanding" identifies which reads have completed.

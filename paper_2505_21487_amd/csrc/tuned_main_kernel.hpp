@@ -581,6 +581,21 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   constexpr int IW = ((NS - 1) / 4) * 4;                // step of the last wait for score operands
   constexpr int VPRE = VRS < NP ? VRS : NP;             // value operands requested ahead of [B]
   constexpr int MXS = 4;                                // [B] steps over which the row-max chain is spread
+  // With a deep tile ring (and no score exchange) the per-tile workgroup barrier
+  // sits in the middle of [B] instead of at the top of the iteration: there it
+  // waits for the tile after next, so the first score operands of the next
+  // iteration can be requested under the last value MFMAs and their LDS latency
+  // no longer opens the iteration; the loads of the iteration follow the barrier
+  // (they overwrite the stage of the tile before this one, which every wave has
+  // left by then).  One tile less is in flight at the wait, hence the deep ring.
+#ifdef GLA_EXPERIMENT_NO_COMPUTE
+  constexpr bool kEarlyBar = false;  // (the load-only experiment build keeps the barrier at the top)
+#else
+  constexpr bool kEarlyBar = KS == 1 && STAGES >= 8;
+#endif
+  constexpr int JB = NB / 2 - 1;                        // [B] step that carries the barrier
+  constexpr int RSN = RS < NS ? RS : NS;                // score operands requested ahead
+  static_assert(!kEarlyBar || (JB >= 3 && NB - 3 > JB && NP - 2 < NB - 3), "step layout of [B] with the barrier inside");
   static_assert(2 + MXS <= NB, "row-max steps fit into [B]");
   float mx_carry = -INFINITY;                           // kEarlyMax: lane-local max of the next tile's scores
   auto mask_tile = [&](f32x16_t (&sc)[NTB], int tile_j) {
@@ -647,7 +662,8 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
 #else
 #define GLA_PHASE(i) do { } while (0)
 #endif
-  auto tile_iter = [&](f32x16_t (&s_rd)[NTB], f32x16_t (&s_wr)[NTB], int k, int tile_j, bool has_next, int seg_L) {
+  auto tile_iter = [&](f32x16_t (&s_rd)[NTB], f32x16_t (&s_wr)[NTB], int k, int tile_j, bool has_next, bool has_next2,
+                       int seg_L) {
 #ifdef GLA_EXPERIMENT_PHASE_CLOCKS
     ph_t = (long long)clock64();
     ++ph_n;
@@ -655,13 +671,17 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     constexpr std::integral_constant<int, -1> psgc{}, ssgc{};  // stages live in the address registers
     const int pv_stage = k % STAGES;
     // ---- tile k+1 landed?  (also: every wave is done with tile k-1, so its stage is free)
-    if (has_next) {
-      if (issued - 2 - k >= STAGES - 3) wait_vmcnt<LPW * (STAGES - 3)>();
-      else wait_vmcnt<0>();
+    if constexpr (!kEarlyBar) {
+      if (has_next) {
+        if (issued - 2 - k >= STAGES - 3) wait_vmcnt<LPW * (STAGES - 3)>();
+        else wait_vmcnt<0>();
+      }
+      lds_barrier();
     }
-    lds_barrier();
     GLA_PHASE(0);
-    if (has_next) zero_tail((pv_stage + 1) % STAGES, tile_j + 1, seg_L);
+    if constexpr (!kEarlyBar) {
+      if (has_next) zero_tail((pv_stage + 1) % STAGES, tile_j + 1, seg_L);
+    }
 
 #ifdef GLA_EXPERIMENT_NO_COMPUTE
     dma_prepare((pv_stage + STAGES - 1) % STAGES);
@@ -673,7 +693,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     //          whatever is in that stage and the result is dropped), under the
     //          masking and row-max search of tile k
     xchg_fetch();
-    static_for<0, (RS < NS ? RS : NS)>([&](auto ic) { s_issue(ssgc, ic); });
+    if constexpr (!kEarlyBar) static_for<0, RSN>([&](auto ic) { s_issue(ssgc, ic); });  // (else: requested in the previous [B])
     xchg_add(s_rd);
     float mx;
     if constexpr (kEarlyMax) {
@@ -774,13 +794,42 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       if constexpr (i == 0) dma_prepare_0((pv_stage + STAGES - 1) % STAGES);
       else if constexpr (i == 1) dma_prepare_1();
       else if constexpr (i == 2) dma_prepare_2();
-      else static_for<((i - 3) * LPW) / (NB - 3), ((i - 2) * LPW) / (NB - 3)>(dma_load);
-      // score addresses: next used in the next tile's [A]
-      static_for<(i * (8 + NKR)) / NB, ((i + 1) * (8 + NKR)) / NB>([&](auto ec) {
-        constexpr int e = decltype(ec)::value;
-        if constexpr (e < 8) ka[e] += k_step;
-        else ra[e - 8] += r_step;
-      });
+      if constexpr (!kEarlyBar) {
+        if constexpr (i >= 3) static_for<((i - 3) * LPW) / (NB - 3), ((i - 2) * LPW) / (NB - 3)>(dma_load);
+        // score addresses: next used in the next tile's [A]
+        static_for<(i * (8 + NKR)) / NB, ((i + 1) * (8 + NKR)) / NB>([&](auto ec) {
+          constexpr int e = decltype(ec)::value;
+          if constexpr (e < 8) ka[e] += k_step;
+          else ra[e - 8] += r_step;
+        });
+      } else {
+        if constexpr (i == JB) {
+          // tile k+2 landed?  The loads of this iteration have not been issued yet
+          // (`issued` already counts its tile if one was prepared above): behind
+          // tile k+2 there are then the tiles up to k + STAGES - 2.
+          if (has_next2) {
+            if (issued - (prep_active ? 1 : 0) - (k + 3) >= STAGES - 4) wait_vmcnt<LPW * (STAGES - 4)>();
+            else wait_vmcnt<0>();
+          }
+          bare_barrier();  // (value operands of this tile stay in flight across it)
+          if (has_next2) zero_tail((pv_stage + 2) % STAGES, tile_j + 2, seg_L);
+        } else if constexpr (i > JB) {
+          static_for<((i - JB - 1) * LPW) / (NB - JB - 1), ((i - JB) * LPW) / (NB - JB - 1)>(dma_load);
+        }
+        // score addresses: moved on to the stage of tile k+2 before the last three steps ...
+        if constexpr (i < NB - 3) {
+          static_for<(i * (8 + NKR)) / (NB - 3), ((i + 1) * (8 + NKR)) / (NB - 3)>([&](auto ec) {
+            constexpr int e = decltype(ec)::value;
+            if constexpr (e < 8) ka[e] += k_step;
+            else ra[e - 8] += r_step;
+          });
+        } else {
+          // ... in which the first score operands of the next iteration are requested
+          // (no value operand is waited for any more at this point)
+          if (has_next)
+            static_for<((i - (NB - 3)) * RSN) / 3, ((i - (NB - 3) + 1) * RSN) / 3>([&](auto jc) { s_issue(ssgc, jc); });
+        }
+      }
       __builtin_amdgcn_sched_barrier(0);
     });
     // value addresses: every read of this tile has been issued
@@ -832,6 +881,9 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     //      (value reads) and, after its scores are done, of tile k+1 (score reads)
     lds_barrier();
     zero_tail(k % STAGES, seg_j0, seg_L);
+    if constexpr (kEarlyBar) {  // the tile after it has landed too (everything requested so far has)
+      if (seg_n >= 2) zero_tail((k + 1) % STAGES, seg_j0 + 1, seg_L);
+    }
     {
       const int ss = k % STAGES;
 #pragma unroll
@@ -853,6 +905,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       for (int e = 0; e < 8; ++e) ka[e] += wrap ? -(STAGES - 1) * STB : STB;
 #pragma unroll
       for (int e = 0; e < NKR; ++e) ra[e] += wrap ? -(STAGES - 1) * RTB : RTB;
+      if constexpr (kEarlyBar) static_for<0, RSN>([&](auto ic) { s_issue(rt, ic); });  // for the first iteration's [A]
     }
     // the scores are read by the vector ALU next; the wait is tied to them so
     // that no read can be scheduled ahead of it
@@ -871,11 +924,11 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
 
     // two tiles per trip so that the two score register sets swap roles without copies
     for (int t = 0; t < seg_n; t += 2) {
-      tile_iter(s_even, s_odd, k, seg_j0 + t, t + 1 < seg_n, seg_L);
+      tile_iter(s_even, s_odd, k, seg_j0 + t, t + 1 < seg_n, t + 2 < seg_n, seg_L);
       if (k == 0) GLA_STAMP(7);
       ++k;
       if (t + 1 < seg_n) {
-        tile_iter(s_odd, s_even, k, seg_j0 + t + 1, t + 2 < seg_n, seg_L);
+        tile_iter(s_odd, s_even, k, seg_j0 + t + 1, t + 2 < seg_n, t + 3 < seg_n, seg_L);
         ++k;
       }
     }
