@@ -259,3 +259,17 @@ def test_full_size_small_pages_on_sampled_rows(index, T, page_size):
     b_long = int(np.argmax(p.seq_lens))
     sel += [(b_long, t, h) for t in range(p.T) for h in (0, p.h_q - 1)]
     check_problem(p, sel=sel, what=f"cfg{index} T={T} page {page_size}")
+
+
+@pytest.mark.parametrize("B,hi,page_size", [(1000, 300, 64), (3000, 100, 16), (700, 500, 1)])
+def test_very_large_batches_of_short_sequences(B, hi, page_size):
+    """Thousands of units, many of them empty or shorter than a tile: the plan's
+    prefix sums run over more sequences than a wave has lanes, most chunks hold
+    several units."""
+    rng = np.random.default_rng(5 + B)
+    lens = [int(x) for x in rng.integers(0, hi, size=B)]
+    pages = sum(-(-n // page_size) for n in lens)
+    p = make_problem(f"big_batch_{B}", seq_lens=lens, T=2, h_q=16, h_c=2, d_v=256, page_size=page_size,
+                     num_pages=max(4096, 2 * pages), seed=77 + B, poison_tail=True, extra_table_cols=1)
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, what=f"B={B} page {page_size} impl={impl}")
