@@ -273,3 +273,41 @@ def test_very_large_batches_of_short_sequences(B, hi, page_size):
                      num_pages=max(4096, 2 * pages), seed=77 + B, poison_tail=True, extra_table_cols=1)
     for impl in impls_for(p):
         check_problem(p, impl=impl, what=f"B={B} page {page_size} impl={impl}")
+
+
+@pytest.mark.parametrize("page_size", [64, 16, 1])
+def test_tuned_kernel_with_strided_tensors(page_size):
+    """Queries and output as slices of wider buffers, caches as slices of pools
+    with padded page strides (one more group / a few more token rows per page
+    than used): the MFMA kernel takes every stride from the parameter block."""
+    p = make_problem("strided", seq_lens=[300, 0, 77, 1200], T=2, h_q=32, h_c=2, d_v=256, page_size=page_size,
+                     seed=510 + page_size, num_pages=4096, poison_tail=True, extra_table_cols=1)
+    dp = DeviceProblem(p, poison_unused=True)
+    dev = "cuda"
+    wide = torch.zeros(p.B, p.T, p.h_q, p.d_n + 64, dtype=torch.bfloat16, device=dev)
+    wide[..., 16:16 + p.d_n] = dp.q_nope
+    dp.q_nope = wide[..., 16:16 + p.d_n]
+    wide_r = torch.zeros(p.B, p.T + 1, p.h_q, p.d_r, dtype=torch.bfloat16, device=dev)
+    wide_r[:, :p.T] = dp.q_rope
+    dp.q_rope = wide_r[:, :p.T]
+    pool_s = torch.full((p.num_pages, p.h_c + 1, p.page_size, p.d_v), float("nan"), dtype=torch.bfloat16, device=dev)
+    pool_s[:, :p.h_c] = dp.state_cache
+    dp.state_cache = pool_s[:, :p.h_c]
+    pool_r = torch.full((p.num_pages, p.page_size + 8, p.d_r), float("nan"), dtype=torch.bfloat16, device=dev)
+    pool_r[:, :p.page_size] = dp.rope_cache
+    dp.rope_cache = pool_r[:, :p.page_size]
+    ref_out, ref_lse = oracle.decode_problem(p)
+    for out_dtype in (torch.float32, torch.bfloat16):
+        out_wide = torch.zeros(p.B, p.T, p.h_q, p.d_v + 32, dtype=out_dtype, device=dev)
+        out, lse = gla.gla_decode(*dp.args(), out=out_wide[..., :p.d_v], impl=TUNED)
+        torch.cuda.synchronize()
+        compare(out.double().cpu().numpy(), lse.double().cpu().numpy(), ref_out, ref_lse,
+                what=f"strided tuned page {page_size} {out_dtype}", bf16_out_allowance=out_dtype == torch.bfloat16)
+        assert (out_wide[..., p.d_v:] == 0).all()
+
+
+def test_batch_of_empty_sequences():
+    """No key anywhere: every output row is zero and every lse is -inf, on both kernels."""
+    p = make_problem("all_empty", seq_lens=[0, 0, 0], T=2, h_q=128, h_c=2, d_v=256, seed=520, num_pages=64)
+    for impl in impls_for(p):
+        check_problem(p, impl=impl, what=f"all empty impl={impl}")
