@@ -129,6 +129,17 @@ int gla_decode_select_impl(const gla_decode_params* p, int is_gta);
 int gla_decode_profile(const gla_decode_params* p, int is_gta, int iters, float* main_us,
                        float* combine_us);
 
+/* Debug helper for callers that build page tables themselves: checks the
+ * device contents the decode calls trust (they are not checked there, and a
+ * bad page id makes a decode call read outside the pools).  Counts, into the
+ * host int *n_bad, the sequences whose length is outside
+ * [0, max_pages_per_seq * page_size] and the page-table entries a sequence
+ * holds (the first ceil(L_b / page_size) of its row) that are outside
+ * [0, num_pages).  Needs num_pages > 0 and 256 bytes of workspace (whose first
+ * bytes it overwrites); enqueues one small kernel on p->stream and DOES
+ * synchronise the stream.  Returns GLA_OK when the check itself ran. */
+int gla_decode_check_contents(const gla_decode_params* p, int is_gta, int* n_bad);
+
 /* Static, NUL-terminated description of a status code. */
 const char* gla_status_string(int status);
 

@@ -25,7 +25,7 @@ GLA_IMPL_AUTO, GLA_IMPL_GENERIC, GLA_IMPL_TUNED = 0, 1, 2
 GLA_OUT_BF16, GLA_OUT_FP32 = 0, 1
 
 EXPORTS = ("gla_decode", "gta_decode", "gla_decode_workspace_size", "gla_decode_select_impl",
-           "gla_decode_profile", "gla_status_string", "gla_decode_version")
+           "gla_decode_profile", "gla_decode_check_contents", "gla_status_string", "gla_decode_version")
 
 
 class GlaDecodeParams(ctypes.Structure):
@@ -80,6 +80,8 @@ def load_library() -> ctypes.CDLL:
                                            ctypes.POINTER(ctypes.c_float),
                                            ctypes.POINTER(ctypes.c_float)]
         lib.gla_decode_profile.restype = ctypes.c_int
+        lib.gla_decode_check_contents.argtypes = [P, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+        lib.gla_decode_check_contents.restype = ctypes.c_int
         lib.gla_status_string.argtypes = [ctypes.c_int]
         lib.gla_status_string.restype = ctypes.c_char_p
         lib.gla_decode_version.argtypes = []
@@ -212,6 +214,16 @@ def decode_prepared(p: GlaDecodeParams, is_gta: bool = False) -> None:
     rc = (lib.gta_decode if is_gta else lib.gla_decode)(ctypes.byref(p))
     if rc != GLA_OK:
         raise GlaError(rc)
+
+
+def gla_decode_check_contents(p: GlaDecodeParams, is_gta: bool = False) -> int:
+    """Number of out-of-range lengths and held page-table entries in the device
+    buffers of `p` (0 = what the decode calls trust holds).  Synchronises p.stream."""
+    n = ctypes.c_int(0)
+    rc = load_library().gla_decode_check_contents(ctypes.byref(p), int(is_gta), ctypes.byref(n))
+    if rc != GLA_OK:
+        raise GlaError(rc)
+    return int(n.value)
 
 
 def gla_decode_profile(p: GlaDecodeParams, is_gta: bool, iters: int) -> Tuple[float, float]:

@@ -149,10 +149,61 @@ int run(const gla_decode_params* p, int is_gta, hipEvent_t* ev) {
   return launch_generic(p, d, st, ev);
 }
 
+__global__ void zero_int_kernel(int* x) { *x = 0; }
+
+// Device contents the decode kernels trust: one thread per (sequence, table
+// entry).  Counts lengths outside [0, max_pages * page_size] and held table
+// entries outside [0, num_pages) into *bad (a vector-memory atomic).
+__global__ void check_contents_kernel(const int32_t* seq_lens, const int32_t* page_table, int B, int max_pages,
+                                      int page_size, int64_t num_pages, int* bad) {
+  const int b = blockIdx.y;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const int L = seq_lens[b];
+  const int64_t cap = (int64_t)max_pages * page_size;
+  if (L < 0 || L > cap) {
+    if (j == 0) atomicAdd(bad, 1);
+    return;
+  }
+  const int held = (L + page_size - 1) / page_size;
+  if (j < held) {
+    const int32_t pg = page_table[(int64_t)b * max_pages + j];
+    if (pg < 0 || (int64_t)pg >= num_pages) atomicAdd(bad, 1);
+  }
+}
+
+int check_contents(const gla_decode_params* p, int is_gta, int* n_bad) {
+  const int impl = select_impl(p, is_gta);
+  if (impl < 0) return impl;
+  int rc = check_pointers(p);
+  if (rc != GLA_OK) return rc;
+  if (!n_bad || p->num_pages <= 0) return GLA_ERR_INVALID_ARG;
+  *n_bad = 0;
+  if (p->batch == 0) return GLA_OK;
+  if (!p->workspace || p->workspace_bytes < 256) return GLA_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t st = (hipStream_t)p->stream;
+  int* counter = (int*)p->workspace;
+  hipLaunchKernelGGL(zero_int_kernel, dim3(1), dim3(1), 0, st, counter);
+  if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
+  const int threads = 256;
+  const dim3 grid((unsigned)((p->max_pages_per_seq + threads - 1) / threads), (unsigned)p->batch);
+  hipLaunchKernelGGL(check_contents_kernel, grid, dim3(threads), 0, st, p->seq_lens, p->page_table, p->batch,
+                     p->max_pages_per_seq, p->page_size, p->num_pages, counter);
+  if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
+  if (hipMemcpyAsync(n_bad, counter, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipStreamSynchronize(st) != hipSuccess)
+    return GLA_ERR_LAUNCH;
+  return GLA_OK;
+}
+
 }  // namespace
 }  // namespace gla
 
 extern "C" {
+
+int gla_decode_check_contents(const gla_decode_params* p, int is_gta, int* n_bad) {
+  return gla::check_contents(p, is_gta, n_bad);
+}
 
 int gla_decode(const gla_decode_params* p) { return gla::run(p, 0, nullptr); }
 

@@ -311,3 +311,23 @@ def test_batch_of_empty_sequences():
     p = make_problem("all_empty", seq_lens=[0, 0, 0], T=2, h_q=128, h_c=2, d_v=256, seed=520, num_pages=64)
     for impl in impls_for(p):
         check_problem(p, impl=impl, what=f"all empty impl={impl}")
+
+
+def test_check_contents_counts_bad_lengths_and_page_ids():
+    """The debug checker accepts what the generators build (unused table slots
+    hold -1 and are not counted) and counts planted out-of-range values; the
+    decode call is not run on the corrupted buffers."""
+    p = make_problem("chk", seq_lens=[100, 0, 700, 64], T=1, h_q=16, h_c=2, d_v=256, seed=530, num_pages=256,
+                     extra_table_cols=2)
+    dp = DeviceProblem(p)
+    out = torch.empty(p.B, p.T, p.h_q, p.d_v, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(p.B, p.T, p.h_q, dtype=torch.float32, device="cuda")
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    prm = gla.make_params(*dp.args()[:6], p.scale, out=out, lse=lse, workspace=ws)
+    assert gla.gla_decode_check_contents(prm) == 0
+    dp.page_table[0, 1] = p.num_pages        # held by sequence 0 (100 tokens = 2 pages): out of range
+    dp.page_table[2, 3] = -7                 # held by sequence 2
+    dp.page_table[3, 1] = 10 ** 6            # NOT held by sequence 3 (64 tokens = 1 page): ignored
+    dp.seq_lens[1] = -1
+    torch.cuda.synchronize()
+    assert gla.gla_decode_check_contents(prm) == 3
