@@ -15,7 +15,7 @@
 namespace gla {
 namespace {
 
-constexpr int kVersion = 100;
+constexpr int kVersion = 101;  // 1.01: gla_decode_check_contents added
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
