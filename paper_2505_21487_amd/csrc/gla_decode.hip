@@ -156,8 +156,10 @@ __global__ void zero_int_kernel(int* x) { *x = 0; }
 // entries outside [0, num_pages) into *bad (a vector-memory atomic).
 __global__ void check_contents_kernel(const int32_t* seq_lens, const int32_t* page_table, int B, int max_pages,
                                       int page_size, int64_t num_pages, int* bad) {
-  const int b = blockIdx.y;
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  // (the batch is folded into grid.x: grid.y would cap it at 65535 sequences)
+  const int bpr = (max_pages + (int)blockDim.x - 1) / (int)blockDim.x;  // blocks per table row
+  const int b = (int)(blockIdx.x / (unsigned)bpr);
+  const int j = (int)(blockIdx.x % (unsigned)bpr) * (int)blockDim.x + (int)threadIdx.x;
   if (b >= B) return;
   const int L = seq_lens[b];
   const int64_t cap = (int64_t)max_pages * page_size;
@@ -186,7 +188,9 @@ int check_contents(const gla_decode_params* p, int is_gta, int* n_bad) {
   hipLaunchKernelGGL(zero_int_kernel, dim3(1), dim3(1), 0, st, counter);
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   const int threads = 256;
-  const dim3 grid((unsigned)((p->max_pages_per_seq + threads - 1) / threads), (unsigned)p->batch);
+  const int64_t blocks = (int64_t)((p->max_pages_per_seq + threads - 1) / threads) * p->batch;
+  if (blocks > 0x7fffffff) return GLA_ERR_INVALID_ARG;
+  const dim3 grid((unsigned)blocks);
   hipLaunchKernelGGL(check_contents_kernel, grid, dim3(threads), 0, st, p->seq_lens, p->page_table, p->batch,
                      p->max_pages_per_seq, p->page_size, p->num_pages, counter);
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;

@@ -33,10 +33,6 @@ __global__ __launch_bounds__(64 * KW) void tuned_combine_kernel(DevParams p) {
   __shared__ f32x4_t red_a[KW][NQ4][64];
   const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
   const int col = lane & 31, hi = lane >> 5;
-#ifdef GLA_EXPERIMENT_TIMESTAMPS
-  if (tid == 0)
-    ((long long*)((char*)p.ws_out + (193ll << 20)))[blockIdx.y * gridDim.x + blockIdx.x] = (long long)wall_clock64();
-#endif
   const int wv = blockIdx.y / QS;
   const int q_base = QS == 1 ? 0 : (int)blockIdx.y % QS;  // first quarter this workgroup handles
   const int w = wv / NDB, db = wv - w * NDB;  // wave of the main kernel and one of its 32-dim blocks

@@ -142,6 +142,15 @@ __device__ __forceinline__ void sm_ops_a(float& sum, float p2) {
 __device__ __forceinline__ void sm_ops_ac(float& sum, float p2, uint32_t& pk, float p3) {
   asm volatile("s_nop 0\n\tv_add_f32 %0, %0, %2\n\tv_cvt_pk_bf16_f32 %1, %3, %2" : "+v"(sum), "=&v"(pk) : "v"(p2), "v"(p3));
 }
+// Two fp32 values rounded to bf16 (nearest even), `a` in the low half: one
+// v_cvt_pk_bf16_f32.  Left to the compiler (not inline asm) so that it sees the
+// instruction and provides the wait state a transcendental result needs before
+// its first use.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));
+}
 __device__ __forceinline__ void asm_max3(float& m, float a, float b) {
   asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(m) : "v"(a), "v"(b));
 }

@@ -97,15 +97,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   const int rows_group = p.g_q * p.T;
   const int MB = p.mb;    // row blocks per group
   const int UPB = p.upb;  // units (group blocks) per sequence
-#ifdef GLA_EXPERIMENT_TIMESTAMPS
-  // experiment build: wall-clock stamps of workgroup phases, 8 per workgroup,
-  // written 192 MiB into the workspace (the experiment passes a larger one)
-  long long* const stamps = (long long*)((char*)p.ws_out + (192ll << 20)) + (size_t)blockIdx.x * 8;
-#define GLA_STAMP(i) do { if (tid == 0) stamps[i] = (long long)wall_clock64(); } while (0)
-#else
-#define GLA_STAMP(i) do { } while (0)
-#endif
-  GLA_STAMP(0);
 
   // A chunk of the list is worked on by MB workgroups, one per row block of its
   // groups (MB > 1 when a group has more query rows than a workgroup holds).
@@ -169,7 +160,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
 
   TileCursor cur = locate_tile<TOK>(p, UPB, c0, lane, L_first, incl0);  // compute position
   TileCursor pre = cur;                                  // prefetch position
-  GLA_STAMP(1);
 
   // ---- tile loads, global -> LDS, 16 B per lane, 1 KiB per wave instruction.
   // The LDS side is linear in the lane index, so each lane fetches the global
@@ -362,7 +352,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   // i-th of this wave's LPW loads of the prepared tile
   auto dma_load = [&](auto ic) {
     constexpr int i = decltype(ic)::value;
-#ifndef GLA_EXPERIMENT_NO_TILE_LOADS
     if constexpr (kLane) {
       // address of this lane's row: page base + row within the page + the chunk
       // of the row whose swizzled home is this lane's LDS slot
@@ -390,7 +379,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_r[ir] + voff),
                                        (lds_void_t*)(dma_lr + ir * 1024), 16, 0, 0);
     }
-#endif
   };
 
   // ---- query fragments of the unit at `cur`: this wave's 32 rows, B operand of
@@ -428,7 +416,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     }
   }
 
-  GLA_STAMP(2);
   // ---- lane-constant LDS read addresses (stage 0; other stages are immediates)
   // score operand (K rows, 16 B): token = 32*tb + col, logical chunk = 2*ks + hi
   const int sw_col = swz16(col);
@@ -588,11 +575,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   // no longer opens the iteration; the loads of the iteration follow the barrier
   // (they overwrite the stage of the tile before this one, which every wave has
   // left by then).  One tile less is in flight at the wait, hence the deep ring.
-#ifdef GLA_EXPERIMENT_NO_COMPUTE
-  constexpr bool kEarlyBar = false;  // (the load-only experiment build keeps the barrier at the top)
-#else
   constexpr bool kEarlyBar = KS == 1 && STAGES >= 8;
-#endif
   constexpr int JB = NB / 2 - 1;                        // [B] step that carries the barrier
   constexpr int RSN = RS < NS ? RS : NS;                // score operands requested ahead
   static_assert(!kEarlyBar || (JB >= 3 && NB - 3 > JB && NP - 2 < NB - 3), "step layout of [B] with the barrier inside");
@@ -649,25 +632,43 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       asm volatile("s_barrier" ::: "memory");
     }
   };
+  // Second value pass of a tile with heavy weights (rare: the first tiles of a
+  // segment, rows with a few dominant keys).  The weights are formed again from
+  // the scores exactly as the softmax slots formed them, p = 2^(s * sc2 - m),
+  // split as p = hi + lo with hi = bf16(p) (what the first pass used), and lo,
+  // exact in fp32 and itself rounded to bf16, goes through the same value and
+  // row-sum MFMAs: the tile's weights then carry 16 significant bits.  Runs
+  // right behind [B] of the same tile: its stage is still intact (no wave can
+  // pass the next barrier, after which the stage is reloaded, before this wave
+  // has), the address registers still point at it and the operand rings are free.
+  auto residual_pass = [&](f32x16_t (&sc)[NTB]) {
+    static_for<0, NE / 2>([&](auto jc) {
+      constexpr int e = 2 * decltype(jc)::value;
+      constexpr int pi = (e / 16) * 2 + ((e % 16) >> 3), pj = (e & 7) >> 1;
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e / 16][e % 16], sc2, neg_m));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[(e + 1) / 16][(e + 1) % 16], sc2, neg_m));
+      const uint32_t hi_pk = cvt_pk_bf16(p0, p1);
+      const float h0 = __builtin_bit_cast(float, hi_pk << 16), h1 = __builtin_bit_cast(float, hi_pk & 0xffff0000u);
+      const float l0 = p0 - h0, l1 = p1 - h1;  // (0 - 0 for masked elements; padding rows may hold anything)
+      pkw[pi][pj] = cvt_pk_bf16(l0, l1);
+    });
+    constexpr std::integral_constant<int, -1> psgc{};
+    static_for<0, VPRE>([&](auto jc) { v_issue(psgc, jc); });
+    wait_states<2>();  // the residuals were packed by the vector ALU just above
+    static_for<0, NB>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      if constexpr (i < NP && i % 2 == 0) v_wait(ic);
+      v_mfma(psgc, ic);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+
   // One tile: [A] softmax of tile k (scores in s_rd) under the score MFMAs of
   // tile k+1 (into s_wr), then [B] value MFMAs of tile k under the loads of tile
   // k + STAGES - 1.  k: chunk-local tile index, tile_j: index in the unit, PSG /
   // SSG: stage of tile k / of tile k+1 (or -1, see above), pv_stage: stage of tile k.
-#ifdef GLA_EXPERIMENT_PHASE_CLOCKS
-  // experiment build: core-clock time of wave 0 spent in the phases of the tile loop
-  long long ph_acc[4] = {0, 0, 0, 0};
-  long long ph_t = 0;
-  int ph_n = 0;
-#define GLA_PHASE(i) do { const long long t_ = (long long)clock64(); ph_acc[i] += t_ - ph_t; ph_t = t_; } while (0)
-#else
-#define GLA_PHASE(i) do { } while (0)
-#endif
   auto tile_iter = [&](f32x16_t (&s_rd)[NTB], f32x16_t (&s_wr)[NTB], int k, int tile_j, bool has_next, bool has_next2,
                        int seg_L) {
-#ifdef GLA_EXPERIMENT_PHASE_CLOCKS
-    ph_t = (long long)clock64();
-    ++ph_n;
-#endif
     constexpr std::integral_constant<int, -1> psgc{}, ssgc{};  // stages live in the address registers
     const int pv_stage = k % STAGES;
     // ---- tile k+1 landed?  (also: every wave is done with tile k-1, so its stage is free)
@@ -678,17 +679,10 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       }
       lds_barrier();
     }
-    GLA_PHASE(0);
     if constexpr (!kEarlyBar) {
       if (has_next) zero_tail((pv_stage + 1) % STAGES, tile_j + 1, seg_L);
     }
 
-#ifdef GLA_EXPERIMENT_NO_COMPUTE
-    dma_prepare((pv_stage + STAGES - 1) % STAGES);
-    static_for<0, LPW>(dma_load);
-    (void)s_rd; (void)s_wr; (void)tile_j;
-    return;
-#endif
     // ---- [A] first score steps of tile k+1 (without a next tile they read
     //          whatever is in that stage and the result is dropped), under the
     //          masking and row-max search of tile k
@@ -748,7 +742,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     lsum = 0.f;
     pin_arch(neg_m);
     pin_arch(lsum);
-    GLA_PHASE(1);
     // ---- [A] (remaining) score steps of tile k+1 under the exponentials of tile k.
     //          Once the last score operands have been waited for, the first value
     //          operands of [B] are requested so that they arrive under these MFMAs.
@@ -763,8 +756,16 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       __builtin_amdgcn_sched_barrier(0);
     });
     l_run += lsum;
+    // Weights go into the value product rounded to bf16 (relative error up to
+    // 2^-9 each).  Spread over many keys that averages out; a row whose sum is
+    // carried by two or three keys keeps up to 2^-9 |v_j - out| of it.  So a
+    // tile holding a weight above 1/8 of its row's running sum (this lane's
+    // share of the sum: a smaller number, the test only fires more often) gets
+    // a second value pass with the rounding residuals, see residual_pass.
+    // Later tiles only make the sum larger, so every key left out of that
+    // pass ends with a normalised weight below 1/8.
+    const bool heavy_tile = __ballot(__builtin_amdgcn_exp2f(mx + neg_m) * 8.0f > l_run) != 0;
     xchg_post(s_wr);
-    GLA_PHASE(2);
 
     // ---- [B] O^T += V^T . P^T for tile k under the loads of the tile that reuses
     //          the stage of tile k-1.  Contraction slot (hi, j) of step st is token
@@ -832,12 +833,12 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       }
       __builtin_amdgcn_sched_barrier(0);
     });
+    if (heavy_tile) residual_pass(s_rd);
     // value addresses: every read of this tile has been issued
 #pragma unroll
     for (int d4 = 0; d4 < 4; ++d4)
 #pragma unroll
       for (int a = 0; a < 2; ++a) va[d4][a] += v_step;
-    GLA_PHASE(3);
   };
   // the two score register sets: tile t of a segment reads the one tile t-1 wrote
   f32x16_t s_even[NTB], s_odd[NTB];
@@ -883,6 +884,10 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     zero_tail(k % STAGES, seg_j0, seg_L);
     if constexpr (kEarlyBar) {  // the tile after it has landed too (everything requested so far has)
       if (seg_n >= 2) zero_tail((k + 1) % STAGES, seg_j0 + 1, seg_L);
+      // The zeroing is spread over all threads and the first iteration has no
+      // barrier before its value reads of tile k (they are requested at the end
+      // of its phase [A]): every wave's zeros must have landed before that.
+      if constexpr (NWAVES > 1) lds_barrier();
     }
     {
       const int ss = k % STAGES;
@@ -920,12 +925,10 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       });
     }
     xchg_post(s_even);
-    if (k == 0) GLA_STAMP(3);
 
     // two tiles per trip so that the two score register sets swap roles without copies
     for (int t = 0; t < seg_n; t += 2) {
       tile_iter(s_even, s_odd, k, seg_j0 + t, t + 1 < seg_n, t + 2 < seg_n, seg_L);
-      if (k == 0) GLA_STAMP(7);
       ++k;
       if (t + 1 < seg_n) {
         tile_iter(s_odd, s_even, k, seg_j0 + t + 1, t + 2 < seg_n, t + 3 < seg_n, seg_L);
@@ -933,7 +936,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       }
     }
     for (int i = 0; i < seg_n; ++i) advance<TOK>(p, UPB, cur);
-    GLA_STAMP(4);
 
     // ================= end of segment: write the unit's result or its partial
     wait_states<16>();  // output accumulators: last MFMA -> vector ALU reads
@@ -945,9 +947,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       pin_arch(one_t);
       const float r_tot = one_t[0];
       const float inv = r_tot > 0.f ? 1.0f / r_tot : 0.f;
-#ifdef GLA_EXPERIMENT_NO_STORES
-      if (inv != 12345.678f) continue;  // experiment build: results are computed and dropped
-#endif
       const float lse = l_tot > 0.f ? (m_ref + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
       const int lr = wave * 32 + col;
       const int64_t ob = row_b * p.out_s[0] + row_t * p.out_s[1] + row_h * p.out_s[2];
@@ -990,18 +989,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
         }
       }
     }
-    GLA_STAMP(5);
   }
-  GLA_STAMP(6);
-#ifdef GLA_EXPERIMENT_PHASE_CLOCKS
-  if (tid == 0) {
-    long long* const out_ph = (long long*)((char*)p.ws_out + (194ll << 20)) + (size_t)blockIdx.x * 8;
-    for (int i = 0; i < 4; ++i) out_ph[i] = ph_acc[i];
-    out_ph[4] = ph_n;
-  }
-#endif
 }
-#undef GLA_STAMP
-#undef GLA_PHASE
 
 }  // namespace gla
