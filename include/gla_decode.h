@@ -114,6 +114,23 @@ int gla_decode(const gla_decode_params* p);
 /* GTA decode (Section 3.3.1).  Requires d_nope == d_v / 2 (d_v even). */
 int gta_decode(const gla_decode_params* p);
 
+/* For callers that cannot allocate device memory or obtain a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the same operation as gla_decode (is_gta == 0) or gta_decode
+ * (is_gta != 0), with the partial results of the split over the key axis kept
+ * in a buffer of GLA_DECODE_NOALLOC_SCRATCH_BYTES that is part of the library
+ * image, one per GPU, held from the library's load to the end of the process.
+ * p->workspace and p->workspace_bytes are ignored; inputs and outputs are the
+ * caller's as before.  The call allocates and frees nothing.  The buffer covers
+ * every automatic plan (num_splits == 0) of the MFMA kernels; a problem that
+ * needs more (large explicit num_splits, or the generic kernel on very many
+ * rows) returns GLA_ERR_WORKSPACE_TOO_SMALL and enqueues nothing.  All calls on
+ * one GPU share that GPU's buffer: calls that may overlap in time (different
+ * streams, different threads) race on it and must be serialised by the caller.
+ * The GPU the buffer belongs to is the one current at the call. */
+#define GLA_DECODE_NOALLOC_SCRATCH_BYTES (72u << 20)
+int gla_decode_noalloc(const gla_decode_params* p, int is_gta);
+
 /* Bytes of workspace a call with these parameters needs (host only; pointer
  * fields are ignored).  Returns 0 for an invalid parameter set. */
 size_t gla_decode_workspace_size(const gla_decode_params* p, int is_gta);

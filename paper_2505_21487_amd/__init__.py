@@ -3,10 +3,10 @@
 `binding` wraps libgla_decode.so; `accounting` holds the byte / FLOP formulas
 used for roofline reporting; `harness` uploads synthetic problems to the GPU.
 """
-from .binding import (GLA_ERR_INVALID_ARG, GLA_ERR_LAUNCH, GLA_ERR_UNSUPPORTED_SHAPE,
+from .binding import (GLA_DECODE_NOALLOC_SCRATCH_BYTES, GLA_ERR_INVALID_ARG, GLA_ERR_LAUNCH, GLA_ERR_UNSUPPORTED_SHAPE,
                       GLA_ERR_WORKSPACE_TOO_SMALL, GLA_IMPL_AUTO, GLA_IMPL_GENERIC,
                       GLA_IMPL_TUNED, GLA_OK, GlaDecodeParams, GlaError, gla_decode,
-                      gla_decode_check_contents, gla_decode_profile, gla_decode_select_impl, gla_decode_version,
+                      gla_decode_check_contents, gla_decode_noalloc, gla_decode_profile, gla_decode_select_impl, gla_decode_version,
                       gla_decode_workspace_size, gla_status_string, gta_decode, load_library,
                       make_params, shape_params, decode_prepared)
 

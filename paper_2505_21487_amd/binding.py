@@ -23,8 +23,9 @@ GLA_ERR_WORKSPACE_TOO_SMALL = -3
 GLA_ERR_LAUNCH = -4
 GLA_IMPL_AUTO, GLA_IMPL_GENERIC, GLA_IMPL_TUNED = 0, 1, 2
 GLA_OUT_BF16, GLA_OUT_FP32 = 0, 1
+GLA_DECODE_NOALLOC_SCRATCH_BYTES = 72 << 20
 
-EXPORTS = ("gla_decode", "gta_decode", "gla_decode_workspace_size", "gla_decode_select_impl",
+EXPORTS = ("gla_decode", "gta_decode", "gla_decode_noalloc", "gla_decode_workspace_size", "gla_decode_select_impl",
            "gla_decode_profile", "gla_decode_check_contents", "gla_status_string", "gla_decode_version")
 
 
@@ -72,6 +73,8 @@ def load_library() -> ctypes.CDLL:
         lib.gla_decode.restype = ctypes.c_int
         lib.gta_decode.argtypes = [P]
         lib.gta_decode.restype = ctypes.c_int
+        lib.gla_decode_noalloc.argtypes = [P, ctypes.c_int]
+        lib.gla_decode_noalloc.restype = ctypes.c_int
         lib.gla_decode_workspace_size.argtypes = [P, ctypes.c_int]
         lib.gla_decode_workspace_size.restype = ctypes.c_size_t
         lib.gla_decode_select_impl.argtypes = [P, ctypes.c_int]
@@ -212,6 +215,15 @@ def decode_prepared(p: GlaDecodeParams, is_gta: bool = False) -> None:
     inspection and no allocation on the Python side."""
     lib = load_library()
     rc = (lib.gta_decode if is_gta else lib.gla_decode)(ctypes.byref(p))
+    if rc != GLA_OK:
+        raise GlaError(rc)
+
+
+def gla_decode_noalloc(p: GlaDecodeParams, is_gta: bool = False) -> None:
+    """Enqueue one decode call from a filled parameter block through the entry
+    point that allocates nothing: partial results go to the library's own fixed
+    buffer, p.workspace is ignored."""
+    rc = load_library().gla_decode_noalloc(ctypes.byref(p), int(is_gta))
     if rc != GLA_OK:
         raise GlaError(rc)
 

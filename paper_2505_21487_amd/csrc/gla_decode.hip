@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 
 #include "common.hpp"
 #include "generic_kernels.hpp"
@@ -15,7 +16,7 @@
 namespace gla {
 namespace {
 
-constexpr int kVersion = 101;  // 1.01: gla_decode_check_contents added
+constexpr int kVersion = 102;  // 1.02: gla_decode_noalloc added
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -149,6 +150,51 @@ int run(const gla_decode_params* p, int is_gta, hipEvent_t* ev) {
   return launch_generic(p, d, st, ev);
 }
 
+// ---- fixed scratch buffer of the allocation-free entry point -------------------
+// One array per GPU the library runs on, in that GPU's memory for the lifetime
+// of the process.  In host code the array's name is only a handle: the device
+// address is asked for once per device (with that device current) and every
+// later use goes through the address kept here.
+constexpr size_t kScratchBytes = (size_t)GLA_DECODE_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* scratch_addr[kMaxDevices];  // device address of `scratch` per device, null until asked for
+static std::mutex scratch_mutex;
+
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GLA_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_addr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return GLA_ERR_LAUNCH;
+    }
+    scratch_addr[dev] = ptr;
+  }
+  *out = scratch_addr[dev];
+  return GLA_OK;
+}
+
+int run_noalloc(const gla_decode_params* p, int is_gta) {
+  const int impl = select_impl(p, is_gta);
+  if (impl < 0) return impl;
+  const size_t need = impl == GLA_IMPL_TUNED ? tuned_workspace(p, is_gta) : generic_workspace(p);
+  if (need > kScratchBytes) return GLA_ERR_WORKSPACE_TOO_SMALL;  // beyond the fixed buffer: use gla_decode / gta_decode
+  gla_decode_params q = *p;
+  void* ptr = nullptr;
+  if (p->batch > 0) {
+    const int rc = scratch_of_current_device(&ptr);
+    if (rc != GLA_OK) return rc;
+  }
+  q.workspace = ptr;
+  q.workspace_bytes = kScratchBytes;
+  // (nothing in the buffer has to start at zero: every word a call reads back
+  // was written by that call's own kernels first)
+  return run(&q, is_gta, nullptr);
+}
+
 __global__ void zero_int_kernel(int* x) { *x = 0; }
 
 // Device contents the decode kernels trust: one thread per (sequence, table
@@ -213,6 +259,8 @@ int gla_decode(const gla_decode_params* p) { return gla::run(p, 0, nullptr); }
 
 int gta_decode(const gla_decode_params* p) { return gla::run(p, 1, nullptr); }
 
+int gla_decode_noalloc(const gla_decode_params* p, int is_gta) { return gla::run_noalloc(p, is_gta); }
+
 size_t gla_decode_workspace_size(const gla_decode_params* p, int is_gta) {
   const int impl = gla::select_impl(p, is_gta);
   if (impl < 0) return 0;
@@ -261,7 +309,7 @@ const char* gla_status_string(int status) {
     case GLA_OK: return "ok";
     case GLA_ERR_INVALID_ARG: return "invalid argument";
     case GLA_ERR_UNSUPPORTED_SHAPE: return "no kernel for this shape with the requested implementation";
-    case GLA_ERR_WORKSPACE_TOO_SMALL: return "workspace missing or too small";
+    case GLA_ERR_WORKSPACE_TOO_SMALL: return "workspace missing or too small (allocation-free entry point: the problem needs more than its fixed buffer)";
     case GLA_ERR_LAUNCH: return "HIP launch or event call failed";
     default: return "unknown status";
   }
