@@ -451,6 +451,19 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   f32x16_t o[NDB];
   f32x16_t o_one;   // every row: sum of the bf16-rounded weights (V block of ones)
   float m_ref = -INFINITY, l_run = 0.f;
+  float heavy_thr = -INFINITY;  // see the heavy-weight test in tile_iter
+  // log2 of the share of a row's running sum from which a weight counts as heavy.
+  // 1/4: keys passed over end below a quarter of their row's sum each, which
+  // bounds what their rounding can leave at 2^-8 times the weighted mean
+  // distance of at least five values from the output (about 1e-3 for values of
+  // unit variance; rows of four to eight random keys with every weight rounded
+  // stay below 4.7e-3 in a CPU model of this arithmetic, and there the largest
+  // weights, which this test catches, carry most of that).  At the start of a
+  // segment, while the running sums are small, some row of a workgroup passes
+  // the test on the first two or three tiles without holding a key that
+  // matters in the end: that is the cost, about 0.6 % of a long chunk (with a
+  // share of 1/8 it is 1.5 %).
+  constexpr float kLogHeavyShare = -2.0f;
   int n_vis = 0, n_vis_min = 0;
 
   // ---- building blocks of the tile pipeline ---------------------------------------
@@ -756,15 +769,6 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       __builtin_amdgcn_sched_barrier(0);
     });
     l_run += lsum;
-    // Weights go into the value product rounded to bf16 (relative error up to
-    // 2^-9 each).  Spread over many keys that averages out; a row whose sum is
-    // carried by two or three keys keeps up to 2^-9 |v_j - out| of it.  So a
-    // tile holding a weight above 1/8 of its row's running sum (this lane's
-    // share of the sum: a smaller number, the test only fires more often) gets
-    // a second value pass with the rounding residuals, see residual_pass.
-    // Later tiles only make the sum larger, so every key left out of that
-    // pass ends with a normalised weight below 1/8.
-    const bool heavy_tile = __ballot(__builtin_amdgcn_exp2f(mx + neg_m) * 8.0f > l_run) != 0;
     xchg_post(s_wr);
 
     // ---- [B] O^T += V^T . P^T for tile k under the loads of the tile that reuses
@@ -833,7 +837,23 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       }
       __builtin_amdgcn_sched_barrier(0);
     });
-    if (heavy_tile) residual_pass(s_rd);
+    // Weights went into the value product rounded to bf16 (relative error up to
+    // 2^-8 each).  Spread over many keys that averages out; a row whose sum is
+    // carried by two or three keys keeps up to 2^-8 w_1 w_2 |v_1 - v_2| of it.  So a
+    // tile holding a weight above kHeavyShare of its row's running sum gets a
+    // second value pass with the rounding residuals (residual_pass).  Later
+    // tiles only make the sum larger, so every key this test passes over ends
+    // with a normalised weight below that share.  In base-2 logarithms the test
+    // reads (row max of the tile) > log2(row sum) + log2(share), all taken
+    // absolute (not relative to the lazy reference), and the right-hand side
+    // only grows along a segment: heavy_thr holds its value from the last time
+    // it was worked out, one compare per tile decides whether it has to be
+    // worked out again.  Kept out of the straight-line path.
+    if (__builtin_expect(__ballot(mx > heavy_thr) != 0, 0)) {
+      const float l_row = half_swap_sum(l_run);  // both halves of the row
+      heavy_thr = __builtin_amdgcn_logf(l_row) + kLogHeavyShare - neg_m;  // (-inf while the row has no key)
+      if (__ballot(mx > heavy_thr) != 0) residual_pass(s_rd);
+    }
     // value addresses: every read of this tile has been issued
 #pragma unroll
     for (int d4 = 0; d4 < 4; ++d4)
@@ -872,6 +892,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
       pin_acc(o_one);
       m_ref = -INFINITY;
       l_run = 0.f;
+      heavy_thr = -INFINITY;
       // visible keys of this lane's row; padding rows are left unmasked (never stored)
       n_vis = row_valid ? (p.causal ? cur.L - p.T + 1 + row_t : cur.L) : 0x7fffffff;
       // the smallest count of the wave: its first row (lane 0) has the earliest query position
