@@ -6,6 +6,12 @@ over one batch of synthetic paged cache that is already resident in HBM.  Two
 disjoint draws of the workload alternate so that no call re-reads the pages of
 the previous one.  Prints one JSON line.
 
+Timing protocol.  The first K calls of the process are timed as they come
+(`first_calls_us`: cold clocks, then the 10-35 % slower transient of the first
+~15 ms of load).  Then an untimed pre-heat (`preheat`, default 150 ms of calls),
+the W warm-up calls, and the K timed calls that give `value`; `settled_us` is
+the same over at least 1000 further calls.
+
     python bench.py [--steps K] [--warmup W] [--config 1] [--q-len T]
 
 HBM traffic of the main kernel cannot be read from inside the process: it comes
@@ -82,9 +88,10 @@ def workload_key(config: int, q_len: int) -> str:
 
 
 def stored_traffic(config: int, q_len: int):
+    """Entry of traffic.json for a workload ({bytes_per_launch, date, ...}) or None."""
     try:
         with open(TRAFFIC_JSON) as fh:
-            return json.load(fh).get(workload_key(config, q_len), {}).get("bytes_per_launch")
+            return json.load(fh).get(workload_key(config, q_len))
     except (OSError, ValueError):
         return None
 
@@ -133,6 +140,8 @@ def summarise_pmc(fetch_dir: str, write_dir: str) -> int:
         except (OSError, ValueError):
             table = {}
         table[workload] = {"bytes_per_launch": total,
+                           "date": time.strftime("%Y-%m-%d"),
+                           "summary": "profiles/hbm_traffic_" + workload.replace("configs[", "cfg").replace("] q_len=", "_q") + ".txt",
                            "fetch_bytes": out["FETCH_SIZE"]["main_bytes_per_launch_scaled"],
                            "write_bytes": out["WRITE_SIZE"]["main_bytes_per_launch_scaled"],
                            "fetch_factor": out["FETCH_SIZE"]["factor"],
@@ -149,8 +158,11 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=300,
-                    help="untimed calls first; the default outlasts the clock transient of the first ~10 ms of load")
+    ap.add_argument("--warmup", type=int, default=300, help="untimed calls right before the timed ones")
+    ap.add_argument("--preheat-ms", type=float, default=150.0,
+                    help="milliseconds of untimed back-to-back calls BEFORE --warmup: the first ~15 ms of load on a cold "
+                         "GPU run 10-35 %% slower (clock transient, see the first_calls figures of the output line); "
+                         "0 switches the pre-heat off")
     ap.add_argument("--config", type=int, default=1, help="index into the configuration list")
     ap.add_argument("--q-len", type=int, default=0, help="override query length (1..4)")
     ap.add_argument("--lens", default="", help="instead of --config: sequence lengths, e.g. 131072 or "
@@ -208,15 +220,34 @@ def main() -> int:
     probs = (d0, d1)
 
     fn(*probs[0].args(), **kw)  # once through the tensor-level entry point
+    torch.cuda.synchronize()
+
+    def timed(n):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(n):
+            gla.decode_prepared(prm[i & 1], is_gta)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / max(n, 1) * 1e6
+
+    # (1) the very first calls of the process, as they are: cold clocks, then the transient
+    first_us = timed(args.steps)
+    # (2) pre-heat: untimed load until the clocks have settled
+    preheat_calls = 0
+    t_pre = time.perf_counter()
+    while args.preheat_ms > 0 and (time.perf_counter() - t_pre) * 1e3 < args.preheat_ms:
+        for i in range(50):
+            gla.decode_prepared(prm[i & 1], is_gta)
+        torch.cuda.synchronize()
+        preheat_calls += 50
+    preheat_ms = (time.perf_counter() - t_pre) * 1e3
+    # (3) the contract: W untimed calls, then exactly K timed ones
     for i in range(args.warmup):
         gla.decode_prepared(prm[i & 1], is_gta)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        gla.decode_prepared(prm[i & 1], is_gta)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    us_per_call = dt / args.steps * 1e6
+    us_per_call = timed(args.steps)
+    # (4) the same once more over a long stretch (a short K is noisy)
+    settled_n = max(args.steps, 1000)
+    settled_us = timed(settled_n)
 
     # per-kernel durations from HIP events recorded by the library on its launch stream
     main_us = comb_us = 0.0
@@ -236,9 +267,15 @@ def main() -> int:
         roof = {"bound": "mfma", "achieved": fl / (main_us * 1e-6) / 1e12,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None if (args.lens or args.page_size != 64) else stored_traffic(args.config, p0.T)
+    tr = None if (args.lens or args.page_size != 64) else stored_traffic(args.config, p0.T)
+    roof["traffic"] = tr["bytes_per_launch"] if tr else None
+    roof["traffic_source"] = (f"stored, not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
+                              f"{tr.get('date', 'unknown date')}, {tr.get('summary', 'profiles/')}") if tr else None
     roof["kernel"] = "main (split-KV attention)"
     roof["kernel_us"] = main_us
+    roof["kernel_us_source"] = (f"HIP events recorded by the library on its launch stream around the kernel, mean of "
+                                f"2 x {args.profile_iters} launches after the timed region (a rocprofv3 kernel trace of "
+                                f"the same command reads a few us less: it excludes the gap to the event records)")
     roof["combine_us"] = comb_us
 
     rec = {
@@ -261,6 +298,10 @@ def main() -> int:
                    "kind": p0.kind,
                    "impl": {1: "generic", 2: "tuned"}.get(impl, str(impl)),
                    "num_splits": args.num_splits},
+        "first_calls_us": first_us,
+        "preheat": {"calls": preheat_calls, "ms": preheat_ms},
+        "settled_us": settled_us,
+        "settled_steps": settled_n,
         "cache_bytes": cache_b,
         "cache_GBps": cache_b / (us_per_call * 1e-6) / 1e9,
         "hbm_frac_of_peak": cache_b / (us_per_call * 1e-6) / 1e9 / HBM_PEAK_GBPS,
