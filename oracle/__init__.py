@@ -50,6 +50,10 @@ def _load():
         lib.gla_oracle_merge.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
                                          ctypes.c_int64, ctypes.c_int, ctypes.c_void_p,
                                          ctypes.c_void_p]
+        lib.gla_oracle_project.restype = ctypes.c_int
+        lib.gla_oracle_project.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                           ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_int, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -132,6 +136,24 @@ def merge(part_out: np.ndarray, part_lse: np.ndarray):
     if rc != 0:
         raise ValueError("gla_oracle_merge: bad argument")
     return out, lse
+
+
+def project(a: np.ndarray, w: np.ndarray, *, sum_groups: bool) -> np.ndarray:
+    """Projection by per-group weights: a [M, G, K] and w [G, N, K] are uint16
+    arrays of bf16 bit patterns; returns fp64 [M, G, N] (sum_groups False: the
+    absorbed queries, one weight matrix per head) or [M, N] summed over the
+    groups (the grouped output projection)."""
+    lib = _load()
+    a = np.ascontiguousarray(a, dtype=np.uint16)
+    w = np.ascontiguousarray(w, dtype=np.uint16)
+    M, G, K = a.shape
+    G2, N, K2 = w.shape
+    assert G2 == G and K2 == K
+    c = np.empty((M, N) if sum_groups else (M, G, N), dtype=np.float64)
+    rc = lib.gla_oracle_project(_ptr(a), G * K, K, _ptr(w), M, G, N, K, int(bool(sum_groups)), _ptr(c))
+    if rc != 0:
+        raise ValueError("gla_oracle_project: bad argument")
+    return c
 
 
 def decode_problem(p, **kw):

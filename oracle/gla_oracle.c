@@ -32,9 +32,16 @@
  * Everything is two-pass and accumulated in fp64; bf16 inputs are widened
  * exactly.  No blocking, no online softmax, no fusion.
  *
+ * The two projections around the attention (gla_oracle_project, at the end of
+ * this file): the key up-projection absorbed on the query side (Section 2.1)
+ * and the grouped output projection with the value up-projection absorbed
+ * (Section 3.3.2), both as plain fp64 sums.
+ *
  * Pins (tests/test_oracle_pins.py): equality with explicit up-projected
  * attention, with an assembled-K GQA for GTA, closed forms, paging invariance,
- * split/merge identity.  No function here is unpinned.
+ * split/merge identity; for the projections: the whole absorbed block against
+ * explicit per-head attention with separate W_UK, W_UV, W_O, numpy products,
+ * identity weights.  No function here is unpinned.
  */
 #include <math.h>
 #include <stdint.h>
@@ -204,6 +211,45 @@ int gla_oracle_merge(const double* part_out, const double* part_lse, int n_parts
       const double* po = part_out + ((int64_t)s * rows + r) * d_v;
       for (int d = 0; d < d_v; ++d) o[d] += w * po[d];
     }
+  }
+  return 0;
+}
+
+/*
+ * The projections on either side of the attention, both instances of
+ *
+ *      C[m][g][n] = sum_k A[m][g][k] * W[g][n][k]          (sum_groups == 0)
+ *      C[m][n]    = sum_g sum_k A[m][g][k] * W[g][n][k]    (sum_groups != 0)
+ *
+ * Query side (Section 2.1): with W = W_UK of head g (latent dim n, head dim k)
+ * and A the raw per-head queries, C is the absorbed query that scores directly
+ * against the latent: q . (W_UK^T c) == (W_UK q) . c.
+ * Output side (Section 3.3.2): with A the latent-space attention output of group
+ * g (its heads' outputs side by side, k over g_q * d_c) and W = W_g^vo stored
+ * output-major, the sum over groups is the block's output; with several devices
+ * that sum is the all-reduce.
+ *
+ * a: bf16 bits, element strides (row m, group g), k contiguous
+ * w: bf16 bits [G][N][K] contiguous
+ * c: fp64 [M][G][N] or [M][N] contiguous
+ * returns 0, or -1 on a bad argument.
+ */
+int gla_oracle_project(const uint16_t* a, int64_t a_row_stride, int64_t a_group_stride,
+                       const uint16_t* w, int M, int G, int N, int K, int sum_groups, double* c) {
+  if (M < 0 || G < 1 || N < 1 || K < 1) return -1;
+#pragma omp parallel for schedule(static)
+  for (int64_t mn = 0; mn < (int64_t)M * N; ++mn) {
+    const int m = (int)(mn / N), n = (int)(mn % N);
+    double total = 0.0;
+    for (int g = 0; g < G; ++g) {
+      const uint16_t* ar = a + m * a_row_stride + g * a_group_stride;
+      const uint16_t* wr = w + ((int64_t)g * N + n) * K;
+      double acc = 0.0;
+      for (int k = 0; k < K; ++k) acc += bf16_to_f64(ar[k]) * bf16_to_f64(wr[k]);
+      if (sum_groups) total += acc;
+      else c[((int64_t)m * G + g) * N + n] = acc;
+    }
+    if (sum_groups) c[(int64_t)m * N + n] = total;
   }
   return 0;
 }

@@ -68,6 +68,82 @@ def test_absorbed_equals_explicit_upprojection():
         np.testing.assert_allclose(got, ref, rtol=0, atol=TOL)
 
 
+def bits_of(x: np.ndarray) -> np.ndarray:
+    """fp64 array of values that bf16 holds exactly -> their bf16 bit patterns."""
+    t = torch.from_numpy(np.ascontiguousarray(x)).to(torch.bfloat16)
+    assert np.array_equal(f64(t), x), "value not representable in bf16"
+    return bf16_bits(t)
+
+
+def test_whole_absorbed_block_equals_explicit_attention_with_separate_projections():
+    """Sections 2.1 and 3.3.2 end to end on a tiny case: raw per-head queries,
+    W_UK absorbed on the query side (oracle.project, one matrix per head), the
+    latent attention, then the grouped output projection with W^vo = W_UV W_O
+    (oracle.project summed over the groups), against per-head attention over
+    explicitly up-projected keys and values followed by the ordinary output
+    projection sum_h o_h W_O^h.  Small integer weights keep every intermediate
+    that crosses a bf16 interface exactly representable, except the latent
+    output itself, which BOTH sides take rounded to bf16: the identity checked
+    downstream of it is then exact."""
+    rng = np.random.default_rng(21)
+    h_q, h_c, d_c, d_h, d_r, D, L, B, T = 6, 2, 16, 8, 4, 10, 29, 2, 2
+    g_q = h_q // h_c
+    p = make_problem("block", seq_lens=[L, 7], T=T, h_q=h_q, h_c=h_c, d_v=d_c, d_r=d_r, page_size=8, seed=12, scale=0.3)
+    W_UK = rng.integers(-1, 2, size=(h_q, d_c, d_h)).astype(np.float64)       # [head][latent dim n][head dim k]
+    W_UV = rng.integers(-1, 2, size=(h_q, d_c, d_h)).astype(np.float64)
+    W_O = rng.integers(-1, 2, size=(h_q, d_h, D)).astype(np.float64)
+    q_raw = rng.integers(-2, 3, size=(B, T, h_q, d_h)).astype(np.float64)
+    # --- query side: q~[m][h][n] = sum_k W_UK[h][n][k] q[m][h][k]
+    q_abs = oracle.project(bits_of(q_raw.reshape(B * T, h_q, d_h)), bits_of(W_UK), sum_groups=False)
+    np.testing.assert_array_equal(q_abs, np.einsum("hnk,mhk->mhn", W_UK, q_raw.reshape(B * T, h_q, d_h)))
+    p.q_nope = torch.from_numpy(q_abs.reshape(B, T, h_q, d_c)).to(torch.bfloat16)
+    assert np.array_equal(f64(p.q_nope).reshape(B * T, h_q, d_c), q_abs)      # |.| <= 16: exact in bf16
+    out, _ = oracle.decode_problem(p)                                          # [B, T, h_q, d_c] latent-space outputs
+    out_bf = torch.from_numpy(out).to(torch.bfloat16)                          # the interface between the two kernels
+    # --- output side: W^vo of group g, output-major: [D][g_q * d_c], rows of head h inside it = W_UV[h] W_O[h]
+    W_vo = np.einsum("hcd,hdn->hcn", W_UV, W_O)                                # [h_q][d_c][D], |.| <= 8
+    W_vo_g = W_vo.reshape(h_c, g_q * d_c, D).transpose(0, 2, 1)                # [G][N = D][K = g_q * d_c]
+    y = oracle.project(bf16_bits(out_bf.reshape(B * T, h_c, g_q * d_c)), bits_of(W_vo_g), sum_groups=True)
+    # --- explicit: per-head keys / values, textbook attention, up-projected value output, ordinary W_O
+    y_ref = np.zeros((B * T, D))
+    qr = f64(p.q_rope)
+    for b in range(B):
+        st, rp = gather_logical(p, b)
+        for t in range(T):
+            n_vis = int(p.seq_lens[b]) - T + 1 + t
+            for h in range(h_q):
+                c = st[h // g_q][:n_vis]
+                K = np.concatenate([c @ W_UK[h], rp[:n_vis]], axis=1)
+                V = c @ W_UV[h]
+                o_h, _ = textbook_attention(np.concatenate([q_raw[b, t, h], qr[b, t, h]]), K, V, p.scale)
+                # the explicit per-head output equals the up-projected latent output (the identity of the test above) ...
+                np.testing.assert_allclose(out[b, t, h] @ W_UV[h], o_h, rtol=0, atol=TOL)
+                # ... and downstream of the bf16 interface both sides use the rounded latent output
+                y_ref[b * T + t] += (f64(out_bf)[b, t, h] @ W_UV[h]) @ W_O[h]
+    np.testing.assert_allclose(y, y_ref, rtol=0, atol=1e-9)
+
+
+def test_projection_against_numpy_and_closed_forms():
+    """oracle.project against numpy's fp64 products on random bf16 data, with and
+    without the sum over groups; identity weights copy the input; a transposed
+    weight operand or a group taken from the wrong stride would show."""
+    g = torch.Generator().manual_seed(5)
+    M, G, N, K = 7, 3, 11, 20
+    a = torch.randn(M, G, K, generator=g).to(torch.bfloat16)
+    w = torch.randn(G, N, K, generator=g).to(torch.bfloat16)
+    ref = np.einsum("mgk,gnk->mgn", f64(a), f64(w))
+    np.testing.assert_allclose(oracle.project(bf16_bits(a), bf16_bits(w), sum_groups=False), ref, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(oracle.project(bf16_bits(a), bf16_bits(w), sum_groups=True), ref.sum(axis=1), rtol=0, atol=1e-12)
+    eye = torch.eye(K).repeat(G, 1, 1).to(torch.bfloat16)                      # N == K: C[m][g] = A[m][g]
+    np.testing.assert_array_equal(oracle.project(bf16_bits(a), bf16_bits(eye), sum_groups=False), f64(a))
+    one_hot = torch.zeros(G, N, K, dtype=torch.bfloat16)
+    one_hot[1, 4, 9] = 1.0                                                     # picks A[m][1][9] into C[m][1][4] only
+    got = oracle.project(bf16_bits(a), bf16_bits(one_hot), sum_groups=False)
+    want = np.zeros((M, G, N))
+    want[:, 1, 4] = f64(a)[:, 1, 9]
+    np.testing.assert_array_equal(got, want)
+
+
 # ---------------------------------------------------------------- P2
 def test_softmax_weights_are_a_distribution():
     p = make_problem("p2", seq_lens=[19, 64, 1], T=2, h_q=4, h_c=2, d_v=8, d_r=4, page_size=16,
