@@ -79,6 +79,43 @@ def cpu_baseline(p, budget_s: float = 15.0):
     }
 
 
+def time_projections(p, model_dim: int, dev, iters: int = 200):
+    """The two GEMMs around the attention at the workload's shape, timed with
+    events on the current stream: absorbed query (one W_UK per head, raw head
+    dim 128) and grouped output projection to `model_dim`.  Both are bound by
+    reading their weights once; reported against the HBM peak."""
+    import torch
+    import paper_2505_21487_amd as gla
+    from workloads import projection_weights
+    M, d_h = p.B * p.T, 128
+    g_q = p.h_q // p.h_c
+    q_raw = torch.randn(M, p.h_q, d_h, device=dev).to(torch.bfloat16)
+    w_uk = projection_weights(p.h_q, p.d_v, d_h, seed=1).to(dev)
+    o = (torch.randn(M, p.h_c, g_q * p.d_v, device=dev) * 0.05).to(torch.bfloat16)
+    w_vo = projection_weights(p.h_c, model_dim, g_q * p.d_v, seed=2).to(dev)
+    q_abs = torch.empty(M, p.h_q, p.d_v, dtype=torch.bfloat16, device=dev)
+    y = torch.empty(M, model_dim, dtype=torch.bfloat16, device=dev)
+    out = {}
+    for name, fn, a, w, c in (("absorb_query", gla.gla_absorb_query, q_raw, w_uk, q_abs),
+                              ("output_proj", gla.gla_output_proj, o, w_vo, y)):
+        ws = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
+        for _ in range(20):
+            fn(a, w, out=c, workspace=ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn(a, w, out=c, workspace=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / iters
+        nbytes = (a.numel() + w.numel() + c.numel()) * 2
+        out[name] = {"us": us, "shape": {"rows": M, "groups": int(w.shape[0]), "n": int(w.shape[1]), "k": int(w.shape[2])},
+                     "algorithmic_bytes": nbytes, "GBps": nbytes / (us * 1e-6) / 1e9,
+                     "frac_of_hbm_peak": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+                     "tflops": 2.0 * M * w.numel() / (us * 1e-6) / 1e12}
+    return out
+
+
 CAL_COPY_BYTES = 1 << 30
 TRAFFIC_JSON = os.path.join(ROOT, "paper_2505_21487_amd", "traffic.json")
 
@@ -172,6 +209,8 @@ def main() -> int:
     ap.add_argument("--num-splits", type=int, default=0)
     ap.add_argument("--impl", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--model-dim", type=int, default=5120,
+                    help="model dim D of the grouped output projection timed beside the attention (0: skip the projections)")
     ap.add_argument("--profile-iters", type=int, default=200)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also make a plain 1 GiB device copy (reference for the HBM counters)")
@@ -309,6 +348,8 @@ def main() -> int:
         "flops_per_cache_byte": ai,
         "roofline": roof,
     }
+    if args.model_dim > 0 and not is_gta:
+        rec["projections"] = time_projections(p0, args.model_dim, dev)
     if args.calibration_copy:
         src = torch.empty(CAL_COPY_BYTES // 4, dtype=torch.float32, device=dev).fill_(1.0)
         dst = torch.empty_like(src)

@@ -135,6 +135,60 @@ int gla_decode_noalloc(const gla_decode_params* p, int is_gta);
  * fields are ignored).  Returns 0 for an invalid parameter set. */
 size_t gla_decode_workspace_size(const gla_decode_params* p, int is_gta);
 
+/* ---- the two projections around the attention -----------------------------------
+ * Both compute, on bf16 operands with fp32 accumulation,
+ *
+ *     gla_absorb_query:  C[m][g][n] = sum_k A[m][g][k] * W[g][n][k]
+ *     gla_output_proj:   C[m][n]    = sum_g sum_k A[m][g][k] * W[g][n][k]
+ *
+ * over the `rows` query rows m of a decode step (batch * q_len, flattened).
+ *
+ * gla_absorb_query (Section 2.1: the key up-projection W^UK absorbed on the query
+ * side).  groups = query heads, k = d_h (raw head dim), n = d_c (latent dim):
+ * A = raw non-RoPE queries [rows][h_q][d_h], W[g] = W^UK of head g stored
+ * [d_c][d_h], C = the absorbed queries [rows][h_q][d_c] that gla_decode takes as
+ * q_nope (q . (W^UK^T c) == (W^UK q) . c).  The RoPE part of the query is not
+ * touched.
+ *
+ * gla_output_proj (Section 3.3.2: O~_g = O_g W_g^vo, summed over the groups; the
+ * value up-projection W^UV is absorbed in W^vo).  groups = latent heads h_c,
+ * k = g_q * d_c (the latent outputs of the group's heads side by side, which is
+ * how gla_decode lays out `out`), n = model dim D: A = out [rows][h_c][g_q * d_c],
+ * W[g] = W_g^vo stored output-major [D][g_q * d_c], C = [rows][D].  On several
+ * devices each rank would run this on its own groups and all-reduce C.
+ *
+ * Weights are contiguous [groups][n][k] (k fastest).  All pointers are device
+ * pointers, 16-byte aligned; strides in elements.  Needs k % 64 == 0,
+ * n % 32 == 0, a strides % 8 == 0, c strides % 4 == 0 (else
+ * GLA_ERR_UNSUPPORTED_SHAPE).  When the input features are cut into ranges
+ * (always for gla_output_proj with more than one group) fp32 partial sums go to
+ * `workspace` (gla_proj_workspace_size bytes, 256-byte aligned) and are added
+ * in a fixed order by a second kernel: results are reproducible bit for bit.
+ * Nothing is allocated, nothing synchronises. */
+typedef struct gla_proj_params {
+  int32_t rows;             /* M = batch * q_len                                              */
+  int32_t groups;           /* G                                                              */
+  int32_t n;                /* output features per group                                      */
+  int32_t k;                /* input features per group                                       */
+  const void* a;            /* bf16 A[m][g][k]                                                */
+  int64_t a_row_stride;     /* elements between rows m                                        */
+  int64_t a_group_stride;   /* elements between groups g                                      */
+  const void* w;            /* bf16 W[g][n][k], contiguous                                    */
+  void* c;                  /* c_dtype; absorb: C[m][g][n], output projection: C[m][n]        */
+  int64_t c_row_stride;     /* elements between rows m                                        */
+  int64_t c_group_stride;   /* elements between groups g (ignored by gla_output_proj)         */
+  int32_t c_dtype;          /* GLA_OUT_BF16 or GLA_OUT_FP32                                   */
+  void* workspace;
+  size_t workspace_bytes;
+  void* stream;             /* hipStream_t                                                    */
+} gla_proj_params;
+
+int gla_absorb_query(const gla_proj_params* p);
+int gla_output_proj(const gla_proj_params* p);
+/* Bytes of workspace (host only; pointer fields ignored); sum_groups = 0 for
+ * gla_absorb_query, 1 for gla_output_proj.  0 for an invalid parameter set. */
+size_t gla_proj_workspace_size(const gla_proj_params* p, int sum_groups);
+
 /* Which implementation a call would run: GLA_IMPL_GENERIC or GLA_IMPL_TUNED,
  * or a negative error code.  Host only; pointer fields are ignored. */
 int gla_decode_select_impl(const gla_decode_params* p, int is_gta);

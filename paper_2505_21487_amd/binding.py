@@ -25,7 +25,8 @@ GLA_IMPL_AUTO, GLA_IMPL_GENERIC, GLA_IMPL_TUNED = 0, 1, 2
 GLA_OUT_BF16, GLA_OUT_FP32 = 0, 1
 GLA_DECODE_NOALLOC_SCRATCH_BYTES = 72 << 20
 
-EXPORTS = ("gla_decode", "gta_decode", "gla_decode_noalloc", "gla_decode_workspace_size", "gla_decode_select_impl",
+EXPORTS = ("gla_decode", "gta_decode", "gla_decode_noalloc", "gla_absorb_query", "gla_output_proj",
+           "gla_proj_workspace_size", "gla_decode_workspace_size", "gla_decode_select_impl",
            "gla_decode_profile", "gla_decode_check_contents", "gla_status_string", "gla_decode_version")
 
 
@@ -46,6 +47,18 @@ class GlaDecodeParams(ctypes.Structure):
         ("lse", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("num_splits", ctypes.c_int32), ("impl", ctypes.c_int32),
+        ("stream", ctypes.c_void_p),
+    ]
+
+
+class GlaProjParams(ctypes.Structure):
+    _fields_ = [
+        ("rows", ctypes.c_int32), ("groups", ctypes.c_int32), ("n", ctypes.c_int32), ("k", ctypes.c_int32),
+        ("a", ctypes.c_void_p), ("a_row_stride", ctypes.c_int64), ("a_group_stride", ctypes.c_int64),
+        ("w", ctypes.c_void_p),
+        ("c", ctypes.c_void_p), ("c_row_stride", ctypes.c_int64), ("c_group_stride", ctypes.c_int64),
+        ("c_dtype", ctypes.c_int32),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p),
     ]
 
@@ -75,6 +88,13 @@ def load_library() -> ctypes.CDLL:
         lib.gta_decode.restype = ctypes.c_int
         lib.gla_decode_noalloc.argtypes = [P, ctypes.c_int]
         lib.gla_decode_noalloc.restype = ctypes.c_int
+        PP = ctypes.POINTER(GlaProjParams)
+        lib.gla_absorb_query.argtypes = [PP]
+        lib.gla_absorb_query.restype = ctypes.c_int
+        lib.gla_output_proj.argtypes = [PP]
+        lib.gla_output_proj.restype = ctypes.c_int
+        lib.gla_proj_workspace_size.argtypes = [PP, ctypes.c_int]
+        lib.gla_proj_workspace_size.restype = ctypes.c_size_t
         lib.gla_decode_workspace_size.argtypes = [P, ctypes.c_int]
         lib.gla_decode_workspace_size.restype = ctypes.c_size_t
         lib.gla_decode_select_impl.argtypes = [P, ctypes.c_int]
@@ -226,6 +246,50 @@ def gla_decode_noalloc(p: GlaDecodeParams, is_gta: bool = False) -> None:
     rc = load_library().gla_decode_noalloc(ctypes.byref(p), int(is_gta))
     if rc != GLA_OK:
         raise GlaError(rc)
+
+
+def _proj(sum_groups: bool, a: torch.Tensor, w: torch.Tensor, *, out=None, out_dtype=torch.bfloat16,
+          workspace=None) -> torch.Tensor:
+    """a [rows, G, K] (strided rows / groups, K contiguous), w [G, N, K] contiguous."""
+    lib = load_library()
+    M, G, K = a.shape
+    G2, N, K2 = w.shape
+    assert (G2, K2) == (G, K) and a.dtype == torch.bfloat16 and w.dtype == torch.bfloat16
+    assert a.stride(-1) == 1 and w.is_contiguous()
+    if out is None:
+        out = torch.empty((M, N) if sum_groups else (M, G, N), dtype=out_dtype, device=a.device)
+    assert out.stride(-1) == 1
+    p = GlaProjParams()
+    p.rows, p.groups, p.n, p.k = M, G, N, K
+    p.a, p.a_row_stride, p.a_group_stride = a.data_ptr(), a.stride(0), a.stride(1)
+    p.w = w.data_ptr()
+    p.c, p.c_row_stride = out.data_ptr(), out.stride(0)
+    p.c_group_stride = 0 if sum_groups else out.stride(1)
+    p.c_dtype = {torch.bfloat16: GLA_OUT_BF16, torch.float32: GLA_OUT_FP32}[out.dtype]
+    need = int(lib.gla_proj_workspace_size(ctypes.byref(p), int(sum_groups)))
+    if need == 0:
+        raise GlaError(GLA_ERR_UNSUPPORTED_SHAPE)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=a.device)
+    p.workspace, p.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    p.stream = torch.cuda.current_stream(a.device).cuda_stream
+    with torch.cuda.device(a.device):
+        rc = (lib.gla_output_proj if sum_groups else lib.gla_absorb_query)(ctypes.byref(p))
+    if rc != GLA_OK:
+        raise GlaError(rc)
+    return out
+
+
+def gla_absorb_query(q: torch.Tensor, w_uk: torch.Tensor, **kw) -> torch.Tensor:
+    """Absorbed queries (Section 2.1): q [rows, h_q, d_h] raw non-RoPE queries,
+    w_uk [h_q, d_c, d_h] -> [rows, h_q, d_c]."""
+    return _proj(False, q, w_uk, **kw)
+
+
+def gla_output_proj(o: torch.Tensor, w_vo: torch.Tensor, **kw) -> torch.Tensor:
+    """Grouped output projection (Section 3.3.2): o [rows, h_c, g_q * d_c] latent
+    outputs grouped by latent head, w_vo [h_c, D, g_q * d_c] -> [rows, D]."""
+    return _proj(True, o, w_vo, **kw)
 
 
 def gla_decode_check_contents(p: GlaDecodeParams, is_gta: bool = False) -> int:

@@ -11,12 +11,13 @@
 
 #include "common.hpp"
 #include "generic_kernels.hpp"
+#include "proj_kernels.hpp"
 #include "tuned_kernels.hpp"
 
 namespace gla {
 namespace {
 
-constexpr int kVersion = 102;  // 1.02: gla_decode_noalloc added
+constexpr int kVersion = 103;  // 1.03: gla_absorb_query, gla_output_proj
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -195,6 +196,88 @@ int run_noalloc(const gla_decode_params* p, int is_gta) {
   return run(&q, is_gta, nullptr);
 }
 
+// ---- projections around the attention ------------------------------------------
+struct ProjPlan {
+  int mt;          // 32-row blocks of query rows per workgroup (1 or 2)
+  int ksplit;      // ranges the input features of a group are cut into
+  int k_per_split;
+  bool direct;     // no partials: the kernel writes the result itself
+  size_t part_bytes;
+};
+
+int proj_plan(const gla_proj_params* p, int sum_groups, ProjPlan* plan) {
+  if (!p || p->rows < 0 || p->groups < 1 || p->n < 1 || p->k < 1) return GLA_ERR_INVALID_ARG;
+  if (p->c_dtype != GLA_OUT_BF16 && p->c_dtype != GLA_OUT_FP32) return GLA_ERR_INVALID_ARG;
+  if ((int64_t)p->rows * p->groups * p->n > (int64_t)0x7fffffff) return GLA_ERR_INVALID_ARG;
+  // what the kernel assumes: whole steps of 64 input features, whole waves of 32 output features, 16-byte loads
+  if (p->k % 64 || p->n % 32) return GLA_ERR_UNSUPPORTED_SHAPE;
+  if (p->a_row_stride % 8 || p->a_group_stride % 8 || p->c_row_stride % 4 || p->c_group_stride % 4)
+    return GLA_ERR_UNSUPPORTED_SHAPE;
+  plan->mt = p->rows <= 32 ? 1 : 2;
+  const int64_t tiles = (int64_t)((p->n + 127) / 128) * ((p->rows + 32 * plan->mt - 1) / (32 * plan->mt));
+  // Ranges per group: one workgroup is resident per compute unit (its LDS ring), so the grid runs in
+  // rounds of as many workgroups as there are compute units.  Among the cuts into ranges of at least
+  // 512 features pick the one with the least estimated time: rounds x (steps per range + a fixed cost
+  // per workgroup of about four steps: start-up latency, partial store).
+  int ks = 1;
+  {
+    const int cus = device_cu_count();
+    double best = 1e30;
+    for (int c = 1; c <= 64 && p->k / c >= 512 && (p->k / c) % 64 == 0; c *= 2) {
+      const int64_t wgs = tiles * p->groups * c;
+      const double t = (double)((wgs + cus - 1) / cus) * (p->k / c / 64 + 4);
+      if (t < best * 0.999) { best = t; ks = c; }
+    }
+  }
+  plan->ksplit = ks;
+  plan->k_per_split = p->k / ks;
+  plan->direct = ks == 1 && (!sum_groups || p->groups == 1);
+  plan->part_bytes = plan->direct ? 0 : (size_t)p->groups * ks * p->rows * p->n * sizeof(float);
+  return GLA_OK;
+}
+
+int run_proj(const gla_proj_params* p, int sum_groups) {
+  ProjPlan plan;
+  const int rc = proj_plan(p, sum_groups, &plan);
+  if (rc != GLA_OK) return rc;
+  if (p->rows == 0) return GLA_OK;
+  if (!p->a || !p->w || !p->c) return GLA_ERR_INVALID_ARG;
+  if (((uintptr_t)p->a | (uintptr_t)p->w | (uintptr_t)p->c) & 15u) return GLA_ERR_UNSUPPORTED_SHAPE;
+  if (plan.part_bytes > 0 && (!p->workspace || p->workspace_bytes < plan.part_bytes)) return GLA_ERR_WORKSPACE_TOO_SMALL;
+  if (plan.part_bytes > 0 && ((uintptr_t)p->workspace & 255u)) return GLA_ERR_INVALID_ARG;
+  ProjParams d;
+  d.a = (const uint16_t*)p->a;
+  d.w = (const uint16_t*)p->w;
+  d.c = p->c;
+  d.part = (float*)p->workspace;
+  d.a_row = p->a_row_stride;
+  d.a_group = p->a_group_stride;
+  d.c_row = p->c_row_stride;
+  d.c_group = p->c_group_stride;
+  d.M = p->rows;
+  d.G = p->groups;
+  d.N = p->n;
+  d.K = p->k;
+  d.ksplit = plan.ksplit;
+  d.k_per_split = plan.k_per_split;
+  d.sum_groups = sum_groups ? 1 : 0;
+  d.c_fp32 = p->c_dtype == GLA_OUT_FP32;
+  d.direct = plan.direct ? 1 : 0;
+  hipStream_t st = (hipStream_t)p->stream;
+  const dim3 grid((unsigned)((p->n + 127) / 128), (unsigned)((p->rows + 32 * plan.mt - 1) / (32 * plan.mt)),
+                  (unsigned)(p->groups * plan.ksplit));
+  if (grid.y > 65535u || grid.z > 65535u) return GLA_ERR_UNSUPPORTED_SHAPE;
+  if (plan.mt == 1) hipLaunchKernelGGL(proj_kernel<1>, grid, dim3(256), 0, st, d);
+  else hipLaunchKernelGGL(proj_kernel<2>, grid, dim3(256), 0, st, d);
+  if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
+  if (!plan.direct) {
+    const int64_t outs = (int64_t)p->rows * (sum_groups ? 1 : p->groups) * (p->n / 4);
+    hipLaunchKernelGGL(proj_reduce_kernel, dim3((unsigned)((outs + 255) / 256)), dim3(256), 0, st, d);
+    if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
+  }
+  return GLA_OK;
+}
+
 __global__ void zero_int_kernel(int* x) { *x = 0; }
 
 // Device contents the decode kernels trust: one thread per (sequence, table
@@ -267,6 +350,16 @@ size_t gla_decode_workspace_size(const gla_decode_params* p, int is_gta) {
   // A little more than nothing, so callers can always pass a real buffer.
   const size_t need = impl == GLA_IMPL_TUNED ? gla::tuned_workspace(p, is_gta) : gla::generic_workspace(p);
   return std::max<size_t>(need, 256);
+}
+
+int gla_absorb_query(const gla_proj_params* p) { return gla::run_proj(p, 0); }
+
+int gla_output_proj(const gla_proj_params* p) { return gla::run_proj(p, 1); }
+
+size_t gla_proj_workspace_size(const gla_proj_params* p, int sum_groups) {
+  gla::ProjPlan plan;
+  if (gla::proj_plan(p, sum_groups, &plan) != GLA_OK) return 0;
+  return std::max<size_t>(plan.part_bytes, 256);
 }
 
 int gla_decode_select_impl(const gla_decode_params* p, int is_gta) {

@@ -1,0 +1,195 @@
+// The two projections around the decode attention (paper Sections 2.1 and
+// 3.3.2), both instances of a skinny grouped GEMM on bf16 MFMA:
+//
+//     C[m][g][n] = sum_k A[m][g][k] * W[g][n][k]              (absorbed query)
+//     C[m][n]    = sum_g sum_k A[m][g][k] * W[g][n][k]        (grouped output projection)
+//
+// m runs over the few query rows of a decode step (batch x q_len), so the
+// work is reading W once: the kernel is bound by HBM, and the weights are the
+// operand that streams.  Transposed form C^T = W . A^T: a wave owns 32 output
+// features (rows of W, the MFMA A operand) and all 32*MT query rows of its
+// workgroup (columns, the B operand).
+//
+// Both operands travel global -> LDS with direct-to-LDS loads of 16 bytes per
+// lane, one instruction moving eight rows of 128 bytes (64 input features): whole
+// cache lines per instruction, each line touched by exactly one instruction
+// (register-direct loads in MFMA operand order touch every line four times and
+// run at a quarter of the rate).  Every wave has its own ring of NST stages in
+// LDS (a stage = 64 input features of its 32 weight rows and of the 32*MT query
+// rows), so there is no workgroup barrier anywhere; NST - 1 stages stay in
+// flight.  The LDS side of such a load is linear in the lane, so each lane
+// fetches the 16-byte chunk whose swizzled home is its slot (chunk index XOR
+// row mod 8: the operand reads, 32 rows at one chunk index, spread over the
+// banks).  Operand reads are 16 bytes per lane: lane (r, h) takes chunks
+// 4h .. 4h + 3 of row r for the four MFMA steps of a stage; both operands use
+// the same assignment of input features to contraction slots.
+//
+// The input features of a group can be cut into KSPLIT ranges (and, for the
+// output projection, the groups themselves are ranges of one long sum): each
+// (group, range) is one grid.z slice that leaves an fp32 partial [m][n] in the
+// workspace, summed by proj_reduce_kernel.  Without a cut the result is
+// written directly.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "common.hpp"
+#include "tuned_device.hpp"
+
+namespace gla {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 proj_bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float proj_f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float proj_f32x4_t;
+
+struct ProjParams {
+  const uint16_t* a;
+  const uint16_t* w;
+  void* c;
+  float* part;             // [z][M][N] fp32 partials (z = g * ksplit + s), used when direct == 0
+  int64_t a_row, a_group;  // element strides of A
+  int64_t c_row, c_group;  // element strides of C
+  int32_t M, G, N, K;
+  int32_t ksplit, k_per_split;
+  int32_t sum_groups, c_fp32, direct;
+};
+
+template <int MT>
+__global__ __launch_bounds__(256) void proj_kernel(ProjParams p) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 31, h = lane >> 5;
+  const int n0 = blockIdx.x * 128 + wave * 32;
+  if (n0 >= p.N) return;  // (whole wave: N is a multiple of 32)
+  const int m0 = blockIdx.y * (32 * MT);
+  const int g = (int)blockIdx.z / p.ksplit, ks = (int)blockIdx.z % p.ksplit;
+  const int k_begin = ks * p.k_per_split;
+  const int k_end = min(p.K, k_begin + p.k_per_split);
+
+  constexpr int NST = MT == 1 ? 5 : 3;                 // ring stages per wave (40 KB of LDS per wave at most)
+  constexpr int kStage = (1 + MT) * 4096;              // bytes: 32 weight rows + 32*MT query rows of 128 bytes
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * NST * kStage];
+  static_assert(sizeof(smem) <= 160 * 1024, "LDS capacity");
+  unsigned char* const ring = smem + wave * (NST * kStage);
+  const unsigned ring_addr = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring;
+
+  // load side: lane l of instruction j moves row 8j + l / 8; its LDS slot l % 8 is home to chunk (l % 8) ^ (row % 8)
+  const int lr = lane >> 3, lc = (lane & 7) ^ (lane >> 3);
+  const unsigned char* wsrc[4];
+  const unsigned char* asrc[MT][4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    wsrc[j] = (const unsigned char*)(p.w + ((int64_t)g * p.N + n0 + 8 * j + lr) * p.K) + lc * 16;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = min(m0 + mt * 32 + 8 * j + lr, p.M - 1);  // rows past the end repeat the last one (never stored)
+      asrc[mt][j] = (const unsigned char*)(p.a + m * p.a_row + g * p.a_group) + lc * 16;
+    }
+  }
+  auto issue = [&](int k, int stage) {  // 4 + 4 * MT loads
+    unsigned char* dst = ring + stage * kStage;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(wsrc[j] + (int64_t)k * 2), (lds_void_t*)(dst + j * 1024), 16, 0, 0);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(asrc[mt][j] + (int64_t)k * 2), (lds_void_t*)(dst + (1 + mt) * 4096 + j * 1024), 16, 0, 0);
+  };
+  // operand side: row r, chunk 4h + s at slot (4h + s) ^ (r % 8)
+  unsigned rd[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) rd[s] = ring_addr + (unsigned)(r * 128 + (((4 * h + s) ^ (r & 7)) << 4));
+
+  proj_f32x16_t acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
+
+  constexpr int LPS = 4 + 4 * MT;  // loads per stage
+  static_assert(LPS * (NST - 1) <= 63, "vmcnt range");
+  const int k_last = k_end - 64;
+#pragma unroll
+  for (int st = 0; st < NST - 1; ++st) issue(min(k_begin + 64 * st, k_last), st);  // (steps past the end fetch the last one again)
+  for (int k = k_begin; k < k_end; k += 64 * NST) {
+    static_for<0, NST>([&](auto stc) {
+      constexpr int st = decltype(stc)::value;
+      if (k + 64 * st < k_end) {  // (uniform)
+        issue(min(k + 64 * (st + NST - 1), k_last), (st + NST - 1) % NST);
+        wait_vmcnt<LPS * (NST - 1)>();  // everything but the NST - 1 newest stages has landed: stage st is in LDS
+        u32x4_t wf[4], af[MT][4];
+        static_for<0, 4>([&](auto sc) {
+          constexpr int s = decltype(sc)::value;
+          lds_read_b128<st * kStage>(wf[s], rd[s]);
+          static_for<0, MT>([&](auto mc) { lds_read_b128<st * kStage + (1 + decltype(mc)::value) * 4096>(af[decltype(mc)::value][s], rd[s]); });
+        });
+        static_for<0, 4>([&](auto sc) {
+          constexpr int s = decltype(sc)::value;
+          constexpr int left = (3 - s) * (1 + MT);  // reads of later steps may still be in flight
+          lds_wait<left>(wf[s]);
+          static_for<0, MT>([&](auto mc) {
+            constexpr int mt = decltype(mc)::value;
+            asm volatile("" : "+v"(af[mt][s]));  // (covered by the wait above: LDS returns in order)
+            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(proj_bf16x8_t, wf[s]),
+                                                               __builtin_bit_cast(proj_bf16x8_t, af[mt][s]), acc[mt], 0, 0, 0);
+          });
+        });
+      }
+    });
+  }
+
+  wait_vmcnt<0>();  // (re-fetched steps past the end of the range: let them land before the wave leaves)
+  // accumulator element i of lane (r, h): output feature n0 + 8 * (i / 4) + 4 * h + i % 4, query row m0 + 32 * mt + r
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = m0 + mt * 32 + r;
+    if (m >= p.M) continue;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int n = n0 + 8 * q4 + 4 * h;
+      const proj_f32x4_t v = {acc[mt][4 * q4], acc[mt][4 * q4 + 1], acc[mt][4 * q4 + 2], acc[mt][4 * q4 + 3]};
+      if (!p.direct) {
+        *reinterpret_cast<proj_f32x4_t*>(p.part + ((int64_t)blockIdx.z * p.M + m) * p.N + n) = v;
+      } else {
+        const int64_t off = m * p.c_row + (p.sum_groups ? 0 : g * p.c_group) + n;
+        if (p.c_fp32) {
+          *reinterpret_cast<proj_f32x4_t*>((float*)p.c + off) = v;
+        } else {
+          uint2 pk;
+          pk.x = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
+          pk.y = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
+          *reinterpret_cast<uint2*>((uint16_t*)p.c + off) = pk;
+        }
+      }
+    }
+  }
+}
+
+// Sum of the partials of one output: over all grid.z slices (output projection)
+// or over the ksplit slices of each group (absorbed query).  One thread per four
+// consecutive output features, slices added in index order (deterministic).
+__global__ __launch_bounds__(256) void proj_reduce_kernel(ProjParams p) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int n4 = p.N / 4;
+  const int outs = p.sum_groups ? 1 : p.G;
+  if (idx >= (int64_t)p.M * outs * n4) return;
+  const int n = (int)(idx % n4) * 4;
+  const int g = (int)((idx / n4) % outs);
+  const int m = (int)(idx / ((int64_t)n4 * outs));
+  const int z0 = p.sum_groups ? 0 : g * p.ksplit, z1 = p.sum_groups ? p.G * p.ksplit : (g + 1) * p.ksplit;
+  proj_f32x4_t v = {0.f, 0.f, 0.f, 0.f};
+  for (int z = z0; z < z1; ++z) v += *reinterpret_cast<const proj_f32x4_t*>(p.part + ((int64_t)z * p.M + m) * p.N + n);
+  const int64_t off = m * p.c_row + (p.sum_groups ? 0 : g * p.c_group) + n;
+  if (p.c_fp32) {
+    *reinterpret_cast<proj_f32x4_t*>((float*)p.c + off) = v;
+  } else {
+    uint2 pk;
+    pk.x = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
+    pk.y = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
+    *reinterpret_cast<uint2*>((uint16_t*)p.c + off) = pk;
+  }
+}
+
+}  // namespace gla

@@ -1,0 +1,115 @@
+"""GPU parity of the two projections around the attention (absorbed query,
+grouped output projection) against the CPU oracle, and the whole absorbed block
+raw queries -> absorb -> decode -> output projection end to end."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_21487_amd as gla
+from paper_2505_21487_amd.harness import DeviceProblem
+from workloads import bf16_bits, make_problem, projection_weights
+
+pytestmark = pytest.mark.gpu
+
+
+def check_projection(c, ref, abs_prod, *, bf16_out, what):
+    """fp32 accumulation of exact bf16 products: the sum is off by at most
+    K * 2^-24 * sum_k |a_k w_k| (abs_prod), far below the bound used here,
+    2^-16 of that sum; a bf16 result adds half an ulp of the value."""
+    err = np.abs(c - ref)
+    bound = abs_prod * 2.0 ** -16 + 1e-30
+    if bf16_out:
+        bound = bound + np.where(ref != 0, 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 1e-300))) - 8), 0.0)
+    worst = (err - bound).max()
+    assert worst <= 0, f"{what}: max-abs {err.max():.3e} exceeds its bound by {worst:.3e}"
+    rel = np.linalg.norm((c - ref).ravel()) / max(np.linalg.norm(ref.ravel()), 1e-30)
+    assert rel <= (4e-3 if bf16_out else 1e-5), f"{what}: rel-L2 {rel:.3e}"
+
+
+@pytest.mark.parametrize("M,G,N,K", [(1, 3, 32, 64), (33, 5, 96, 192), (64, 128, 256, 128), (128, 16, 512, 128), (70, 1, 4096, 1024)])
+def test_absorb_query_against_oracle(M, G, N, K):
+    """(64, 128, 256, 128) is the benchmark workload's shape: 64 rows, 128 heads, d_c 256, d_h 128;
+    (70, 1, 4096, 1024): one merged weight from a hidden vector, input features cut into ranges."""
+    g = torch.Generator().manual_seed(700 + M)
+    a = torch.randn(M, G, K, generator=g).to(torch.bfloat16)
+    w = (torch.randn(G, N, K, generator=g) / K ** 0.5).to(torch.bfloat16)
+    ref = oracle.project(bf16_bits(a), bf16_bits(w), sum_groups=False)
+    abs_prod = np.einsum("mgk,gnk->mgn", np.abs(a.double().numpy()), np.abs(w.double().numpy()))
+    # strided input (queries as a slice of a wider buffer) and strided output
+    wide = torch.zeros(M, G, K + 64, dtype=torch.bfloat16, device="cuda")
+    wide[..., 32:32 + K] = a.cuda()
+    for dt in (torch.float32, torch.bfloat16):
+        out_wide = torch.zeros(M, G, N + 32, dtype=dt, device="cuda")
+        c = gla.gla_absorb_query(wide[..., 32:32 + K], w.cuda(), out=out_wide[..., :N])
+        torch.cuda.synchronize()
+        assert (out_wide[..., N:] == 0).all()
+        check_projection(c.double().cpu().numpy(), ref, abs_prod, bf16_out=dt == torch.bfloat16, what=f"absorb {M}x{G}x{N}x{K} {dt}")
+
+
+@pytest.mark.parametrize("M,G,N,K", [(1, 2, 64, 256), (64, 2, 5120, 16384), (37, 4, 160, 8192), (128, 1, 1024, 32768)])
+def test_output_proj_against_oracle(M, G, N, K):
+    """(64, 2, 5120, 16384): the benchmark workload's shape (two latent heads, 64 heads x 256 dims each, model dim 5120)."""
+    g = torch.Generator().manual_seed(800 + M)
+    a = (torch.randn(M, G, K, generator=g) * 0.05).to(torch.bfloat16)     # attention outputs are small
+    w = projection_weights(G, N, K, seed=801 + M)
+    ref = oracle.project(bf16_bits(a), bf16_bits(w), sum_groups=True)
+    abs_prod = np.einsum("mgk,gnk->mn", np.abs(a.double().numpy()), np.abs(w.double().numpy()))
+    ad, wd = a.cuda(), w.cuda()
+    for dt in (torch.float32, torch.bfloat16):
+        c = gla.gla_output_proj(ad, wd, out_dtype=dt)
+        c2 = gla.gla_output_proj(ad, wd, out_dtype=dt)
+        torch.cuda.synchronize()
+        assert torch.equal(c, c2), "partials are added in a fixed order: repeat calls must agree bit for bit"
+        check_projection(c.double().cpu().numpy(), ref, abs_prod, bf16_out=dt == torch.bfloat16, what=f"out-proj {M}x{G}x{N}x{K} {dt}")
+
+
+def test_projection_argument_checks():
+    a = torch.zeros(4, 2, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(gla.GlaError) as e:
+        gla.gla_absorb_query(a, torch.zeros(2, 30, 64, dtype=torch.bfloat16, device="cuda"))   # n % 32 != 0
+    assert e.value.status == gla.GLA_ERR_UNSUPPORTED_SHAPE
+    with pytest.raises(gla.GlaError) as e:
+        gla.gla_output_proj(a[..., :32].contiguous(), torch.zeros(2, 32, 32, dtype=torch.bfloat16, device="cuda"))  # k % 64 != 0
+    assert e.value.status == gla.GLA_ERR_UNSUPPORTED_SHAPE
+    with pytest.raises(gla.GlaError) as e:       # partials needed, workspace too small
+        gla.gla_output_proj(torch.zeros(4, 2, 1024, dtype=torch.bfloat16, device="cuda"),
+                            torch.zeros(2, 64, 1024, dtype=torch.bfloat16, device="cuda"),
+                            workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == gla.GLA_ERR_WORKSPACE_TOO_SMALL
+
+
+@pytest.mark.parametrize("T", [1, 2])
+def test_absorbed_block_end_to_end(T):
+    """Raw per-head queries -> gla_absorb_query -> gla_decode -> gla_output_proj
+    on the GPU against the same chain in the oracle, both sides rounding to bf16
+    where the kernels hand over (absorbed queries, latent outputs).  The block
+    output inherits the attention's tolerance: |dy_n| <= 5e-3 * sum_k |W_nk|
+    (every latent output off by at most 5e-3) and relative L2 1e-2."""
+    h_q, h_c, d_c, d_h, D = 128, 2, 256, 128, 1024
+    g_q = h_q // h_c
+    p = make_problem("block_e2e", seq_lens=[300, 1000, 64, 2000], T=T, h_q=h_q, h_c=h_c, d_v=d_c, seed=900 + T,
+                     num_pages=512, poison_tail=True)
+    M = p.B * T
+    g = torch.Generator().manual_seed(901 + T)
+    q_raw = torch.randn(M, h_q, d_h, generator=g).to(torch.bfloat16)
+    w_uk = projection_weights(h_q, d_c, d_h, seed=902, gain=h_q ** 0.5)       # absorbed queries of about unit scale
+    w_vo = projection_weights(h_c, D, g_q * d_c, seed=903)
+    # ---- oracle chain
+    q_abs = oracle.project(bf16_bits(q_raw), bf16_bits(w_uk), sum_groups=False)
+    p.q_nope = torch.from_numpy(q_abs.reshape(p.B, T, h_q, d_c)).to(torch.bfloat16)
+    o_ref, _ = oracle.decode_problem(p)
+    o_ref_bf = torch.from_numpy(o_ref).to(torch.bfloat16).reshape(M, h_c, g_q * d_c)
+    y_ref = oracle.project(bf16_bits(o_ref_bf), bf16_bits(w_vo), sum_groups=True)
+    # ---- GPU chain (the device problem's q_nope is replaced by the absorb kernel's output)
+    dp = DeviceProblem(p, poison_unused=True)
+    q_dev = gla.gla_absorb_query(q_raw.cuda(), w_uk.cuda())
+    dp.q_nope = q_dev.reshape(p.B, T, h_q, d_c)
+    out, _ = gla.gla_decode(*dp.args(), impl=gla.GLA_IMPL_TUNED)
+    y = gla.gla_output_proj(out.reshape(M, h_c, g_q * d_c), w_vo.cuda(), out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    y = y.double().cpu().numpy()
+    bound = 5e-3 * np.abs(w_vo.double().numpy()).sum(axis=(0, 2))[None, :]
+    assert (np.abs(y - y_ref) <= bound).all(), f"max-abs {np.abs(y - y_ref).max():.3e}"
+    rel = np.linalg.norm(y - y_ref) / np.linalg.norm(y_ref)
+    assert rel <= 1e-2, f"rel-L2 {rel:.3e}"

@@ -225,6 +225,20 @@ def config(index: int, *, T: Optional[int] = None, draw: int = 0, batch: Optiona
     raise ValueError(f"no config {index}")
 
 
+def projection_weights(groups: int, n: int, k: int, *, seed: int, gain: float = 1.0) -> torch.Tensor:
+    """Seeded random weights [groups][n][k] (output-major) for the projections
+    around the attention: bf16 draws from N(0, gain^2 / (groups * k)), so that a
+    sum over all groups and input features of unit-variance inputs has variance
+    gain^2.  Inputs only: no arithmetic of the method."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(int(seed))
+    w = torch.empty(groups, n, k, dtype=torch.bfloat16)
+    std = gain / math.sqrt(groups * k)
+    for i in range(groups):                      # one group at a time: bounded fp32 staging
+        w[i] = (torch.randn(n, k, generator=g) * std).to(torch.bfloat16)
+    return w
+
+
 def parse_lens(spec: str):
     """'1024x15,65536' -> [1024] * 15 + [65536]."""
     out = []
