@@ -50,6 +50,10 @@ def _load():
         lib.gla_oracle_merge.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
                                          ctypes.c_int64, ctypes.c_int, ctypes.c_void_p,
                                          ctypes.c_void_p]
+        lib.gla_oracle_gqa_decode.restype = ctypes.c_int
+        lib.gla_oracle_gqa_decode.argtypes = ([ctypes.c_void_p] * 5 + [ctypes.c_int] * 8 +
+                                              [ctypes.c_double, ctypes.c_int, ctypes.c_void_p, ctypes.c_int64,
+                                               ctypes.c_void_p, ctypes.c_void_p])
         lib.gla_oracle_project.restype = ctypes.c_int
         lib.gla_oracle_project.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                                            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -156,9 +160,44 @@ def project(a: np.ndarray, w: np.ndarray, *, sum_groups: bool) -> np.ndarray:
     return c
 
 
+def gqa_decode(q: np.ndarray, kcache: np.ndarray, vcache: np.ndarray, page_table: np.ndarray,
+               seq_lens: np.ndarray, *, scale: float, causal: int = 1,
+               sel: Optional[Sequence[Tuple[int, int, int]]] = None):
+    """Grouped-query decode with separate key / value caches: q [B,T,h_q,d_k],
+    kcache [n_pages,h_kv,P,d_k], vcache [n_pages,h_kv,P,d_v] (uint16 bf16 bits).
+    Returns (out fp64 [B,T,h_q,d_v] or [n_sel,d_v], lse)."""
+    lib = _load()
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    kcache = np.ascontiguousarray(kcache, dtype=np.uint16)
+    vcache = np.ascontiguousarray(vcache, dtype=np.uint16)
+    B, T, h_q, d_k = q.shape
+    _, h_kv, P, d_k2 = kcache.shape
+    d_v = vcache.shape[-1]
+    assert d_k2 == d_k and vcache.shape[:3] == kcache.shape[:3]
+    page_table = np.ascontiguousarray(page_table, dtype=np.int32)
+    seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    sel_arr = None
+    if sel is not None:
+        sel_arr = np.ascontiguousarray(np.asarray(sel, dtype=np.int32).reshape(-1, 3))
+        out = np.empty((sel_arr.shape[0], d_v), dtype=np.float64)
+        lse = np.empty((sel_arr.shape[0],), dtype=np.float64)
+    else:
+        out = np.empty((B, T, h_q, d_v), dtype=np.float64)
+        lse = np.empty((B, T, h_q), dtype=np.float64)
+    rc = lib.gla_oracle_gqa_decode(_ptr(q), _ptr(kcache), _ptr(vcache), _ptr(page_table), _ptr(seq_lens),
+                                   B, T, h_q, h_kv, d_k, d_v, P, page_table.shape[1], float(scale), int(causal),
+                                   _ptr(sel_arr), 0 if sel_arr is None else sel_arr.shape[0], _ptr(out), _ptr(lse))
+    if rc != 0:
+        raise ValueError("gla_oracle_gqa_decode: bad argument")
+    return out, lse
+
+
 def decode_problem(p, **kw):
     """Oracle on a `workloads.DecodeProblem` (compact pages + compact table)."""
     from workloads import bf16_bits
+    if p.kind == "gqa":
+        return gqa_decode(bf16_bits(p.q_nope), bf16_bits(p.key_pages), bf16_bits(p.state_pages), p.table_compact,
+                          p.seq_lens, scale=p.scale, causal=p.causal, **kw)
     return decode(bf16_bits(p.q_nope), bf16_bits(p.q_rope), bf16_bits(p.state_pages),
                   bf16_bits(p.rope_pages), p.table_compact, p.seq_lens, h_c=p.h_c,
                   scale=p.scale, causal=p.causal, **kw)

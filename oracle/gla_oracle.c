@@ -41,7 +41,9 @@
  * attention, with an assembled-K GQA for GTA, closed forms, paging invariance,
  * split/merge identity; for the projections: the whole absorbed block against
  * explicit per-head attention with separate W_UK, W_UV, W_O, numpy products,
- * identity weights.  No function here is unpinned.
+ * identity weights; for the grouped-query baseline: textbook attention on the
+ * gathered keys and values, and GTA as the special case whose key is assembled
+ * from the tied state and the shared RoPE key.  No function here is unpinned.
  */
 #include <math.h>
 #include <stdint.h>
@@ -252,4 +254,78 @@ int gla_oracle_project(const uint16_t* a, int64_t a_row_stride, int64_t a_group_
     if (sum_groups) c[(int64_t)m * N + n] = total;
   }
   return 0;
+}
+
+/*
+ * Grouped-query attention decode with keys and values in separate paged caches:
+ * the baseline Grouped-Tied Attention is measured against (Section 3.3.1: the
+ * tied state replaces the separate key and value of a GQA group, halving the
+ * cache).  Plain definition, two-pass, fp64:
+ *
+ *      s_j = scale * q . K[j],   p = softmax_j(s),   out = sum_j p_j V[j]
+ *
+ * for query head h with its group's key / value head g = h / (h_q / h_kv); the
+ * rotary embedding is already part of q and of the cached keys.  Visible keys
+ * and empty rows as in gla_oracle_decode.
+ *
+ *  q        [B, T, h_q, d_k]       bf16 bits
+ *  kcache   [n_pages, h_kv, P, d_k], vcache [n_pages, h_kv, P, d_v]   bf16 bits
+ *  sel / n_sel, out [rows, d_v], lse [rows] as in gla_oracle_decode
+ */
+int gla_oracle_gqa_decode(const uint16_t* q, const uint16_t* kcache, const uint16_t* vcache,
+                          const int32_t* page_table, const int32_t* seq_lens, int B, int T, int h_q,
+                          int h_kv, int d_k, int d_v, int P, int max_pages, double scale, int causal,
+                          const int32_t* sel, int64_t n_sel, double* out, double* lse) {
+  if (B < 0 || T < 1 || h_q < 1 || h_kv < 1 || h_q % h_kv != 0 || d_k < 1 || d_v < 1 || P < 1) return -1;
+  const int g_q = h_q / h_kv;
+  const int64_t rows = sel ? n_sel : (int64_t)B * T * h_q;
+  int64_t max_len = 0;
+  for (int b = 0; b < B; ++b)
+    if (seq_lens[b] > max_len) max_len = seq_lens[b];
+  int failed = 0;
+#pragma omp parallel
+  {
+    double* s = (double*)malloc(sizeof(double) * (size_t)(max_len > 0 ? max_len : 1));
+    if (!s) {
+#pragma omp atomic write
+      failed = 1;
+    }
+#pragma omp for schedule(dynamic, 1)
+    for (int64_t r = 0; r < rows; ++r) {
+      if (!s) continue;
+      const int b = sel ? sel[3 * r] : (int)(r / ((int64_t)T * h_q));
+      const int t = sel ? sel[3 * r + 1] : (int)((r / h_q) % T);
+      const int h = sel ? sel[3 * r + 2] : (int)(r % h_q);
+      const int g = h / g_q;
+      const int64_t L = seq_lens[b];
+      const int64_t n_vis = causal ? L - T + 1 + t : L;
+      double* o = out + r * d_v;
+      for (int d = 0; d < d_v; ++d) o[d] = 0.0;
+      if (n_vis <= 0) {
+        lse[r] = -INFINITY;
+        continue;
+      }
+      const uint16_t* qv = q + (((int64_t)b * T + t) * h_q + h) * d_k;
+      double m = -INFINITY;
+      for (int64_t j = 0; j < n_vis; ++j) {
+        const int64_t page = page_table[(int64_t)b * max_pages + j / P];
+        const uint16_t* k = kcache + ((page * h_kv + g) * P + j % P) * d_k;
+        double acc = 0.0;
+        for (int d = 0; d < d_k; ++d) acc += bf16_to_f64(qv[d]) * bf16_to_f64(k[d]);
+        s[j] = scale * acc;
+        if (s[j] > m) m = s[j];
+      }
+      double l = 0.0;
+      for (int64_t j = 0; j < n_vis; ++j) l += exp(s[j] - m);
+      lse[r] = m + log(l);
+      for (int64_t j = 0; j < n_vis; ++j) {
+        const double pj = exp(s[j] - m) / l;
+        const int64_t page = page_table[(int64_t)b * max_pages + j / P];
+        const uint16_t* v = vcache + ((page * h_kv + g) * P + j % P) * d_v;
+        for (int d = 0; d < d_v; ++d) o[d] += pj * bf16_to_f64(v[d]);
+      }
+    }
+    free(s);
+  }
+  return failed ? -1 : 0;
 }

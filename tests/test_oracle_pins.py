@@ -144,6 +144,42 @@ def test_projection_against_numpy_and_closed_forms():
     np.testing.assert_array_equal(got, want)
 
 
+def test_gqa_oracle_against_textbook_attention_and_as_generalisation_of_gta():
+    """The grouped-query baseline (separate key and value caches): (a) textbook
+    attention on the gathered keys / values of every row, causal rows included;
+    (b) Section 3.3.1 read the other way round: a GTA problem IS the GQA problem
+    whose key rows are [first half of the tied state | shared RoPE key] and whose
+    values are the tied state, so both oracle functions must agree on it."""
+    p = make_problem("gqa_pin", kind="gqa", seq_lens=[37, 5, 0, 16], T=2, h_q=8, h_c=2, d_v=16, page_size=8, seed=31,
+                     poison_tail=True)
+    out, lse = oracle.decode_problem(p)
+    g_q = p.h_q // p.h_c
+    for b in range(p.B):
+        L = int(p.seq_lens[b])
+        n = (L + p.page_size - 1) // p.page_size
+        idx = p.table_compact[b, :n]
+        K = f64(p.key_pages)[idx].transpose(1, 0, 2, 3).reshape(p.h_c, n * p.page_size, p.d_n)
+        V = f64(p.state_pages)[idx].transpose(1, 0, 2, 3).reshape(p.h_c, n * p.page_size, p.d_v)
+        for t in range(p.T):
+            n_vis = L - p.T + 1 + t
+            for h in range(p.h_q):
+                if n_vis <= 0:
+                    assert np.isneginf(lse[b, t, h]) and (out[b, t, h] == 0).all()
+                    continue
+                ref, _ = textbook_attention(f64(p.q_nope)[b, t, h], K[h // g_q][:n_vis], V[h // g_q][:n_vis], p.scale)
+                np.testing.assert_allclose(out[b, t, h], ref, rtol=0, atol=TOL)
+    # (b)
+    pg = make_problem("gta_as_gqa", kind="gta", seq_lens=[29, 8, 3], T=2, h_q=8, h_c=2, d_v=16, d_r=4, page_size=8, seed=32)
+    out_t, lse_t = oracle.decode_problem(pg)
+    st = pg.state_pages                                              # [n, h_c, P, d_h]
+    key = torch.cat([st[..., :pg.d_n], pg.rope_pages[:, None].expand(-1, pg.h_c, -1, -1)], dim=-1)
+    q = torch.cat([pg.q_nope, pg.q_rope], dim=-1)
+    out_q, lse_q = oracle.gqa_decode(bf16_bits(q), bf16_bits(key), bf16_bits(st), pg.table_compact, pg.seq_lens,
+                                     scale=pg.scale, causal=pg.causal)
+    np.testing.assert_allclose(out_q, out_t, rtol=0, atol=TOL)
+    np.testing.assert_allclose(lse_q, lse_t, rtol=0, atol=TOL)
+
+
 # ---------------------------------------------------------------- P2
 def test_softmax_weights_are_a_distribution():
     p = make_problem("p2", seq_lens=[19, 64, 1], T=2, h_q=4, h_c=2, d_v=8, d_r=4, page_size=16,

@@ -33,7 +33,7 @@ BASE_SEED = 250521487
 @dataclasses.dataclass
 class DecodeProblem:
     name: str
-    kind: str            # "gla" (d_n == d_v) or "gta" (d_n == d_v // 2)
+    kind: str            # "gla" (d_n == d_v), "gta" (d_n == d_v // 2) or "gqa" (separate key cache, d_r == 0)
     B: int
     T: int               # query length, 1..4
     h_q: int
@@ -54,6 +54,7 @@ class DecodeProblem:
     page_ids: np.ndarray          # int64 [n_used] physical slot of compact page i
     table_compact: np.ndarray     # int32 [B, max_pages] -> compact index, -1 unused
     table_pool: np.ndarray        # int32 [B, max_pages] -> physical slot, -1 unused
+    key_pages: Optional[torch.Tensor] = None   # kind "gqa" only: bf16 [n_used, h_c, page_size, d_n] (keys of their own)
 
     @property
     def g_q(self) -> int:
@@ -65,6 +66,8 @@ class DecodeProblem:
 
     @property
     def cache_bytes_per_token(self) -> int:
+        if self.kind == "gqa":
+            return 2 * self.h_c * (self.d_n + self.d_v)
         return 2 * (self.h_c * self.d_v + self.d_r)
 
 
@@ -108,8 +111,10 @@ def make_problem(
     random permutation of the pool drawn from `table_seed` (default: the value
     seed), so problems sharing a table_seed can occupy disjoint pages of one pool.
     """
-    assert kind in ("gla", "gta")
-    d_n = d_v if kind == "gla" else d_v // 2
+    assert kind in ("gla", "gta", "gqa")
+    d_n = d_v // 2 if kind == "gta" else d_v
+    if kind == "gqa":
+        d_r = 0          # the rotated dims are part of the cached key
     if scale is None:
         scale = 1.0 / math.sqrt(d_n + d_r)
     seq = np.asarray(seq_lens, dtype=np.int32)
@@ -127,6 +132,7 @@ def make_problem(
     q_rope = (torch.randn(B, T, h_q, d_r, generator=g) * q_gain).to(torch.bfloat16)
     state_pages = torch.randn(max(n_used, 1), h_c, page_size, d_v, generator=g).to(torch.bfloat16)
     rope_pages = torch.randn(max(n_used, 1), page_size, d_r, generator=g).to(torch.bfloat16)
+    key_pages = torch.randn(max(n_used, 1), h_c, page_size, d_n, generator=g).to(torch.bfloat16) if kind == "gqa" else None
 
     if identity_table:
         page_ids = np.arange(n_used, dtype=np.int64)
@@ -151,6 +157,8 @@ def make_problem(
             if used < page_size:
                 state_pages[cur + n - 1, :, used:, :] = float("nan")
                 rope_pages[cur + n - 1, used:, :] = float("nan")
+                if key_pages is not None:
+                    key_pages[cur + n - 1, :, used:, :] = float("nan")
         cur += n
 
     return DecodeProblem(
@@ -159,7 +167,7 @@ def make_problem(
         scale=float(scale), causal=int(causal), seq_lens=seq,
         q_nope=q_nope, q_rope=q_rope, state_pages=state_pages[:max(n_used, 1)],
         rope_pages=rope_pages[:max(n_used, 1)], page_ids=page_ids,
-        table_compact=table_compact, table_pool=table_pool,
+        table_compact=table_compact, table_pool=table_pool, key_pages=key_pages,
     )
 
 
