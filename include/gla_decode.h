@@ -28,9 +28,13 @@
  * beyond ceil(L_b / page_size) are never read (they may hold anything, -1
  * included); slots at or beyond L_b inside a page the table does hold may be
  * fetched but never reach a result, whatever they contain (NaN included).
- * The MFMA kernel runs for every power-of-two page_size from 64 down to 1
- * (paper Section 4.2 for the small ones); other page sizes take the generic
- * kernel.
+ * The main MFMA kernel runs for every power-of-two page_size from 64 down to 1
+ * (paper Section 4.2 for the small ones), state dims (d_v, d_nope) = (256, 256),
+ * (512, 512), (128, 64) and RoPE dims 64, 48 or 32.  A second, simpler MFMA
+ * kernel covers GTA states of 64 and 96 dims (RoPE key d_v / 2), latent heads of
+ * 128 dims with a RoPE key of 32, and gqa_decode, with pages of 32 tokens or
+ * more.  Everything else takes the generic kernel.  GLA_IMPL_TUNED means
+ * "one of the MFMA kernels".
  *
  * Ownership and execution.  Every pointer in the struct is a DEVICE pointer
  * owned by the caller unless stated otherwise; the library allocates no device
@@ -114,6 +118,22 @@ int gla_decode(const gla_decode_params* p);
 /* GTA decode (Section 3.3.1).  Requires d_nope == d_v / 2 (d_v even). */
 int gta_decode(const gla_decode_params* p);
 
+/* Grouped-query attention decode with keys and values in separate paged caches:
+ * the baseline that Grouped-Tied Attention is compared with (Section 3.3.1: the
+ * tied state stands in for a GQA group's key and value, about half the cache
+ * bytes per token).  Same parameter block with these readings: state_cache is
+ * the VALUE cache [num_pages, h_kv, page_size, d_v] (num_groups = h_kv);
+ * key_cache is bf16 [num_pages, h_kv, page_size, d_nope] with element strides
+ * key_stride (page, head, token), last dim contiguous; q_nope holds the whole
+ * query [B, T, h_q, d_nope] (rotary embedding already applied to it and to the
+ * cached keys); d_rope must be 0, q_rope and rope_cache are ignored.
+ *     s_j = softmax_scale * q . key[j],  out = softmax(s) . value
+ * Visible keys, empty rows, paging, workspace and errors as for gla_decode
+ * (workspace size: gla_decode_workspace_size(p, 2)).  An MFMA kernel runs for
+ * head dims (d_nope, d_v) = (128, 128) and (64, 64) with pages of 32 tokens or
+ * more; other shapes take the generic kernel. */
+int gqa_decode(const gla_decode_params* p, const void* key_cache, const int64_t key_stride[3]);
+
 /* For callers that cannot allocate device memory or obtain a workspace (code
  * under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc): the same operation as gla_decode (is_gta == 0) or gta_decode
@@ -132,7 +152,10 @@ int gta_decode(const gla_decode_params* p);
 int gla_decode_noalloc(const gla_decode_params* p, int is_gta);
 
 /* Bytes of workspace a call with these parameters needs (host only; pointer
- * fields are ignored).  Returns 0 for an invalid parameter set. */
+ * fields are ignored).  is_gta: 0 for gla_decode, 1 for gta_decode, 2 for
+ * gqa_decode (the helpers below take the same values; they have no passage of
+ * the paper to cite: they describe this library's own kernels).  Returns 0 for
+ * an invalid parameter set. */
 size_t gla_decode_workspace_size(const gla_decode_params* p, int is_gta);
 
 /* ---- the two projections around the attention -----------------------------------

@@ -7,8 +7,8 @@ from .binding import (GLA_DECODE_NOALLOC_SCRATCH_BYTES, GLA_ERR_INVALID_ARG, GLA
                       GLA_ERR_WORKSPACE_TOO_SMALL, GLA_IMPL_AUTO, GLA_IMPL_GENERIC,
                       GLA_IMPL_TUNED, GLA_OK, GlaDecodeParams, GlaError, GlaProjParams, gla_absorb_query, gla_decode,
                       gla_decode_check_contents, gla_decode_noalloc, gla_decode_profile, gla_decode_select_impl, gla_decode_version,
-                      gla_decode_workspace_size, gla_output_proj, gla_status_string, gta_decode, load_library,
+                      gla_decode_workspace_size, gla_output_proj, gla_status_string, gqa_decode, gqa_decode_prepared, gta_decode, load_library,
                       make_params, shape_params, decode_prepared)
 
-__all__ = [n for n in dir() if n.startswith(("gla_", "gta_", "GLA_", "Gla"))] + [
-    "load_library", "make_params", "shape_params", "decode_prepared"]
+__all__ = [n for n in dir() if n.startswith(("gla_", "gta_", "gqa_", "GLA_", "Gla"))] + [
+    "load_library", "make_params", "shape_params", "decode_prepared", "gqa_decode_prepared"]

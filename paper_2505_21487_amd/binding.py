@@ -25,7 +25,7 @@ GLA_IMPL_AUTO, GLA_IMPL_GENERIC, GLA_IMPL_TUNED = 0, 1, 2
 GLA_OUT_BF16, GLA_OUT_FP32 = 0, 1
 GLA_DECODE_NOALLOC_SCRATCH_BYTES = 72 << 20
 
-EXPORTS = ("gla_decode", "gta_decode", "gla_decode_noalloc", "gla_absorb_query", "gla_output_proj",
+EXPORTS = ("gla_decode", "gta_decode", "gqa_decode", "gla_decode_noalloc", "gla_absorb_query", "gla_output_proj",
            "gla_proj_workspace_size", "gla_decode_workspace_size", "gla_decode_select_impl",
            "gla_decode_profile", "gla_decode_check_contents", "gla_status_string", "gla_decode_version")
 
@@ -86,6 +86,8 @@ def load_library() -> ctypes.CDLL:
         lib.gla_decode.restype = ctypes.c_int
         lib.gta_decode.argtypes = [P]
         lib.gta_decode.restype = ctypes.c_int
+        lib.gqa_decode.argtypes = [P, ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64)]
+        lib.gqa_decode.restype = ctypes.c_int
         lib.gla_decode_noalloc.argtypes = [P, ctypes.c_int]
         lib.gla_decode_noalloc.restype = ctypes.c_int
         PP = ctypes.POINTER(GlaProjParams)
@@ -189,9 +191,9 @@ def make_params(q_nope: torch.Tensor, q_rope: Optional[torch.Tensor], state_cach
     return p
 
 
-def _decode(is_gta: bool, q_nope, q_rope, state_cache, rope_cache, page_table, seq_lens,
+def _decode(is_gta, q_nope, q_rope, state_cache, rope_cache, page_table, seq_lens,
             softmax_scale, *, causal=True, out=None, lse=None, workspace=None, num_splits=0,
-            impl=GLA_IMPL_AUTO, out_dtype=torch.bfloat16) -> Tuple[torch.Tensor, torch.Tensor]:
+            impl=GLA_IMPL_AUTO, out_dtype=torch.bfloat16, key_cache=None) -> Tuple[torch.Tensor, torch.Tensor]:
     lib = load_library()
     B, T, h_q, _ = q_nope.shape
     d_v = state_cache.shape[-1]
@@ -209,7 +211,12 @@ def _decode(is_gta: bool, q_nope, q_rope, state_cache, rope_cache, page_table, s
         p.workspace = workspace.data_ptr()
         p.workspace_bytes = workspace.numel()
     with torch.cuda.device(dev):
-        rc = (lib.gta_decode if is_gta else lib.gla_decode)(ctypes.byref(p))
+        if key_cache is not None:
+            assert key_cache.dtype == torch.bfloat16 and key_cache.stride(-1) == 1
+            ks = (ctypes.c_int64 * 3)(*_strides(key_cache, 3))
+            rc = lib.gqa_decode(ctypes.byref(p), key_cache.data_ptr(), ks)
+        else:
+            rc = (lib.gta_decode if is_gta else lib.gla_decode)(ctypes.byref(p))
     if rc != GLA_OK:
         raise GlaError(rc)
     return out, lse
@@ -227,6 +234,12 @@ def gta_decode(q_nope, q_rope, state_cache, rope_cache, page_table, seq_lens, so
     half, shared RoPE key]."""
     return _decode(True, q_nope, q_rope, state_cache, rope_cache, page_table, seq_lens,
                    softmax_scale, **kw)
+
+
+def gqa_decode(q, key_cache, value_cache, page_table, seq_lens, softmax_scale, **kw):
+    """Grouped-query decode baseline (separate key / value caches, Section 3.3.1's
+    comparison).  q [B,T,h_q,d_k]; returns (out [B,T,h_q,d_v], lse)."""
+    return _decode(2, q, None, value_cache, None, page_table, seq_lens, softmax_scale, key_cache=key_cache, **kw)
 
 
 def decode_prepared(p: GlaDecodeParams, is_gta: bool = False) -> None:
@@ -290,6 +303,14 @@ def gla_output_proj(o: torch.Tensor, w_vo: torch.Tensor, **kw) -> torch.Tensor:
     """Grouped output projection (Section 3.3.2): o [rows, h_c, g_q * d_c] latent
     outputs grouped by latent head, w_vo [h_c, D, g_q * d_c] -> [rows, D]."""
     return _proj(True, o, w_vo, **kw)
+
+
+def gqa_decode_prepared(p: GlaDecodeParams, key_cache: torch.Tensor) -> None:
+    """decode_prepared for the grouped-query entry point."""
+    ks = (ctypes.c_int64 * 3)(*_strides(key_cache, 3))
+    rc = load_library().gqa_decode(ctypes.byref(p), key_cache.data_ptr(), ks)
+    if rc != GLA_OK:
+        raise GlaError(rc)
 
 
 def gla_decode_check_contents(p: GlaDecodeParams, is_gta: bool = False) -> int:

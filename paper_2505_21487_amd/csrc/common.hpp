@@ -34,6 +34,7 @@ struct DevParams {
   const uint16_t* q_rope;
   const uint16_t* state;
   const uint16_t* rope;
+  const uint16_t* kstate;  // keys in a cache of their own (grouped-query baseline); null: key = first d_n dims of the state row
   const int32_t* page_table;
   const int32_t* seq_lens;
   void* out;
@@ -44,14 +45,16 @@ struct DevParams {
   int64_t qr_s[3];
   int64_t st_s[3];
   int64_t rp_s[2];
+  int64_t k_s[3];          // strides of kstate (page, head, token)
   int64_t out_s[3];
   int32_t B, T, h_q, h_c, g_q;
   int32_t d_v, d_n, d_r;
   int32_t P, max_pages;
   int32_t causal, out_fp32;
   float scale;
-  // generic kernel: uniform split of every sequence's page range
+  // generic kernel: uniform split of every sequence's page range (flex kernel: pages_per_split counts tiles of 32 tokens)
   int32_t splits, pages_per_split;
+  int32_t flex_rb;          // flex kernel: blocks of 16 query rows per group
   // tuned kernel: flat partition of all key tiles of the batch into chunks
   int32_t num_chunks;       // chunks of the tile list (the main kernel runs one workgroup per chunk and row block)
   int32_t chunk_tiles;      // > 0: fixed tiles per chunk; 0: ceil(total / num_chunks)

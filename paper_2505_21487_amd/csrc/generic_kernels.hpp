@@ -59,13 +59,15 @@ __global__ __launch_bounds__(64) void generic_main_kernel(DevParams p) {
     const int off = (int)(j % p.P);
     if (off == 0 || j == j0) page = p.page_table[(int64_t)b * p.max_pages + j / p.P];
     const uint16_t* c = p.state + page * p.st_s[0] + g * p.st_s[1] + off * p.st_s[2];
+    const uint16_t* kk = p.kstate ? p.kstate + page * p.k_s[0] + g * p.k_s[1] + off * p.k_s[2] : nullptr;
     float cv[NV];
     float acc = 0.f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int d = lane + 64 * i;
       cv[i] = (d < p.d_v) ? bf16_bits_to_f32(c[d]) : 0.f;
-      acc += qn[i] * cv[i];  // qn is zero beyond d_n
+      // key: the first d_n dims of the state row, or a row of the separate key cache (qn is zero beyond d_n)
+      acc += qn[i] * (kk ? ((d < p.d_n) ? bf16_bits_to_f32(kk[d]) : 0.f) : cv[i]);
     }
     if (p.d_r > 0) {
       const uint16_t* k = p.rope + page * p.rp_s[0] + off * p.rp_s[1];

@@ -10,6 +10,7 @@
 #include <mutex>
 
 #include "common.hpp"
+#include "flex_kernels.hpp"
 #include "generic_kernels.hpp"
 #include "proj_kernels.hpp"
 #include "tuned_kernels.hpp"
@@ -17,9 +18,17 @@
 namespace gla {
 namespace {
 
-constexpr int kVersion = 103;  // 1.03: gla_absorb_query, gla_output_proj
+constexpr int kVersion = 104;  // 1.04: gqa_decode; second MFMA kernel for small head shapes
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// `is_gta` arguments: 0 = GLA / MLA shape, 1 = GTA, kModeGqa = grouped-query baseline with its own key cache.
+constexpr int kModeGqa = 2;
+// The key cache of a gqa_decode call in flight (host-side hand-over from the entry point to the launch code).
+struct KeyCache {
+  const void* ptr;
+  int64_t stride[3];
+};
 
 int check_shape(const gla_decode_params* p, int is_gta) {
   if (!p) return GLA_ERR_INVALID_ARG;
@@ -27,7 +36,9 @@ int check_shape(const gla_decode_params* p, int is_gta) {
   if (p->num_q_heads < 1 || p->num_groups < 1 || p->num_q_heads % p->num_groups != 0)
     return GLA_ERR_INVALID_ARG;
   if (p->d_v < 1 || p->d_nope < 1 || p->d_rope < 0) return GLA_ERR_INVALID_ARG;
-  if (is_gta) {
+  if (is_gta == kModeGqa) {
+    if (p->d_rope != 0) return GLA_ERR_INVALID_ARG;  // (rotated dims are part of the cached key)
+  } else if (is_gta) {
     if (p->d_v % 2 != 0 || p->d_nope != p->d_v / 2) return GLA_ERR_INVALID_ARG;
   } else {
     if (p->d_nope != p->d_v) return GLA_ERR_INVALID_ARG;
@@ -41,7 +52,70 @@ int check_shape(const gla_decode_params* p, int is_gta) {
   return GLA_OK;
 }
 
-bool generic_supported(const gla_decode_params* p) { return p->d_v <= 1024 && p->d_rope <= 128; }
+bool generic_supported(const gla_decode_params* p) { return p->d_v <= 1024 && p->d_nope <= 1024 && p->d_rope <= 128; }
+
+// ---- flex kernel (flex_kernels.hpp): which instantiation, how many key ranges
+struct FlexPlan {
+  int id;       // index into the instantiation list below, -1: none
+  int rb;       // blocks of 16 rows per group
+  int splits, tiles_per_split;
+};
+
+int flex_variant(const gla_decode_params* p, int mode) {
+  if (mode == kModeGqa) {
+    if (p->d_nope == 128 && p->d_v == 128) return 0;
+    if (p->d_nope == 64 && p->d_v == 64) return 1;
+    return -1;
+  }
+  if (mode == 1) {  // GTA: tied state d_h, key = its first half + a RoPE key of d_h / 2
+    if (p->d_v == 64 && p->d_rope == 32) return 2;
+    if (p->d_v == 96 && p->d_rope == 48) return 3;
+    return -1;
+  }
+  if (p->d_v == 128 && p->d_rope == 32) return 4;  // latent heads of 2 x 64 dims
+  return -1;
+}
+
+bool flex_plan(const gla_decode_params* p, int mode, const KeyCache* kc, FlexPlan* plan) {
+  plan->id = flex_variant(p, mode);
+  if (plan->id < 0) return false;
+  const int ps = p->page_size;
+  if (ps < 32 || (ps & (ps - 1))) return false;  // a tile of 32 tokens lies inside one page
+  if (!(p->softmax_scale > 0.f)) return false;
+  // layout the kernel assumes: contiguous rows, 16-byte aligned rows and bases
+  if (p->state_stride[2] != p->d_v || p->state_stride[0] % 8 || p->state_stride[1] % 8) return false;
+  if (p->d_rope > 0 && (p->rope_stride[1] != p->d_rope || p->rope_stride[0] % 8)) return false;
+  for (int i = 0; i < 3; ++i)
+    if (p->q_nope_stride[i] % 4 || (p->d_rope > 0 && p->q_rope_stride[i] % 4) || p->out_stride[i] % 4) return false;
+  if (p->q_nope && (((uintptr_t)p->q_nope | (uintptr_t)p->q_rope) & 7u)) return false;
+  if (p->q_nope && (((uintptr_t)p->state_cache | (uintptr_t)p->rope_cache | (uintptr_t)p->out) & 15u)) return false;
+  if (mode == kModeGqa && kc && kc->ptr) {
+    if (kc->stride[2] != p->d_nope || kc->stride[0] % 8 || kc->stride[1] % 8 || ((uintptr_t)kc->ptr & 15u)) return false;
+  }
+  const int rows_group = (p->num_q_heads / p->num_groups) * p->q_len;
+  plan->rb = (rows_group + 15) / 16;
+  const int64_t units = (int64_t)p->batch * p->num_groups * plan->rb;
+  const int64_t max_tiles = std::max<int64_t>(1, ((int64_t)p->max_pages_per_seq * ps + 31) / 32);
+  int64_t sp;
+  if (p->num_splits > 0) {
+    sp = p->num_splits;
+  } else {
+    // about eight waves' worth of key ranges per compute unit, ranges of at least eight tiles
+    sp = (8 * (int64_t)device_cu_count() + units - 1) / std::max<int64_t>(units, 1);
+    sp = std::min<int64_t>(sp, std::max<int64_t>(1, max_tiles / 8));
+  }
+  sp = std::max<int64_t>(1, std::min<int64_t>(sp, std::min<int64_t>(max_tiles, 65535)));
+  plan->tiles_per_split = (int)((max_tiles + sp - 1) / sp);
+  plan->splits = (int)((max_tiles + plan->tiles_per_split - 1) / plan->tiles_per_split);
+  if (units * plan->splits > (int64_t)0x7fffffff * 4) return false;
+  return true;
+}
+
+size_t flex_workspace(const gla_decode_params* p, const FlexPlan& plan) {
+  if (plan.splits == 1) return 0;
+  const size_t rows = (size_t)p->batch * p->q_len * p->num_q_heads;
+  return align_up((size_t)plan.splits * rows * p->d_v * sizeof(float), 256) + align_up((size_t)plan.splits * rows * sizeof(float), 256);
+}
 
 int generic_splits(const gla_decode_params* p) {
   const int64_t rows = std::max<int64_t>(1, (int64_t)p->batch * p->q_len * p->num_q_heads);
@@ -51,13 +125,25 @@ int generic_splits(const gla_decode_params* p) {
   return (int)std::max<int64_t>(s, 1);
 }
 
-int select_impl(const gla_decode_params* p, int is_gta) {
+// Internal choice: GLA_IMPL_TUNED (the tuned kernel), kImplFlex (the second MFMA kernel, reported to
+// callers as GLA_IMPL_TUNED: "an MFMA kernel"), GLA_IMPL_GENERIC, or an error.
+constexpr int kImplFlex = 3;
+int select_kernel(const gla_decode_params* p, int is_gta, const KeyCache* kc) {
   int rc = check_shape(p, is_gta);
   if (rc != GLA_OK) return rc;
-  const bool tuned_ok = tuned_supported(p, is_gta);
-  if (p->impl == GLA_IMPL_TUNED) return tuned_ok ? GLA_IMPL_TUNED : GLA_ERR_UNSUPPORTED_SHAPE;
-  if (p->impl == GLA_IMPL_AUTO && tuned_ok) return GLA_IMPL_TUNED;
+  const bool tuned_ok = is_gta != kModeGqa && tuned_supported(p, is_gta);
+  FlexPlan fp;
+  const bool flex_ok = !tuned_ok && flex_plan(p, is_gta, kc, &fp);
+  if (p->impl != GLA_IMPL_GENERIC) {
+    if (tuned_ok) return GLA_IMPL_TUNED;
+    if (flex_ok) return kImplFlex;
+    if (p->impl == GLA_IMPL_TUNED) return GLA_ERR_UNSUPPORTED_SHAPE;
+  }
   return generic_supported(p) ? GLA_IMPL_GENERIC : GLA_ERR_UNSUPPORTED_SHAPE;
+}
+int select_impl(const gla_decode_params* p, int is_gta) {
+  const int k = select_kernel(p, is_gta, nullptr);
+  return k == kImplFlex ? GLA_IMPL_TUNED : k;
 }
 
 size_t generic_workspace(const gla_decode_params* p) {
@@ -73,6 +159,39 @@ int check_pointers(const gla_decode_params* p) {
   if (!p->q_nope || !p->state_cache || !p->page_table || !p->seq_lens || !p->out || !p->lse)
     return GLA_ERR_INVALID_ARG;
   if (p->d_rope > 0 && (!p->q_rope || !p->rope_cache)) return GLA_ERR_INVALID_ARG;
+  return GLA_OK;
+}
+
+int launch_flex(const gla_decode_params* p, const FlexPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
+  d.splits = plan.splits;
+  d.pages_per_split = plan.tiles_per_split;
+  d.flex_rb = plan.rb;
+  int lg = 0;
+  while ((1 << lg) < p->page_size) ++lg;
+  d.lg_page = lg;
+  const size_t rows = (size_t)p->batch * p->q_len * p->num_q_heads;
+  if (plan.splits > 1) {
+    d.ws_out = (float*)p->workspace;
+    d.ws_lse = (float*)((char*)p->workspace + align_up((size_t)plan.splits * rows * p->d_v * sizeof(float), 256));
+  }
+  const int64_t waves = (int64_t)p->batch * p->num_groups * plan.rb * plan.splits;
+  const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
+  if (ev) (void)hipEventRecord(ev[0], st);
+  switch (plan.id) {
+    case 0: hipLaunchKernelGGL((flex_main_kernel<128, 0, 128, true>), grid, block, 0, st, d); break;
+    case 1: hipLaunchKernelGGL((flex_main_kernel<64, 0, 64, true>), grid, block, 0, st, d); break;
+    case 2: hipLaunchKernelGGL((flex_main_kernel<32, 32, 64, false>), grid, block, 0, st, d); break;
+    case 3: hipLaunchKernelGGL((flex_main_kernel<48, 48, 96, false>), grid, block, 0, st, d); break;
+    case 4: hipLaunchKernelGGL((flex_main_kernel<128, 32, 128, false>), grid, block, 0, st, d); break;
+    default: return GLA_ERR_UNSUPPORTED_SHAPE;
+  }
+  if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
+  if (ev) (void)hipEventRecord(ev[1], st);
+  if (plan.splits > 1) {
+    hipLaunchKernelGGL(generic_combine_kernel, dim3((unsigned)rows), dim3(64), 0, st, d);
+    if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
+  }
+  if (ev) (void)hipEventRecord(ev[2], st);
   return GLA_OK;
 }
 
@@ -119,7 +238,7 @@ int launch_generic(const gla_decode_params* p, DevParams& d, hipStream_t st, hip
     d.ws_lse = (float*)((char*)p->workspace + align_up((size_t)s * rows * p->d_v * sizeof(float), 256));
   }
   dim3 grid((unsigned)rows, (unsigned)s), block(64);
-  const int nv = (p->d_v + 63) / 64;
+  const int nv = (std::max(p->d_v, p->d_nope) + 63) / 64;
   if (ev) (void)hipEventRecord(ev[0], st);
   if (nv <= 2) hipLaunchKernelGGL(generic_main_kernel<2>, grid, block, 0, st, d);
   else if (nv <= 4) hipLaunchKernelGGL(generic_main_kernel<4>, grid, block, 0, st, d);
@@ -135,19 +254,38 @@ int launch_generic(const gla_decode_params* p, DevParams& d, hipStream_t st, hip
   return GLA_OK;
 }
 
-int run(const gla_decode_params* p, int is_gta, hipEvent_t* ev) {
-  const int impl = select_impl(p, is_gta);
+size_t workspace_need(const gla_decode_params* p, int is_gta, int kernel, const KeyCache* kc) {
+  if (kernel == GLA_IMPL_TUNED) return tuned_workspace(p, is_gta);
+  if (kernel == kImplFlex) {
+    FlexPlan fp;
+    return flex_plan(p, is_gta, kc, &fp) ? flex_workspace(p, fp) : 0;
+  }
+  return generic_workspace(p);
+}
+
+int run(const gla_decode_params* p, int is_gta, hipEvent_t* ev, const KeyCache* kc = nullptr) {
+  const int impl = select_kernel(p, is_gta, kc);
   if (impl < 0) return impl;
   int rc = check_pointers(p);
   if (rc != GLA_OK) return rc;
+  if (is_gta == kModeGqa && p->batch > 0 && (!kc || !kc->ptr)) return GLA_ERR_INVALID_ARG;
   if (p->batch == 0) return GLA_OK;
-  const size_t need = impl == GLA_IMPL_TUNED ? tuned_workspace(p, is_gta) : generic_workspace(p);
+  const size_t need = workspace_need(p, is_gta, impl, kc);
   if (need > 0 && (!p->workspace || p->workspace_bytes < need)) return GLA_ERR_WORKSPACE_TOO_SMALL;
   if (need > 0 && ((uintptr_t)p->workspace & 255u)) return GLA_ERR_INVALID_ARG;
   DevParams d;
   fill_dev(p, &d);
+  if (is_gta == kModeGqa) {
+    d.kstate = (const uint16_t*)kc->ptr;
+    for (int i = 0; i < 3; ++i) d.k_s[i] = kc->stride[i];
+  }
   hipStream_t st = (hipStream_t)p->stream;
   if (impl == GLA_IMPL_TUNED) return tuned_launch(p, is_gta, d, st, ev);
+  if (impl == kImplFlex) {
+    FlexPlan fp;
+    if (!flex_plan(p, is_gta, kc, &fp)) return GLA_ERR_UNSUPPORTED_SHAPE;
+    return launch_flex(p, fp, d, st, ev);
+  }
   return launch_generic(p, d, st, ev);
 }
 
@@ -181,7 +319,7 @@ int scratch_of_current_device(void** out) {
 int run_noalloc(const gla_decode_params* p, int is_gta) {
   const int impl = select_impl(p, is_gta);
   if (impl < 0) return impl;
-  const size_t need = impl == GLA_IMPL_TUNED ? tuned_workspace(p, is_gta) : generic_workspace(p);
+  const size_t need = workspace_need(p, is_gta, select_kernel(p, is_gta, nullptr), nullptr);
   if (need > kScratchBytes) return GLA_ERR_WORKSPACE_TOO_SMALL;  // beyond the fixed buffer: use gla_decode / gta_decode
   gla_decode_params q = *p;
   void* ptr = nullptr;
@@ -345,11 +483,16 @@ int gta_decode(const gla_decode_params* p) { return gla::run(p, 1, nullptr); }
 int gla_decode_noalloc(const gla_decode_params* p, int is_gta) { return gla::run_noalloc(p, is_gta); }
 
 size_t gla_decode_workspace_size(const gla_decode_params* p, int is_gta) {
-  const int impl = gla::select_impl(p, is_gta);
+  const int impl = gla::select_kernel(p, is_gta, nullptr);
   if (impl < 0) return 0;
   // A little more than nothing, so callers can always pass a real buffer.
-  const size_t need = impl == GLA_IMPL_TUNED ? gla::tuned_workspace(p, is_gta) : gla::generic_workspace(p);
-  return std::max<size_t>(need, 256);
+  return std::max<size_t>(gla::workspace_need(p, is_gta, impl, nullptr), 256);
+}
+
+int gqa_decode(const gla_decode_params* p, const void* key_cache, const int64_t* key_stride) {
+  if (!key_stride) return GLA_ERR_INVALID_ARG;
+  const gla::KeyCache kc = {key_cache, {key_stride[0], key_stride[1], key_stride[2]}};
+  return gla::run(p, gla::kModeGqa, nullptr, &kc);
 }
 
 int gla_absorb_query(const gla_proj_params* p) { return gla::run_proj(p, 0); }

@@ -56,7 +56,8 @@ constexpr int tuned_stages(int dv, int ng, int wpg, int ks, bool lane = false) {
 
 inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) {
   const int ps = p->page_size;
-  if (ps < 1 || ps > 64 || (ps & (ps - 1)) || p->d_rope != 64) return false;  // 64, 32, ..., 1 tokens
+  if (ps < 1 || ps > 64 || (ps & (ps - 1))) return false;  // 64, 32, ..., 1 tokens
+  if (p->d_rope != 64 && p->d_rope != 48 && p->d_rope != 32) return false;  // (fewer than 64: padded inside the kernel)
   const bool lane = ps < 16;  // addresses per row and lane
   if (!(p->softmax_scale > 0.f)) return false;  // row maxima are taken on the raw dot products
   if (!((!is_gta && (p->d_v == 256 || p->d_v == 512)) || (is_gta && p->d_v == 128))) return false;

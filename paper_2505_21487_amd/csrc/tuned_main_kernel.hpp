@@ -176,7 +176,20 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   const unsigned s_lane_w =
       (unsigned)(s_rl * ROWB + ((s_pc & ~15) << 4) + (((s_pc & 15) ^ swz16(s_rl) ^ swz16(wpos * SLW * RPL)) << 4));
   const int r_rl = lane >> 3, r_pc = lane & 7;
-  const unsigned r_lane_w = (unsigned)(r_rl * 128 + ((r_pc ^ (r_rl >> 1) ^ (((wave * RLW) & 1) << 2)) << 4));
+  // RoPE keys of fewer than 64 dims (32 or 48): the LDS tile keeps its 128-byte
+  // rows and all four contraction steps; the query's RoPE fragments beyond the
+  // real dims are zero and the lanes whose LDS slot would hold a chunk the cache
+  // rows do not have fetch one of the row's real chunks a second time (finite
+  // data of a valid token times a zero query dim).  rrb: bytes of a RoPE row in
+  // the cache, cpg: its 16-byte chunks; r_voff[x]: this lane's byte offset inside
+  // a block of 8 cache rows for the two chunk keys a wave's loads alternate between.
+  const unsigned rrb = (unsigned)p.d_r * 2u, cpg = (unsigned)p.d_r >> 3;
+  unsigned r_voff[2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x) {
+    const unsigned ch = (unsigned)(r_pc ^ (r_rl >> 1) ^ (((wave * RLW) & 1) << 2)) ^ ((unsigned)x << 2);
+    r_voff[x] = (unsigned)r_rl * rrb + ((ch >= cpg ? ch - cpg : ch) << 4);  // (cpg >= 4)
+  }
   const uint32_t st_page_bytes = (uint32_t)p.st_s[0] * 2u, st_group_bytes = (uint32_t)p.st_s[1] * 2u;
   const uint32_t rp_page_bytes = (uint32_t)p.rp_s[0] * 2u;
   const unsigned char* const state_w = (const unsigned char*)p.state + gl * (uint64_t)st_group_bytes;
@@ -306,7 +319,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
 #pragma unroll
       for (int gi = 0; gi < NSGW; ++gi) dma_s[gi] = pre_sp + prep_tip * STB + (wpos * SLW + 4 * gi) * 1024;
 #pragma unroll
-      for (int ir = 0; ir < RLW; ++ir) dma_r[ir] = pre_rp + prep_tip * RTB + (wave * RLW + ir) * 1024;
+      for (int ir = 0; ir < RLW; ++ir) dma_r[ir] = pre_rp + (prep_tip * TOK + (wave * RLW + ir) * 8) * rrb;
     } else {
       // Smaller pages: one page lookup per load group.  Rows past the end of the
       // sequence may lie in a page the table does not hold: they are fetched from
@@ -326,7 +339,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
         const unsigned tok = tok0 + (unsigned)(wave * RLW + ir) * 8;
         const int pi = min((int)(tok >> lgP), last_page);
         const uint32_t page = (uint32_t)__builtin_amdgcn_readlane(pt_vec, pi - pt_base);
-        dma_r[ir] = rope_w + ((uint64_t)page * rp_page_bytes + (uint64_t)(tok & pmask) * 128);
+        dma_r[ir] = rope_w + ((uint64_t)page * rp_page_bytes + (uint64_t)(tok & pmask) * rrb);
       }
     }
     ++issued;
@@ -363,9 +376,8 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
         __builtin_amdgcn_global_load_lds((global_cvoid_t*)src, (lds_void_t*)(dma_ls + i * 1024), 16, 0, 0);
       } else {
         constexpr int ir = i - SLW;
-        const unsigned voff = r_lane_w ^ ((unsigned)(ir & 1) << 6);
         const unsigned rho = (unsigned)((wave * RLW + ir) * 8 + r_rl);
-        const unsigned off = (rho & dma_pmask) * 128 + (voff & 127);
+        const unsigned off = (rho & dma_pmask) * rrb + (r_voff[ir & 1] - (unsigned)r_rl * rrb);
         const unsigned char* src = rope_w + ((uint64_t)(uint32_t)pg_r[ir] * rp_page_bytes + off);
         __builtin_amdgcn_global_load_lds((global_cvoid_t*)src, (lds_void_t*)(dma_lr + ir * 1024), 16, 0, 0);
       }
@@ -375,8 +387,7 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
                                        (lds_void_t*)(dma_ls + (i / 4) * 4096), 16, (i % 4) * 1024, 0);
     } else {
       constexpr int ir = i - SLW;
-      const unsigned voff = r_lane_w ^ ((unsigned)(ir & 1) << 6);
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_r[ir] + voff),
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(dma_r[ir] + r_voff[ir & 1]),
                                        (lds_void_t*)(dma_lr + ir * 1024), 16, 0, 0);
     }
   };
@@ -404,7 +415,8 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
 #pragma unroll
     for (int ks = 0; ks < NKN; ++ks) load_b128_async(qn[ks], qn_ptr + 16 * ks);
 #pragma unroll
-    for (int ks = 0; ks < NKR; ++ks) load_b128_async(qr[ks], qr_ptr + 16 * ks);
+    for (int ks = 0; ks < NKR; ++ks)  // (dims the RoPE key does not have: the row's first dims again, zeroed after the wait)
+      load_b128_async(qr[ks], kx * DRW + 16 * ks < p.d_r ? qr_ptr + 16 * ks : qr_ptr - kx * DRW);
   };
 
   // ---- prologue: fill STAGES-1 stages
@@ -880,7 +892,11 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
 #pragma unroll
       for (int ks = 0; ks < NKN; ++ks) pin_acc(qn[ks]);
 #pragma unroll
-      for (int ks = 0; ks < NKR; ++ks) pin_acc(qr[ks]);
+      for (int ks = 0; ks < NKR; ++ks) {
+        pin_acc(qr[ks]);  // (first: a use of the loaded value that cannot move ahead of the wait)
+        if (kx * DRW + 16 * ks >= p.d_r) qr[ks] = u32x4_t{0, 0, 0, 0};  // RoPE keys of fewer than 64 dims
+        pin_acc(qr[ks]);
+      }
 #pragma unroll
       for (int db = 0; db < NDB; ++db) {
 #pragma unroll

@@ -18,8 +18,8 @@ def run_gpu(p, dp=None, **kw):
     is handed over filled with 0xFF bytes (NaN as floats, -1 as ints): a result
     that depends on anything the call did not write or was not given shows."""
     dp = dp or DeviceProblem(p, poison_unused=True)
-    is_gta = p.kind == "gta"
-    fn = gla.gta_decode if is_gta else gla.gla_decode
+    is_gta = {"gla": 0, "gta": 1, "gqa": 2}[p.kind]
+    fn = gla.gta_decode if is_gta == 1 else gla.gla_decode
     if "workspace" not in kw:
         out_dtype = kw.get("out_dtype", torch.bfloat16)
         o = torch.empty(p.B, p.T, p.h_q, p.d_v, dtype=out_dtype, device="cuda")
@@ -29,7 +29,11 @@ def run_gpu(p, dp=None, **kw):
                               impl=kw.get("impl", gla.GLA_IMPL_AUTO))
         need = gla.gla_decode_workspace_size(prm, is_gta)
         kw = dict(kw, workspace=torch.full((max(need, 256),), 0xFF, dtype=torch.uint8, device="cuda"))
-    out, lse = fn(*dp.args(), causal=bool(p.causal), **kw)
+    if is_gta == 2:
+        out, lse = gla.gqa_decode(dp.q_nope, dp.key_cache, dp.state_cache, dp.page_table, dp.seq_lens, p.scale,
+                                  causal=bool(p.causal), **kw)
+    else:
+        out, lse = fn(*dp.args(), causal=bool(p.causal), **kw)
     torch.cuda.synchronize()
     return out.to(torch.float64).cpu().numpy(), lse.to(torch.float64).cpu().numpy()
 

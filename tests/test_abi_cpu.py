@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def header_functions():
     text = open(os.path.join(ROOT, "include", "gla_decode.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(g[lt]a_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(g[lqt]a_[a-z_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():

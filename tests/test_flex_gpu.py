@@ -1,0 +1,100 @@
+"""GPU parity of the head shapes served by the second MFMA kernel: small tied
+states (GTA with d_h 64 / 96, RoPE key d_h / 2), latent heads of 128 dims, and
+the grouped-query baseline with separate key / value caches, against the CPU
+oracle.  impl = TUNED must find an MFMA kernel for every one of them."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_21487_amd as gla
+from paper_2505_21487_amd.harness import DeviceProblem
+from workloads import make_problem, uniform_lengths
+
+from gpu_util import check_problem
+
+pytestmark = pytest.mark.gpu
+
+GENERIC, TUNED = gla.GLA_IMPL_GENERIC, gla.GLA_IMPL_TUNED
+LENS = [0, 1, 31, 32, 33, 63, 64, 65, 130, 700, 1500, 2600]
+
+SHAPES = {
+    "gta64": dict(kind="gta", h_q=32, h_c=4, d_v=64, d_r=32),
+    "gta96": dict(kind="gta", h_q=24, h_c=4, d_v=96, d_r=48),
+    "gla128": dict(kind="gla", h_q=32, h_c=2, d_v=128, d_r=32),
+    "gqa128": dict(kind="gqa", h_q=32, h_c=4, d_v=128),
+    "gqa64": dict(kind="gqa", h_q=16, h_c=8, d_v=64),
+}
+
+
+def mfma_kernel_selected(p):
+    prm = gla.shape_params(batch=p.B, q_len=p.T, num_q_heads=p.h_q, num_groups=p.h_c, d_v=p.d_v, d_nope=p.d_n,
+                           d_rope=p.d_r, page_size=p.page_size, max_pages_per_seq=p.max_pages, num_pages=p.num_pages,
+                           impl=TUNED)
+    prm.softmax_scale = p.scale
+    prm.state_stride = (p.h_c * p.page_size * p.d_v, p.page_size * p.d_v, p.d_v)
+    prm.rope_stride = (p.page_size * p.d_r, p.d_r)
+    return gla.gla_decode_select_impl(prm, {"gla": 0, "gta": 1, "gqa": 2}[p.kind]) == TUNED
+
+
+@pytest.mark.parametrize("T", [1, 2, 4])
+@pytest.mark.parametrize("page_size", [64, 32])
+@pytest.mark.parametrize("shape", list(SHAPES))
+def test_small_head_shapes(shape, page_size, T):
+    p = make_problem(f"flex_{shape}", seq_lens=LENS, T=T, page_size=page_size, num_pages=4096, seed=1100 + 7 * T + page_size,
+                     poison_tail=True, extra_table_cols=1, **SHAPES[shape])
+    assert mfma_kernel_selected(p)
+    for impl in (TUNED, GENERIC):
+        check_problem(p, impl=impl, what=f"{shape} page {page_size} T={T} impl={impl}")
+
+
+@pytest.mark.parametrize("splits", [1, 3, 50])
+@pytest.mark.parametrize("shape", list(SHAPES))
+def test_key_ranges_do_not_change_the_result(shape, splits):
+    p = make_problem(f"flex_sp_{shape}", seq_lens=[1000, 129, 64, 5, 3000], T=2, num_pages=2048, seed=1200 + splits,
+                     poison_tail=True, **SHAPES[shape])
+    check_problem(p, impl=TUNED, num_splits=splits, what=f"{shape} splits={splits}")
+
+
+@pytest.mark.parametrize("shape", list(SHAPES))
+def test_few_keys_and_peaky_rows(shape):
+    """Short sequences with every key visible and strongly scaled queries: the
+    weights go into the value product with 16 significant bits."""
+    for seed, lens, gain in ((711, [2] * 30 + [3] * 10 + [1, 4, 5], 1.0), (1301, [900, 77, 2000], 8.0)):
+        p = make_problem(f"flex_pk_{shape}", seq_lens=lens, T=2, num_pages=512, seed=seed, causal=0, q_gain=gain,
+                         poison_tail=True, **SHAPES[shape])
+        check_problem(p, impl=TUNED, what=f"{shape} seed {seed}")
+
+
+@pytest.mark.parametrize("shape", ["gta64", "gqa128"])
+def test_large_ragged_batch_on_sampled_rows(shape):
+    """A ragged batch of the size class of the benchmark's GTA configuration
+    (64 sequences of 1000 to 12000 tokens), the automatic choice of key ranges."""
+    lens = uniform_lengths(64, 1000, 12000, 77)
+    p = make_problem(f"flex_big_{shape}", seq_lens=lens, T=1, num_pages=16384, seed=1400, poison_tail=True, **SHAPES[shape])
+    rng = np.random.default_rng(5)
+    sel = sorted({(int(rng.integers(p.B)), 0, int(rng.integers(p.h_q))) for _ in range(300)})
+    check_problem(p, sel=sel, impl=TUNED, what=f"{shape} large batch")
+
+
+def test_gqa_strided_caches_and_argument_checks():
+    p = make_problem("gqa_strided", kind="gqa", seq_lens=[300, 0, 77, 1200], T=2, h_q=32, h_c=4, d_v=128, seed=1500,
+                     num_pages=256, poison_tail=True)
+    dp = DeviceProblem(p, poison_unused=True)
+    ref_out, ref_lse = oracle.decode_problem(p)
+    # keys and values as slices of pools with one more head per page
+    kpool = torch.full((p.num_pages, p.h_c + 1, p.page_size, p.d_n), float("nan"), dtype=torch.bfloat16, device="cuda")
+    kpool[:, :p.h_c] = dp.key_cache
+    vpool = torch.full((p.num_pages, p.h_c + 1, p.page_size, p.d_v), float("nan"), dtype=torch.bfloat16, device="cuda")
+    vpool[:, 1:] = dp.state_cache
+    out, lse = gla.gqa_decode(dp.q_nope, kpool[:, :p.h_c], vpool[:, 1:], dp.page_table, dp.seq_lens, p.scale,
+                              impl=TUNED, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    from gpu_util import compare
+    compare(out.double().cpu().numpy(), lse.double().cpu().numpy(), ref_out, ref_lse, what="gqa strided", bf16_out_allowance=False)
+    # a RoPE dim is not part of this entry point
+    bad = torch.zeros(p.B, p.T, p.h_q, 64, dtype=torch.bfloat16, device="cuda")
+    prm = gla.make_params(dp.q_nope, bad, dp.state_cache, torch.zeros(p.num_pages, p.page_size, 64, dtype=torch.bfloat16, device="cuda"),
+                          dp.page_table, dp.seq_lens, p.scale, out=torch.empty(p.B, p.T, p.h_q, p.d_v, dtype=torch.bfloat16, device="cuda"),
+                          lse=torch.empty(p.B, p.T, p.h_q, dtype=torch.float32, device="cuda"), workspace=None)
+    assert gla.gla_decode_select_impl(prm, 2) == gla.GLA_ERR_INVALID_ARG

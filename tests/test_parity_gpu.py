@@ -37,7 +37,7 @@ TUNED_SHAPES = {("gla", 256), ("gla", 512), ("gta", 128)}   # (kind, d_v) with a
 def impls_for(p):
     ok = tuned_available(p)
     # a shape that has a tuned kernel must really take it: no silent generic-only pass
-    if (p.kind, p.d_v) in TUNED_SHAPES and p.d_r == 64 and p.page_size in (1, 2, 4, 8, 16, 32, 64):
+    if (p.kind, p.d_v) in TUNED_SHAPES and p.d_r in (32, 48, 64) and p.page_size in (1, 2, 4, 8, 16, 32, 64):
         assert ok, "tuned kernel unexpectedly unavailable"
     return [GENERIC, TUNED] if ok else [GENERIC]
 
@@ -145,6 +145,32 @@ def test_tiny_pages(shape, page_size):
     for impl in impls_for(p):
         for splits in ((0, 1) if impl == TUNED else (0,)):
             check_problem(p, impl=impl, num_splits=splits, what=f"{shape} page {page_size} impl={impl} splits={splits}")
+
+
+@pytest.mark.parametrize("d_r", [32, 48])
+@pytest.mark.parametrize("shape", ["gla2", "gla2_T3_page16", "gla2_page1", "mla", "gta", "gla1_few"])
+def test_rope_dims_32_and_48(shape, d_r):
+    """RoPE keys of 32 and 48 dims (the paper's smaller models) on the MFMA
+    kernel: cache rows of 64 / 96 bytes, queries and LDS tiles padded inside."""
+    lens = [0, 1, 31, 33, 64, 65, 130, 700, 1500, 2600]
+    kw = dict(seq_lens=lens, d_r=d_r, num_pages=4096, poison_tail=True, extra_table_cols=1)
+    if shape == "gla2":
+        p = make_problem("r_gla2", T=1, h_q=128, h_c=2, d_v=256, seed=600 + d_r, **kw)
+    elif shape == "gla2_T3_page16":
+        p = make_problem("r_gla2_T3", T=3, h_q=128, h_c=2, d_v=256, page_size=16, seed=610 + d_r, **kw)
+    elif shape == "gla2_page1":
+        kw["num_pages"] = 16384
+        p = make_problem("r_gla2_p1", T=2, h_q=64, h_c=2, d_v=256, page_size=1, seed=620 + d_r, **kw)
+    elif shape == "mla":
+        p = make_problem("r_mla", T=1, h_q=128, h_c=1, d_v=512, seed=630 + d_r, **kw)
+    elif shape == "gta":
+        p = make_problem("r_gta", kind="gta", T=2, h_q=32, h_c=4, d_v=128, seed=640 + d_r, **kw)
+    else:
+        p = make_problem("r_gla1", T=1, h_q=16, h_c=1, d_v=256, seed=650 + d_r, **kw)
+    impls = impls_for(p)
+    assert TUNED in impls
+    for impl in impls:
+        check_problem(p, impl=impl, what=f"{shape} d_r={d_r} impl={impl}")
 
 
 def test_peaky_softmax_fp32_and_bf16_out():

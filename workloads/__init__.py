@@ -230,6 +230,24 @@ def config(index: int, *, T: Optional[int] = None, draw: int = 0, batch: Optiona
         lens = uniform_lengths(batch or 64, min(4096, hi), hi, seed + 7)
         return make_problem("gla2_ragged_b64", seq_lens=lens, T=T or 1, h_q=128, h_c=2, d_v=256,
                             num_pages=pool, seed=seed, **tbl)
+    if index in (6, 7, 8):
+        # not among the five stated configurations: the lengths of configuration 4 (GTA-4, d_h 128) on the
+        # head shapes of the smaller models and on the grouped-query baseline GTA is compared with
+        hi = max_len or 32768
+        lens = uniform_lengths(batch or 128, min(4096, hi), hi, BASE_SEED + 4 + 1000 * draw + 7)
+        if index == 6:   # GTA-4 with d_h 64 (RoPE key 32)
+            return make_problem("gta4_dh64_b128", kind="gta", seq_lens=lens, T=T or 1, h_q=32, h_c=4, d_v=64, d_r=32,
+                                num_pages=pool, seed=seed, **tbl)
+        if index == 7:   # GQA-4 with d_h 128: separate key and value caches
+            return make_problem("gqa4_dh128_b128", kind="gqa", seq_lens=lens, T=T or 1, h_q=32, h_c=4, d_v=128,
+                                num_pages=pool, seed=seed, **tbl)
+        return make_problem("gta4_dh96_b128", kind="gta", seq_lens=lens, T=T or 1, h_q=24, h_c=4, d_v=96, d_r=48,
+                            num_pages=pool, seed=seed, **tbl)
+    if index == 9:
+        # configuration 1 with a RoPE key of 32 dims
+        L = min(8192, max_len or 8192)
+        return make_problem("gla2_b64_l8192_rope32", seq_lens=[L] * (batch or 64), T=T or 1, h_q=128, h_c=2, d_v=256,
+                            d_r=32, num_pages=pool, seed=seed, **tbl)
     raise ValueError(f"no config {index}")
 
 
