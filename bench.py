@@ -18,9 +18,14 @@ HBM traffic of the main kernel cannot be read from inside the process: it comes
 from two separate counter runs of this same script,
 
     rocprofv3 --pmc FETCH_SIZE -d <dirF> -o f --output-format csv -- \
-        python3 bench.py --steps 2 --warmup 1 --profile-iters 1 --no-cpu-baseline --calibration-copy
+        python3 bench.py --steps 2 --warmup 1 --preheat-ms 0 --settled-steps 0 --profile-iters 1 --model-dim 0 \
+            --no-cpu-baseline --calibration-copy --note-workload <dirF>
     rocprofv3 --pmc WRITE_SIZE -d <dirW> -o w --output-format csv -- (same command)
     python bench.py --summarise-pmc <dirF> <dirW>      # no GPU needed
+
+Kernel traces and SQ counter runs of this script (`rocprofv3 --kernel-trace --stats -d <dir> ... -- python3
+bench.py ... > <dir>/bench.log`, `rocprofv3 --pmc <counters> -d <dir> ...`) are turned into the text
+summaries kept under profiles/ by `python bench.py --summarise-trace <dir>` / `--summarise-sq <dir>`.
 
 The last step scales each counter by what it reads for a plain 1 GiB device
 copy made in the same run (--calibration-copy), prints a summary and stores
@@ -154,7 +159,7 @@ def summarise_pmc(fetch_dir: str, write_dir: str) -> int:
     for counter, d in (("FETCH_SIZE", fetch_dir), ("WRITE_SIZE", write_dir)):
         per = _per_dispatch(d, counter)
         copies = [max(v) for k, v in per.items() if "copyBuffer" in k or "copy_kernel" in k]
-        mains = [v for k, v in per.items() if "tuned_main_kernel" in k]
+        mains = [v for k, v in per.items() if "main_kernel" in k and "generic" not in k]
         if not copies or not mains:
             print(f"{counter}: no calibration copy or no main-kernel dispatch found in {d}", file=sys.stderr)
             return 1
@@ -189,9 +194,102 @@ def summarise_pmc(fetch_dir: str, write_dir: str) -> int:
     return 0
 
 
+def _bench_line(run_dir: str):
+    """The JSON line bench.py printed in a profiled run (kept next to the profiler's output as bench.log)."""
+    try:
+        for line in open(os.path.join(run_dir, "bench.log")):
+            if line.startswith("{"):
+                return json.loads(line)
+    except OSError:
+        pass
+    return None
+
+
+def summarise_trace(run_dir: str) -> int:
+    """Text summary of a `rocprofv3 --kernel-trace --stats` run of this script: per-kernel
+    call counts and durations of the library's kernels, the settled part of the trace (the
+    last third of the launches) apart from the whole, and the roofline figures from them."""
+    import csv
+    import glob
+    import statistics
+    traces = glob.glob(os.path.join(run_dir, "**", "*kernel_trace.csv"), recursive=True)
+    if not traces:
+        print(f"no kernel trace under {run_dir}", file=sys.stderr)
+        return 1
+    per = {}
+    for r in csv.DictReader(open(traces[0])):
+        if "gla::" in r["Kernel_Name"]:
+            per.setdefault(r["Kernel_Name"], []).append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+    rec = _bench_line(run_dir)
+    if rec:
+        print(f"workload: {rec['config']['workload']}")
+        print(f"bench.py line of the same run: value {rec['value']:.1f} us/call (settled {rec['settled_us']:.1f}, first calls "
+              f"{rec['first_calls_us']:.1f}); main kernel {rec['roofline']['kernel_us']:.1f} us and merge kernel "
+              f"{rec['roofline']['combine_us']:.1f} us by HIP events (taken under the tracer)")
+    print(f"{'kernel':<84}{'calls':>6}{'avg_us':>9}{'min_us':>9}{'max_us':>9}{'settled avg':>13}{'settled med':>13}")
+    main_settled = None
+    for k, v in sorted(per.items(), key=lambda kv: -sum(kv[1])):
+        tail = v[len(v) * 2 // 3:]
+        print(f"{k[:83]:<84}{len(v):>6}{sum(v) / len(v):>9.2f}{min(v):>9.2f}{max(v):>9.2f}{sum(tail) / len(tail):>13.2f}"
+              f"{statistics.median(tail):>13.2f}")
+        if main_settled is None and ("main_kernel" in k):
+            main_settled = (sum(v) / len(v), sum(tail) / len(tail), min(v))
+    if rec and main_settled:
+        b, fl = rec["cache_bytes"], rec["tflops"] * rec["value"] * 1e6
+        for name, us in (("average over all launches", main_settled[0]), ("settled launches (last third)", main_settled[1]),
+                         ("fastest launch", main_settled[2])):
+            print(f"main kernel, {name}: {us:.2f} us -> {b / us / 1e3:.0f} GB/s of algorithmic cache bytes "
+                  f"({b / us / 1e3 / HBM_PEAK_GBPS:.3f} of {HBM_PEAK_GBPS:.0f}), {fl / us / 1e6:.0f} TFLOP/s "
+                  f"({fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS:.3f} of {MFMA_BF16_PEAK_TFLOPS:.0f})")
+    return 0
+
+
+def summarise_sq(run_dir: str) -> int:
+    """Counters of one `rocprofv3 --pmc ...` run of this script, summed over the shader
+    engines, for the last launch of each library kernel, with the usual ratios."""
+    import csv
+    import glob
+    files = glob.glob(os.path.join(run_dir, "**", "*counter_collection.csv"), recursive=True)
+    if not files:
+        print(f"no counter file under {run_dir}", file=sys.stderr)
+        return 1
+    agg = {}
+    for r in csv.DictReader(open(files[0])):
+        if "gla::" in r["Kernel_Name"]:
+            d = agg.setdefault(r["Kernel_Name"], {}).setdefault(int(r["Dispatch_Id"]), {})
+            d[r["Counter_Name"]] = d.get(r["Counter_Name"], 0.0) + float(r["Counter_Value"])
+    rec = _bench_line(run_dir)
+    if rec:
+        print(f"workload: {rec['config']['workload']}")
+    for k, disp in agg.items():
+        v = disp[max(disp)]
+        print(k[:110])
+        print("   " + "  ".join(f"{n}={int(x)}" for n, x in sorted(v.items())))
+        g = v.get
+        ratios = []
+        if g("SQ_BUSY_CU_CYCLES"):
+            if g("SQ_VALU_MFMA_BUSY_CYCLES") is not None:
+                ratios.append(f"MFMA busy = MFMA_BUSY / (4 BUSY_CU) = {g('SQ_VALU_MFMA_BUSY_CYCLES') / (4 * g('SQ_BUSY_CU_CYCLES')):.3f}")
+            if g("SQ_LDS_IDX_ACTIVE") is not None:
+                ratios.append(f"LDS_IDX_ACTIVE / BUSY_CU = {g('SQ_LDS_IDX_ACTIVE') / g('SQ_BUSY_CU_CYCLES'):.3f}")
+            if g("SQ_LDS_BANK_CONFLICT") is not None and g("SQ_LDS_IDX_ACTIVE"):
+                ratios.append(f"bank conflict cycles / LDS active = {g('SQ_LDS_BANK_CONFLICT') / g('SQ_LDS_IDX_ACTIVE'):.4f}")
+        if g("SQ_WAVE_CYCLES"):
+            for n in ("SQ_WAIT_INST_ANY", "SQ_WAIT_INST_LDS", "SQ_ACTIVE_INST_LDS", "SQ_ACTIVE_INST_VALU", "SQ_ACTIVE_INST_ANY"):
+                if g(n) is not None:
+                    ratios.append(f"{n[3:]} / WAVE_CYCLES = {g(n) / g('SQ_WAVE_CYCLES'):.3f}")
+        if ratios:
+            print("   " + "; ".join(ratios))
+    return 0
+
+
 def main() -> int:
     if len(sys.argv) >= 4 and sys.argv[1] == "--summarise-pmc":
         return summarise_pmc(sys.argv[2], sys.argv[3])
+    if len(sys.argv) >= 3 and sys.argv[1] == "--summarise-trace":
+        return summarise_trace(sys.argv[2])
+    if len(sys.argv) >= 3 and sys.argv[1] == "--summarise-sq":
+        return summarise_sq(sys.argv[2])
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
@@ -200,6 +298,8 @@ def main() -> int:
                     help="milliseconds of untimed back-to-back calls BEFORE --warmup: the first ~15 ms of load on a cold "
                          "GPU run 10-35 %% slower (clock transient, see the first_calls figures of the output line); "
                          "0 switches the pre-heat off")
+    ap.add_argument("--settled-steps", type=int, default=1000,
+                    help="calls of the extra long timed stretch after the timed region (0: skip; counter runs)")
     ap.add_argument("--config", type=int, default=1, help="index into the configuration list")
     ap.add_argument("--q-len", type=int, default=0, help="override query length (1..4)")
     ap.add_argument("--lens", default="", help="instead of --config: sequence lengths, e.g. 131072 or "
@@ -295,8 +395,8 @@ def main() -> int:
         one_call(i)
     us_per_call = timed(args.steps)
     # (4) the same once more over a long stretch (a short K is noisy)
-    settled_n = max(args.steps, 1000)
-    settled_us = timed(settled_n)
+    settled_n = max(args.steps, args.settled_steps) if args.settled_steps > 0 else 0
+    settled_us = timed(settled_n) if settled_n > 0 else us_per_call
 
     # per-kernel durations from HIP events recorded by the library on its launch stream
     main_us = comb_us = 0.0
