@@ -14,15 +14,17 @@
 // lane, one instruction moving eight rows of 128 bytes (64 input features): whole
 // cache lines per instruction, each line touched by exactly one instruction
 // (register-direct loads in MFMA operand order touch every line four times and
-// run at a quarter of the rate).  Every wave has its own ring of NST stages in
-// LDS (a stage = 64 input features of its 32 weight rows and of the 32*MT query
-// rows), so there is no workgroup barrier anywhere; NST - 1 stages stay in
-// flight.  The LDS side of such a load is linear in the lane, so each lane
-// fetches the 16-byte chunk whose swizzled home is its slot (chunk index XOR
-// row mod 8: the operand reads, 32 rows at one chunk index, spread over the
-// banks).  Operand reads are 16 bytes per lane: lane (r, h) takes chunks
-// 4h .. 4h + 3 of row r for the four MFMA steps of a stage; both operands use
-// the same assignment of input features to contraction slots.
+// run at a quarter of the rate).  The workgroup keeps one ring of NST stages in
+// LDS; a stage holds 64 input features of each wave's 32 weight rows (fetched
+// and read by that wave alone) and of the 32*MT query rows, which all four waves
+// read and each fetches a quarter of (fetched once per wave they cost three
+// times the weights' bytes in L2 traffic).  One barrier per stage; NST - 1
+// stages stay in flight.  The LDS side of such a load is linear in the lane, so
+// each lane fetches the 16-byte chunk whose swizzled home is its slot (chunk
+// index XOR row mod 8: the operand reads, 32 rows at one chunk index, spread
+// over the banks).  Operand reads are 16 bytes per lane: lane (r, h) takes
+// chunks 4h .. 4h + 3 of row r for the four MFMA steps of a stage; both
+// operands use the same assignment of input features to contraction slots.
 //
 // The input features of a group can be cut into KSPLIT ranges (and, for the
 // output projection, the groups themselves are ranges of one long sum): each
@@ -60,47 +62,49 @@ __global__ __launch_bounds__(256) void proj_kernel(ProjParams p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 31, h = lane >> 5;
   const int n0 = blockIdx.x * 128 + wave * 32;
-  if (n0 >= p.N) return;  // (whole wave: N is a multiple of 32)
+  const bool n_valid = n0 < p.N;  // (N is a multiple of 32: a wave's 32 output features exist or do not)
   const int m0 = blockIdx.y * (32 * MT);
   const int g = (int)blockIdx.z / p.ksplit, ks = (int)blockIdx.z % p.ksplit;
   const int k_begin = ks * p.k_per_split;
   const int k_end = min(p.K, k_begin + p.k_per_split);
 
-  constexpr int NST = MT == 1 ? 5 : 3;                 // ring stages per wave (40 KB of LDS per wave at most)
-  constexpr int kStage = (1 + MT) * 4096;              // bytes: 32 weight rows + 32*MT query rows of 128 bytes
-  __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * NST * kStage];
+  // One ring of NST stages per workgroup; a stage holds, for 64 input features, the 32 weight rows of each
+  // of the four waves (private to the wave) and the 32*MT query rows (shared: each wave fetches a quarter).
+  // (three or four stages, 72-80 KB: two workgroups per compute unit, one streaming while the other starts up
+  // or stores; deeper rings with one resident workgroup measured 10 % slower on the output projection)
+  constexpr int NST = MT == 1 ? 4 : 3;
+  constexpr int kStage = (4 + MT) * 4096;
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[NST * kStage];
   static_assert(sizeof(smem) <= 160 * 1024, "LDS capacity");
-  unsigned char* const ring = smem + wave * (NST * kStage);
-  const unsigned ring_addr = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring;
+  const unsigned smem_addr = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
-  // load side: lane l of instruction j moves row 8j + l / 8; its LDS slot l % 8 is home to chunk (l % 8) ^ (row % 8)
+  // load side: lane l of an instruction moves row l / 8 of its block of 8 rows; its LDS slot l % 8 is home to
+  // chunk (l % 8) ^ (row % 8)
   const int lr = lane >> 3, lc = (lane & 7) ^ (lane >> 3);
   const unsigned char* wsrc[4];
-  const unsigned char* asrc[MT][4];
+  const unsigned char* asrc[MT];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    wsrc[j] = (const unsigned char*)(p.w + ((int64_t)g * p.N + n0 + 8 * j + lr) * p.K) + lc * 16;
+  for (int j = 0; j < 4; ++j)  // (waves past the last output feature fetch the last rows again and store nothing)
+    wsrc[j] = (const unsigned char*)(p.w + ((int64_t)g * p.N + min(n0 + 8 * j + lr, p.N - 1)) * p.K) + lc * 16;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = min(m0 + mt * 32 + 8 * j + lr, p.M - 1);  // rows past the end repeat the last one (never stored)
-      asrc[mt][j] = (const unsigned char*)(p.a + m * p.a_row + g * p.a_group) + lc * 16;
-    }
+  for (int mt = 0; mt < MT; ++mt) {  // query rows 32 * mt + 8 * wave .. + 7 (rows past the end repeat the last one)
+    const int m = min(m0 + mt * 32 + 8 * wave + lr, p.M - 1);
+    asrc[mt] = (const unsigned char*)(p.a + m * p.a_row + g * p.a_group) + lc * 16;
   }
-  auto issue = [&](int k, int stage) {  // 4 + 4 * MT loads
-    unsigned char* dst = ring + stage * kStage;
+  auto issue = [&](int k, int stage) {  // 4 + MT loads
+    unsigned char* dst = smem + stage * kStage;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(wsrc[j] + (int64_t)k * 2), (lds_void_t*)(dst + j * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(wsrc[j] + (int64_t)k * 2), (lds_void_t*)(dst + wave * 4096 + j * 1024), 16, 0, 0);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(asrc[mt][j] + (int64_t)k * 2), (lds_void_t*)(dst + (1 + mt) * 4096 + j * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(asrc[mt] + (int64_t)k * 2), (lds_void_t*)(dst + (4 + mt) * 4096 + wave * 1024), 16, 0, 0);
   };
   // operand side: row r, chunk 4h + s at slot (4h + s) ^ (r % 8)
   unsigned rd[4];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) rd[s] = ring_addr + (unsigned)(r * 128 + (((4 * h + s) ^ (r & 7)) << 4));
+  for (int s = 0; s < 4; ++s) rd[s] = smem_addr + (unsigned)(r * 128 + (((4 * h + s) ^ (r & 7)) << 4));
+  const unsigned w_off = (unsigned)wave * 4096u;
 
   proj_f32x16_t acc[MT];
 #pragma unroll
@@ -108,22 +112,28 @@ __global__ __launch_bounds__(256) void proj_kernel(ProjParams p) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
 
-  constexpr int LPS = 4 + 4 * MT;  // loads per stage
-  static_assert(LPS * (NST - 1) <= 63, "vmcnt range");
+  constexpr int LPS = 4 + MT;  // loads per wave and stage
+  static_assert(LPS * (NST - 2) <= 63, "vmcnt range");
   const int k_last = k_end - 64;
 #pragma unroll
   for (int st = 0; st < NST - 1; ++st) issue(min(k_begin + 64 * st, k_last), st);  // (steps past the end fetch the last one again)
   for (int k = k_begin; k < k_end; k += 64 * NST) {
     static_for<0, NST>([&](auto stc) {
       constexpr int st = decltype(stc)::value;
-      if (k + 64 * st < k_end) {  // (uniform)
+      if (k + 64 * st < k_end) {  // (uniform over the workgroup)
+        // this wave's part of stage st has landed (the NST - 2 stages behind it may be in flight); after the
+        // barrier so has everybody's, and everybody is done reading the stage before it, which is loaded next
+        wait_vmcnt<LPS * (NST - 2)>();
+        bare_barrier();
         issue(min(k + 64 * (st + NST - 1), k_last), (st + NST - 1) % NST);
-        wait_vmcnt<LPS * (NST - 1)>();  // everything but the NST - 1 newest stages has landed: stage st is in LDS
         u32x4_t wf[4], af[MT][4];
         static_for<0, 4>([&](auto sc) {
           constexpr int s = decltype(sc)::value;
-          lds_read_b128<st * kStage>(wf[s], rd[s]);
-          static_for<0, MT>([&](auto mc) { lds_read_b128<st * kStage + (1 + decltype(mc)::value) * 4096>(af[decltype(mc)::value][s], rd[s]); });
+          // (the stage offset goes into the address register: the instruction's offset field has 16 bits)
+          lds_read_b128<0>(wf[s], rd[s] + (w_off + (unsigned)(st * kStage)));
+          static_for<0, MT>([&](auto mc) {
+            lds_read_b128<(4 + decltype(mc)::value) * 4096>(af[decltype(mc)::value][s], rd[s] + (unsigned)(st * kStage));
+          });
         });
         static_for<0, 4>([&](auto sc) {
           constexpr int s = decltype(sc)::value;
@@ -145,7 +155,7 @@ __global__ __launch_bounds__(256) void proj_kernel(ProjParams p) {
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int m = m0 + mt * 32 + r;
-    if (m >= p.M) continue;
+    if (m >= p.M || !n_valid) continue;
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
       const int n = n0 + 8 * q4 + 4 * h;
