@@ -46,6 +46,36 @@ __device__ __forceinline__ void flex_lds_zero_b128(unsigned addr) {
   asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(z) : "memory");
 }
 __device__ __forceinline__ void flex_tie(u32x2_t& x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ float flex_max3(float a, float b, float c) {
+  float r;  // (as an instruction of its own: fmaxf() first canonicalises every operand that comes out of an MFMA)
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+// MFMAs as asm with every operand in an architectural VGPR.  (Left to the compiler, the accumulators go
+// to accumulation registers and are copied out and back around every piece of vector arithmetic on
+// them, the scores of every tile included.)  The compiler does not see the matrix pipe's latency behind
+// an asm statement: a result is read by other instructions only after flex_mfma_settle() on it.
+// Back-to-back MFMAs that accumulate into the same registers need no gap.
+__device__ __forceinline__ void flex_mfma0(f32x4_t& acc, const u32x2_t& a, const u32x2_t& b) {
+  asm volatile("v_mfma_f32_16x16x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void flex_mfma(f32x4_t& acc, const u32x2_t& a, const u32x2_t& b) {
+  asm volatile("v_mfma_f32_16x16x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+// The same when an operand may have been written by the vector instruction just before (an MFMA reads
+// a VGPR two wait states after a vector instruction wrote it, and the compiler, which keeps that gap
+// for its own MFMAs, is free to place such an instruction directly in front of an asm statement).
+__device__ __forceinline__ void flex_mfma_fresh(f32x4_t& acc, const u32x2_t& a, const u32x2_t& b) {
+  asm volatile("s_nop 1\n\tv_mfma_f32_16x16x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+// 4-pass MFMA result -> read or overwrite by a vector instruction: 7 wait states; 8 given
+__device__ __forceinline__ void flex_mfma_settle(f32x4_t& a, f32x4_t& b) { asm volatile("s_nop 7" : "+v"(a), "+v"(b)); }
+template <int N>
+__device__ __forceinline__ void flex_mfma_settle(f32x4_t (&o)[N], f32x4_t& one) {
+  asm volatile("s_nop 7" : "+v"(one));
+#pragma unroll
+  for (int i = 0; i < N; ++i) asm volatile("" : "+v"(o[i]));
+}
 template <int N>
 __device__ __forceinline__ void flex_lds_wait_all(u32x2_t (&x)[N]) {
   // every LDS read issued so far has returned; tied to the registers so that no use moves ahead of it
@@ -56,71 +86,92 @@ __device__ __forceinline__ void flex_lds_wait_all(u32x2_t (&x)[N]) {
   for (int i = 0; i < N; ++i) flex_tie(x[i]);
 }
 
-template <int DN, int DR, int DV, bool SEPK>
+// GPW: groups per wave.  With at most eight query rows per group two groups share the 16 rows of a wave
+// (rows 0 .. 7 the first group, 8 .. 15 the second): each group's queries are zero in the other's rows,
+// so the score MFMAs of both groups and of the shared RoPE key add up in ONE accumulator, the softmax
+// arithmetic runs once on 16 full rows instead of twice on half-empty ones, and the RoPE-key tile is
+// fetched and read once for both.  The value products keep one accumulator set per group (each holds
+// all 16 rows against its group's values; only the group's own rows are stored).
+template <int DN, int DR, int DV, bool SEPK, int GPW = 1>
 struct FlexTraits {
   static constexpr int kVB = DV * 2, kKB = DN * 2, kRB = DR * 2;  // row bytes of the value / key / RoPE tiles
-  static constexpr int kStage = 32 * (kVB + (SEPK ? kKB : 0) + kRB);
-  static constexpr int kNST = (40 * 1024 / kStage) < 6 ? (40 * 1024 / kStage) : 6;  // ring stages per wave (40 KB each)
-  static constexpr int loads(int rb) {  // load instructions for 32 rows of rb bytes
-    return rb == 0 ? 0 : (32 + 64 / (rb / 16) - 1) / (64 / (rb / 16));
-  }
-  static constexpr int kLPT = loads(kVB) + (SEPK ? loads(kKB) : 0) + loads(kRB);
+  static constexpr int kStage = 32 * (GPW * kVB + (SEPK ? kKB : 0) + kRB);
+  // Ring stages per wave.  Small tiles: three stages in 20 KB, so that two workgroups (two waves per SIMD)
+  // share a compute unit and one wave's LDS and MFMA latencies hide behind the other's work; larger
+  // tiles: as many stages as 40 KB hold, at most six (one workgroup per compute unit).
+  static constexpr int kNST = 3 * kStage <= 20 * 1024 ? 3 : (40 * 1024 / kStage) < 6 ? (40 * 1024 / kStage) : 6;
+  static constexpr int loads(int rb) { return rb / 32; }  // load instructions (64 lanes x 16 bytes) for 32 rows of rb bytes
+  static constexpr int kLPT = GPW * loads(kVB) + (SEPK ? loads(kKB) : 0) + loads(kRB);
+  static_assert(GPW == 1 || (GPW == 2 && !SEPK), "two groups per wave: tied / latent states only");
   static_assert(kNST >= 2, "at least two stages");
   static_assert(kLPT * (kNST - 1) <= 63, "vmcnt range");
   static_assert(DN % 16 == 0 && DR % 16 == 0 && DV % 16 == 0 && (SEPK || DN <= DV), "dims");
+  static_assert(kVB % 32 == 0 && kKB % 32 == 0 && kRB % 32 == 0, "a tile is a whole number of load instructions");
 };
 
-template <int DN, int DR, int DV, bool SEPK>
+template <int DN, int DR, int DV, bool SEPK, int GPW = 1>
 __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
-  using FT = FlexTraits<DN, DR, DV, SEPK>;
+  using FT = FlexTraits<DN, DR, DV, SEPK, GPW>;
   constexpr int NST = FT::kNST, STAGE = FT::kStage, LPT = FT::kLPT;
   constexpr int VB = FT::kVB, KB = FT::kKB, RB = FT::kRB;
-  constexpr int OFF_K = 32 * VB, OFF_R = OFF_K + (SEPK ? 32 * KB : 0);  // tile offsets inside a stage
-  constexpr int NKN = DN / 16, NKR = DR / 16, NKS = NKN + NKR;         // contraction steps of the scores
-  constexpr int NDB = DV / 16;                                          // 16-dim output blocks
+  constexpr int OFF_K = GPW * 32 * VB, OFF_R = OFF_K + (SEPK ? 32 * KB : 0);  // tile offsets inside a stage
+  constexpr int NKN = DN / 16, NKR = DR / 16;                                  // contraction steps of the scores
+  constexpr int NDB = DV / 16;                                                 // 16-dim output blocks
+  constexpr int NLV = FT::loads(VB), NLK = SEPK ? FT::loads(KB) : 0, NLR = FT::loads(RB);
+  constexpr int NKF = GPW * NKN + NKR;  // key operands per 16-key block
   __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * NST * STAGE];
   static_assert(sizeof(smem) <= 160 * 1024, "LDS capacity");
 
   const int lane = threadIdx.x & 63;
   const int wave = uniform((int)threadIdx.x >> 6);
   const int r16 = lane & 15, q = lane >> 4;
-  unsigned char* const ring = smem + wave * (NST * STAGE);
-  const unsigned ring_addr = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring;
+  const unsigned ring_addr =
+      (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + (unsigned)(wave * (NST * STAGE));
 
-  // ---- this wave's unit: key ranges fastest, so the waves of a workgroup read disjoint keys
+  // ---- this wave's unit: groups fastest, so the waves of a workgroup fetch the
+  //      SAME shared RoPE-key rows at about the same time (one trip to HBM for all of them)
   const int rows_group = p.g_q * p.T;
-  const int RBK = p.flex_rb;  // blocks of 16 rows per group
-  const int64_t unit = (int64_t)blockIdx.x * 4 + wave;
-  if (unit >= (int64_t)p.B * p.h_c * RBK * p.splits) return;
-  const int s = (int)(unit % p.splits);
-  const int rb = (int)((unit / p.splits) % RBK);
-  const int g = (int)((unit / ((int64_t)p.splits * RBK)) % p.h_c);
-  const int b = (int)(unit / ((int64_t)p.splits * RBK * p.h_c));
-  const int L = p.seq_lens[b];
+  const int RBK = p.flex_rb;            // blocks of 16 rows per group (GPW == 2: one)
+  const unsigned HB = (unsigned)p.h_c / GPW;  // group blocks
+  const unsigned unit = blockIdx.x * 4u + (unsigned)wave;  // (the host keeps the number of waves below 2^31)
+  if (unit >= (unsigned)p.B * HB * (unsigned)RBK * (unsigned)p.splits) return;
+  const unsigned u1 = unit / HB, u2 = u1 / (unsigned)p.splits;
+  const int g0 = (int)(unit - u1 * HB) * GPW;  // first group of this wave
+  const int s = (int)(u1 - u2 * (unsigned)p.splits);
+  const int b = (int)(u2 / (unsigned)RBK);
+  const int rb = (int)(u2 - (unsigned)b * (unsigned)RBK);
+  const int L = uniform(p.seq_lens[b]);
   const int tiles_b = L > 0 ? (L + 31) >> 5 : 0;
   const int t0 = min(s * p.pages_per_split, tiles_b);  // (for this kernel: tiles per range)
   const int t1 = min(t0 + p.pages_per_split, tiles_b);
   const int n_t = t1 - t0;
 
   // ---- the query row of this lane (rows past the end of the group repeat the last one, never stored)
-  const int R = rb * 16 + r16;
+  const int jg = GPW == 2 ? r16 >> 3 : 0;                  // which of the wave's groups the row belongs to
+  const int R = GPW == 2 ? (r16 & 7) : rb * 16 + r16;      // row within the group
   const bool row_valid = R < rows_group;
   const int Rc = row_valid ? R : rows_group - 1;
   const int t = Rc / p.g_q;
-  const int h = g * p.g_q + (Rc - t * p.g_q);
-  const int n_vis = row_valid ? (p.causal ? L - p.T + 1 + t : L) : 0;
+  const int h = (g0 + jg) * p.g_q + (Rc - t * p.g_q);
+  const int n_vis = p.causal ? L - p.T + 1 + t : L;
+  const int n_vis_min = uniform(n_vis);  // lane 0 holds the block's first row, which sees the fewest keys
   const int64_t row_idx = ((int64_t)b * p.T + t) * p.h_q + h;
 
-  // ---- query fragments: B operand of the score MFMAs, dims 16 * ks + 4 * q .. + 3 of row r16
-  u32x2_t qf[NKS];
+  // ---- query fragments: B operand of the score MFMAs, dims 16 * ks + 4 * q .. + 3 of row r16; the
+  //      non-RoPE part once per group of the wave, zero in the rows of the other group
+  u32x2_t qn[GPW][NKN], qr[NKR > 0 ? NKR : 1];
   {
-    const uint16_t* qn = p.q_nope + b * p.qn_s[0] + t * p.qn_s[1] + h * p.qn_s[2] + 4 * q;
+    const uint16_t* src = p.q_nope + b * p.qn_s[0] + t * p.qn_s[1] + h * p.qn_s[2] + 4 * q;
 #pragma unroll
-    for (int ks = 0; ks < NKN; ++ks) qf[ks] = *reinterpret_cast<const u32x2_t*>(qn + 16 * ks);
+    for (int ks = 0; ks < NKN; ++ks) {
+      const u32x2_t v = *reinterpret_cast<const u32x2_t*>(src + 16 * ks);
+#pragma unroll
+      for (int j = 0; j < GPW; ++j) qn[j][ks] = (GPW == 1 || jg == j) ? v : u32x2_t{0u, 0u};
+    }
     if constexpr (NKR > 0) {
-      const uint16_t* qr = p.q_rope + b * p.qr_s[0] + t * p.qr_s[1] + h * p.qr_s[2] + 4 * q;
+      const uint16_t* srcr = p.q_rope + b * p.qr_s[0] + t * p.qr_s[1] + h * p.qr_s[2] + 4 * q;
 #pragma unroll
-      for (int ks = 0; ks < NKR; ++ks) qf[NKN + ks] = *reinterpret_cast<const u32x2_t*>(qr + 16 * ks);
+      for (int ks = 0; ks < NKR; ++ks) qr[ks] = *reinterpret_cast<const u32x2_t*>(srcr + 16 * ks);
     }
   }
 
@@ -137,155 +188,235 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
     return __builtin_amdgcn_readlane(pt_vec, pg - pt_base);
   };
 
-  // ---- tile loads.  A load instruction moves 64 / LPR whole rows (LPR = 16-byte chunks per row); lane l
-  //      writes slot l % LPR of row l / LPR and fetches the chunk whose rotated home that slot is.
-  auto issue_rows = [&](auto rbc, const unsigned char* src_tile, int64_t row_stride_bytes, unsigned char* dst) {
+  // ---- tile loads.  A tile of 32 rows of LPR 16-byte chunks is 32 * LPR consecutive LDS slots, 64 per
+  //      load instruction (LPR is even: every instruction is full).  Slot n belongs to row n / LPR and holds
+  //      the chunk that rotation by the row index sends there; the byte offset of that chunk from the tile's
+  //      first row is all a lane needs per load, and it is the same for every tile.
+  unsigned goff_v[NLV], goff_k[NLK > 0 ? NLK : 1], goff_r[NLR > 0 ? NLR : 1];
+  auto lane_offsets = [&](auto rbc, auto& goff) {
     constexpr int RBY = decltype(rbc)::value;
-    constexpr int LPR = RBY / 16, RPI = 64 / LPR, NI = (32 + RPI - 1) / RPI;
-    const int lrow = lane / LPR, slot = lane % LPR;
-    static_for<0, NI>([&](auto jc) {
-      constexpr int j = decltype(jc)::value;
-      const int row = j * RPI + lrow;
-      if (lane < RPI * LPR && row < 32) {
-        int chunk = slot - (row % LPR);
-        chunk += chunk < 0 ? LPR : 0;
-        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_tile + row * row_stride_bytes + chunk * 16),
-                                         (lds_void_t*)(dst + j * RPI * RBY), 16, 0, 0);
-      }
-    });
+    constexpr int LPR = RBY / 16;
+    static_assert(LPR % 2 == 0, "whole load instructions");
+#pragma unroll
+    for (int j = 0; j < LPR / 2; ++j) {
+      const int n = j * 64 + lane, row = n / LPR, slot = n % LPR;
+      int chunk = slot - row % LPR;
+      chunk += chunk < 0 ? LPR : 0;
+      goff[j] = (unsigned)(row * RBY + chunk * 16);
+    }
   };
+  lane_offsets(std::integral_constant<int, VB>{}, goff_v);
+  if constexpr (SEPK) lane_offsets(std::integral_constant<int, KB>{}, goff_k);
+  if constexpr (DR > 0) lane_offsets(std::integral_constant<int, RB>{}, goff_r);
+  const unsigned char* const state_b = (const unsigned char*)(p.state + g0 * p.st_s[1]);
+  const unsigned char* const key_b = SEPK ? (const unsigned char*)(p.kstate + g0 * p.k_s[1]) : nullptr;
+  const unsigned char* const rope_b = (const unsigned char*)p.rope;
   auto issue_tile = [&](int tile, int stage) {
     const int64_t page = page_of_tile(tile);
     const int tok = (tile << 5) & ((1 << lgP) - 1);  // first token of the tile inside its page
-    unsigned char* dst = ring + stage * STAGE;
-    const unsigned char* v = (const unsigned char*)(p.state + page * p.st_s[0] + g * p.st_s[1] + (int64_t)tok * p.st_s[2]);
-    issue_rows(std::integral_constant<int, VB>{}, v, p.st_s[2] * 2, dst);
+    unsigned char* dst = smem + wave * (NST * STAGE) + stage * STAGE;
+    const unsigned char* v = state_b + (page * p.st_s[0] + (int64_t)tok * DV) * 2;
+#pragma unroll
+    for (int j = 0; j < GPW; ++j)
+#pragma unroll
+      for (int i = 0; i < NLV; ++i)
+        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(v + j * p.st_s[1] * 2 + goff_v[i]),
+                                         (lds_void_t*)(dst + j * 32 * VB + i * 1024), 16, 0, 0);
     if constexpr (SEPK) {
-      const unsigned char* k = (const unsigned char*)(p.kstate + page * p.k_s[0] + g * p.k_s[1] + (int64_t)tok * p.k_s[2]);
-      issue_rows(std::integral_constant<int, KB>{}, k, p.k_s[2] * 2, dst + OFF_K);
+      const unsigned char* k = key_b + (page * p.k_s[0] + (int64_t)tok * DN) * 2;
+#pragma unroll
+      for (int j = 0; j < NLK; ++j)
+        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(k + goff_k[j]), (lds_void_t*)(dst + OFF_K + j * 1024), 16, 0, 0);
     }
     if constexpr (DR > 0) {
-      const unsigned char* rp = (const unsigned char*)(p.rope + page * p.rp_s[0] + (int64_t)tok * p.rp_s[1]);
-      issue_rows(std::integral_constant<int, RB>{}, rp, p.rp_s[1] * 2, dst + OFF_R);
+      const unsigned char* rp = rope_b + (page * p.rp_s[0] + (int64_t)tok * DR) * 2;
+#pragma unroll
+      for (int j = 0; j < NLR; ++j)
+        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(rp + goff_r[j]), (lds_void_t*)(dst + OFF_R + j * 1024), 16, 0, 0);
     }
   };
 
-  // ---- per-row state
-  f32x4_t o[NDB];
+  // ---- LDS offsets of this lane's operand reads inside a stage (the same for every tile)
+  //      scores: key row 16 * kb + r16, chunk 2 * ks + q / 2, half q % 2; operand order per key block:
+  //      the non-RoPE steps of group 0, of group 1, then the RoPE steps
+  //      values (transposing read): block q of 16 lanes reads keys 4q .. 4q + 3: lane 4r' + c' takes key r', dims 4c' .. 4c' + 3
+  unsigned koff[2][NKF], voff[2][GPW * NDB];
 #pragma unroll
-  for (int db = 0; db < NDB; ++db) o[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;  // l_run: this lane's share of the row sum
+  for (int kb = 0; kb < 2; ++kb) {
+    const int row = 16 * kb + r16;
+#pragma unroll
+    for (int j = 0; j < GPW; ++j)
+#pragma unroll
+      for (int ks = 0; ks < NKN; ++ks) {
+        constexpr int LPRK = (SEPK ? KB : VB) / 16;
+        const int slot = (2 * ks + (q >> 1) + row) % LPRK;
+        koff[kb][j * NKN + ks] = (unsigned)((SEPK ? OFF_K : j * 32 * VB) + row * (SEPK ? KB : VB) + slot * 16 + (q & 1) * 8);
+      }
+#pragma unroll
+    for (int ks = 0; ks < NKR; ++ks) {
+      constexpr int LPRR = RB > 0 ? RB / 16 : 1;
+      const int slot = (2 * ks + (q >> 1) + row) % LPRR;
+      koff[kb][GPW * NKN + ks] = (unsigned)(OFF_R + row * RB + slot * 16 + (q & 1) * 8);
+    }
+    constexpr int LPRV = VB / 16;
+    const int tr_r = r16 >> 2, tr_c = r16 & 3;
+    const int vrow = 16 * kb + 4 * q + tr_r;
+#pragma unroll
+    for (int j = 0; j < GPW; ++j)
+#pragma unroll
+      for (int db = 0; db < NDB; ++db) {
+        const int slot = (2 * db + (tr_c >> 1) + vrow) % LPRV;
+        voff[kb][j * NDB + db] = (unsigned)(j * 32 * VB + vrow * VB + slot * 16 + (tr_c & 1) * 8);
+      }
+  }
+
+  // ---- per-row state.  Weights are taken relative to a reference m_ref (log2 domain, the same in the four
+  //      lanes of a row) that is moved up only when a score exceeds it by more than kRebase: most tiles
+  //      need no cross-lane traffic and no rescaling.  m_ref starts finite so that a masked score
+  //      (-inf) gives weight exp2(-inf) = 0 and never inf - inf.
+  constexpr float kRebase = 8.f;
+  constexpr float kLogHeavyShare = -2.f;  // a weight above a quarter of its row's running sum gets its rounding residual added
+  f32x4_t o[GPW * NDB], o_one = {0.f, 0.f, 0.f, 0.f};  // o_one: row sum of the weights as the MFMAs saw them (bf16-rounded)
+#pragma unroll
+  for (int db = 0; db < GPW * NDB; ++db) o[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m_ref = -1e30f, l_run = 0.f;  // l_run: this lane's share of the exact fp32 row sum
+  float heavy_thr = -INFINITY;        // refreshed lazily; the running sum only grows, so a stale value errs on the safe side
   const float sc2 = p.scale * 1.4426950408889634f;
+  const u32x2_t ones = {0x3f803f80u, 0x3f803f80u};  // four bf16 ones
+
+  // value MFMAs of one pass over the tile: every group's accumulators against that group's values
+  auto value_mfmas = [&](u32x2_t (&vf)[2 * GPW * NDB], const u32x2_t (&pb)[2]) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      flex_mfma_fresh(o[0], vf[kb * GPW * NDB], pb[kb]);
+#pragma unroll
+      for (int d = 1; d < GPW * NDB; ++d) flex_mfma(o[d], vf[kb * GPW * NDB + d], pb[kb]);
+      flex_mfma(o_one, ones, pb[kb]);
+    }
+  };
 
   if (n_t > 0) {
 #pragma unroll
     for (int st = 0; st < NST - 1; ++st) issue_tile(t0 + min(st, n_t - 1), st);  // (tiles past the end: the last one again)
   }
+  int st_cur = 0, st_load = NST - 1;
   for (int i = 0; i < n_t; ++i) {
-    issue_tile(t0 + min(i + NST - 1, n_t - 1), (i + NST - 1) % NST);
+    issue_tile(t0 + min(i + NST - 1, n_t - 1), st_load);
+    st_load = st_load == NST - 1 ? 0 : st_load + 1;
     wait_vmcnt<LPT * (NST - 1)>();  // all but the NST - 1 newest tiles have landed: tile i is in LDS
     const int tile = t0 + i;
-    const unsigned st_addr = ring_addr + (unsigned)((i % NST) * STAGE);
+    const unsigned st_addr = ring_addr + (unsigned)(st_cur * STAGE);
+    st_cur = st_cur == NST - 1 ? 0 : st_cur + 1;
     // value rows at or past the end of the sequence may hold anything: zero them (weight 0 x NaN must not leak)
     if ((tile << 5) + 32 > L) {
       const int valid = L - (tile << 5);
-      for (int off = valid * VB + lane * 16; off < 32 * VB; off += 64 * 16) flex_lds_zero_b128(st_addr + off);
+#pragma unroll
+      for (int j = 0; j < GPW; ++j)
+        for (int off = valid * VB + lane * 16; off < 32 * VB; off += 64 * 16) flex_lds_zero_b128(st_addr + j * 32 * VB + off);
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
 
     // ---- scores of the two 16-key blocks: S^T[key 4q + i][row r16]
-    f32x4_t sc[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      const int row = 16 * kb + r16;  // key row this lane reads
-      u32x2_t kf[NKS];
-      static_for<0, NKS>([&](auto ksc) {
-        constexpr int ks = decltype(ksc)::value;
-        if constexpr (ks < NKN) {
-          constexpr int LPRK = (SEPK ? KB : VB) / 16;
-          const int slot = (2 * ks + (q >> 1) + row) % LPRK;  // chunk 2 * ks + q / 2, rotated by the row
-          flex_lds_read_b64(kf[ks], st_addr + (SEPK ? OFF_K : 0) + row * (SEPK ? KB : VB) + slot * 16 + (q & 1) * 8);
-        } else {
-          constexpr int LPRR = RB / 16;
-          const int slot = (2 * (ks - NKN) + (q >> 1) + row) % LPRR;
-          flex_lds_read_b64(kf[ks], st_addr + OFF_R + row * RB + slot * 16 + (q & 1) * 8);
-        }
-      });
-      flex_lds_wait_all(kf);
-      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-      static_for<0, NKS>([&](auto ksc) {
-        constexpr int ks = decltype(ksc)::value;
-        acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(flex_s16x4_t, kf[ks]),
-                                                         __builtin_bit_cast(flex_s16x4_t, qf[ks]), acc, 0, 0, 0);
-      });
-      sc[kb] = acc;
-    }
-    // ---- mask by select, row max over the row's four lanes, online softmax
-    float x[8];
-    float mx = -INFINITY;
+    u32x2_t kf[2 * NKF];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int key = (tile << 5) + 16 * kb + 4 * q + e;
-        const float v = key < n_vis ? sc[kb][e] * sc2 : -INFINITY;
-        x[4 * kb + e] = v;
-        mx = fmaxf(mx, v);
+      for (int ks = 0; ks < NKF; ++ks) flex_lds_read_b64(kf[kb * NKF + ks], st_addr + koff[kb][ks]);
+    flex_lds_wait_all(kf);
+    f32x4_t sc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) flex_mfma0(sc[kb], kf[kb * NKF], qn[0][0]);
+    static_for<1, NKF>([&](auto ksc) {
+      constexpr int ks = decltype(ksc)::value;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        if constexpr (ks < GPW * NKN)
+          flex_mfma(sc[kb], kf[kb * NKF + ks], qn[ks / NKN][ks % NKN]);
+        else
+          flex_mfma(sc[kb], kf[kb * NKF + ks], qr[ks - GPW * NKN]);
       }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);  // (m_run = -inf: 0)
+    });
+    flex_mfma_settle(sc[0], sc[1]);
+    // ---- mask by select (last tiles only), then this lane's largest score
+    if ((tile << 5) + 32 > n_vis_min) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          sc[kb][e] = (tile << 5) + 16 * kb + 4 * q + e < n_vis ? sc[kb][e] : -INFINITY;
+    }
+    const float mx = flex_max3(flex_max3(flex_max3(sc[0][0], sc[0][1], sc[0][2]), sc[0][3], sc[1][0]),
+                               flex_max3(sc[1][1], sc[1][2], sc[1][3]), -INFINITY);
+    float lg = __builtin_fmaf(mx, sc2, -m_ref);  // log2 of this lane's largest weight
+    if (__ballot(lg > kRebase) != 0) {
+      flex_mfma_settle(o, o_one);  // (the value MFMAs of the tile before may still be on their way)
+      float mrow = mx * sc2;
+      mrow = fmaxf(mrow, __shfl_xor(mrow, 16, 64));
+      mrow = fmaxf(mrow, __shfl_xor(mrow, 32, 64));
+      const float m_new = fmaxf(m_ref, mrow);
+      const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+      m_ref = m_new;
+      l_run *= alpha;
+      o_one *= alpha;
+#pragma unroll
+      for (int db = 0; db < GPW * NDB; ++db) o[db] *= alpha;
+      heavy_thr = -INFINITY;
+      lg = __builtin_fmaf(mx, sc2, -m_ref);
+    }
+    // ---- value operands on their way while the weights are computed
+    u32x2_t vf[2 * GPW * NDB];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int d = 0; d < GPW * NDB; ++d) flex_lds_read_tr(vf[kb * GPW * NDB + d], st_addr + voff[kb][d]);
+    asm volatile("" : "+v"(sc[0]), "+v"(sc[1]));  // (keeps the reads above ahead of the arithmetic below)
     float pw[8], psum = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      pw[e] = m_new == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(x[e] - m_new);
+      pw[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e >> 2][e & 3], sc2, -m_ref));
       psum += pw[e];
     }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int db = 0; db < NDB; ++db) o[db] *= alpha;
-    // weights as bf16 pairs hi + lo
-    u32x2_t p_hi[2], p_lo[2];
+    l_run += psum;
+    u32x2_t p_hi[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int e2 = 0; e2 < 2; ++e2) {
-        const float a0 = pw[4 * kb + 2 * e2], a1 = pw[4 * kb + 2 * e2 + 1];
-        const uint32_t hi = cvt_pk_bf16(a0, a1);
-        const float h0 = __builtin_bit_cast(float, hi << 16), h1 = __builtin_bit_cast(float, hi & 0xffff0000u);
-        p_hi[kb][e2] = hi;
-        p_lo[kb][e2] = cvt_pk_bf16(a0 - h0, a1 - h1);
-      }
-    // ---- O^T += V^T . P^T: block q of 16 lanes reads keys 4q .. 4q + 3 (lane 4r' + c': key r', dims 4c' .. 4c' + 3)
-    constexpr int LPRV = VB / 16;
-    const int tr_r = r16 >> 2, tr_c = r16 & 3;
+      for (int e2 = 0; e2 < 2; ++e2) p_hi[kb][e2] = cvt_pk_bf16(pw[4 * kb + 2 * e2], pw[4 * kb + 2 * e2 + 1]);
+    flex_lds_wait_all(vf);
+    // ---- O^T += V^T . P^T, and the row sums of the rounded weights through a ones-valued operand
+    value_mfmas(vf, p_hi);
+    // ---- rows that put much of their weight on one key of this tile: add the rounding residuals
+    //      p - bf16(p) (as bf16) in a second pass, so those weights carry 16 significant bits
+    if (__builtin_expect(__ballot(lg > heavy_thr) != 0, 0)) {
+      float l_row = l_run + __shfl_xor(l_run, 16, 64);
+      l_row += __shfl_xor(l_row, 32, 64);
+      heavy_thr = __builtin_amdgcn_logf(l_row) + kLogHeavyShare;
+      if (__ballot(lg > heavy_thr) != 0) {
+        u32x2_t p_lo[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      const int row = 16 * kb + 4 * q + tr_r;
-      u32x2_t vf[NDB];
-      static_for<0, NDB>([&](auto dbc) {
-        constexpr int db = decltype(dbc)::value;
-        const int slot = (2 * db + (tr_c >> 1) + row) % LPRV;
-        flex_lds_read_tr(vf[db], st_addr + row * VB + slot * 16 + (tr_c & 1) * 8);
-      });
-      flex_lds_wait_all(vf);
-      static_for<0, NDB>([&](auto dbc) {
-        constexpr int db = decltype(dbc)::value;
-        const flex_s16x4_t a = __builtin_bit_cast(flex_s16x4_t, vf[db]);
-        o[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(flex_s16x4_t, p_hi[kb]), o[db], 0, 0, 0);
-        o[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(flex_s16x4_t, p_lo[kb]), o[db], 0, 0, 0);
-      });
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int e2 = 0; e2 < 2; ++e2) {
+            const float a0 = pw[4 * kb + 2 * e2], a1 = pw[4 * kb + 2 * e2 + 1];
+            const uint32_t hi = p_hi[kb][e2];
+            p_lo[kb][e2] = cvt_pk_bf16(a0 - __builtin_bit_cast(float, hi << 16), a1 - __builtin_bit_cast(float, hi & 0xffff0000u));
+          }
+        value_mfmas(vf, p_lo);
+      }
     }
   }
   wait_vmcnt<0>();  // (tiles fetched again past the end of the range: let them land before the wave leaves)
+  flex_mfma_settle(o, o_one);
+  auto own = [&](int db) -> f32x4_t {  // the accumulators of this lane's own group
+    if constexpr (GPW == 2) return jg ? o[NDB + db] : o[db];
+    else return o[db];
+  };
 
   // ---- result of this key range: O^T[dim 16 * db + 4q + i][row r16]
   float l_tot = l_run + __shfl_xor(l_run, 16, 64);
   l_tot += __shfl_xor(l_tot, 32, 64);
-  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-  const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
+  const float inv = o_one[0] > 0.f ? 1.f / o_one[0] : 0.f;
+  const float lse = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
   if (!row_valid) return;
   if (p.splits == 1) {
     if (q == 0) p.lse[row_idx] = lse;
@@ -293,7 +424,7 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
 #pragma unroll
     for (int db = 0; db < NDB; ++db) {
       const int dim = 16 * db + 4 * q;
-      const f32x4_t v = o[db] * inv;
+      const f32x4_t v = own(db) * inv;
       if (p.out_fp32) {
         *(f32x4_t*)((float*)p.out + ob + dim) = v;
       } else {
@@ -308,7 +439,7 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
     if (q == 0) p.ws_lse[(int64_t)s * rows + row_idx] = lse;
     float* dst = p.ws_out + ((int64_t)s * rows + row_idx) * DV;
 #pragma unroll
-    for (int db = 0; db < NDB; ++db) *(f32x4_t*)(dst + 16 * db + 4 * q) = o[db] * inv;
+    for (int db = 0; db < NDB; ++db) *(f32x4_t*)(dst + 16 * db + 4 * q) = own(db) * inv;
   }
 }
 

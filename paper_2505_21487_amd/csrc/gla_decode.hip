@@ -57,6 +57,7 @@ bool generic_supported(const gla_decode_params* p) { return p->d_v <= 1024 && p-
 // ---- flex kernel (flex_kernels.hpp): which instantiation, how many key ranges
 struct FlexPlan {
   int id;       // index into the instantiation list below, -1: none
+  int gpw;      // groups per wave (2: two groups of at most eight rows share a wave's 16 rows)
   int rb;       // blocks of 16 rows per group
   int splits, tiles_per_split;
 };
@@ -94,20 +95,22 @@ bool flex_plan(const gla_decode_params* p, int mode, const KeyCache* kc, FlexPla
   }
   const int rows_group = (p->num_q_heads / p->num_groups) * p->q_len;
   plan->rb = (rows_group + 15) / 16;
-  const int64_t units = (int64_t)p->batch * p->num_groups * plan->rb;
+  plan->gpw = (plan->id == 2 && rows_group <= 8 && p->num_groups % 2 == 0) ? 2 : 1;
+  const int64_t units = (int64_t)p->batch * (p->num_groups / plan->gpw) * plan->rb;
   const int64_t max_tiles = std::max<int64_t>(1, ((int64_t)p->max_pages_per_seq * ps + 31) / 32);
   int64_t sp;
   if (p->num_splits > 0) {
     sp = p->num_splits;
   } else {
-    // about eight waves' worth of key ranges per compute unit, ranges of at least eight tiles
-    sp = (8 * (int64_t)device_cu_count() + units - 1) / std::max<int64_t>(units, 1);
+    // about four waves per compute unit (what is resident at once), ranges of at least eight tiles:
+    // a wave's start (lengths, page ids, queries, first tiles) costs several tiles' worth of time
+    sp = (4 * (int64_t)device_cu_count() + units - 1) / std::max<int64_t>(units, 1);
     sp = std::min<int64_t>(sp, std::max<int64_t>(1, max_tiles / 8));
   }
   sp = std::max<int64_t>(1, std::min<int64_t>(sp, std::min<int64_t>(max_tiles, 65535)));
   plan->tiles_per_split = (int)((max_tiles + sp - 1) / sp);
   plan->splits = (int)((max_tiles + plan->tiles_per_split - 1) / plan->tiles_per_split);
-  if (units * plan->splits > (int64_t)0x7fffffff * 4) return false;
+  if (units * plan->splits > (int64_t)0x7fffffff) return false;  // (one wave each; the kernel counts them in 32 bits)
   return true;
 }
 
@@ -174,13 +177,18 @@ int launch_flex(const gla_decode_params* p, const FlexPlan& plan, DevParams& d, 
     d.ws_out = (float*)p->workspace;
     d.ws_lse = (float*)((char*)p->workspace + align_up((size_t)plan.splits * rows * p->d_v * sizeof(float), 256));
   }
-  const int64_t waves = (int64_t)p->batch * p->num_groups * plan.rb * plan.splits;
+  const int64_t waves = (int64_t)p->batch * (p->num_groups / plan.gpw) * plan.rb * plan.splits;
   const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
   if (ev) (void)hipEventRecord(ev[0], st);
   switch (plan.id) {
     case 0: hipLaunchKernelGGL((flex_main_kernel<128, 0, 128, true>), grid, block, 0, st, d); break;
     case 1: hipLaunchKernelGGL((flex_main_kernel<64, 0, 64, true>), grid, block, 0, st, d); break;
-    case 2: hipLaunchKernelGGL((flex_main_kernel<32, 32, 64, false>), grid, block, 0, st, d); break;
+    case 2:
+      if (plan.gpw == 2)
+        hipLaunchKernelGGL((flex_main_kernel<32, 32, 64, false, 2>), grid, block, 0, st, d);
+      else
+        hipLaunchKernelGGL((flex_main_kernel<32, 32, 64, false>), grid, block, 0, st, d);
+      break;
     case 3: hipLaunchKernelGGL((flex_main_kernel<48, 48, 96, false>), grid, block, 0, st, d); break;
     case 4: hipLaunchKernelGGL((flex_main_kernel<128, 32, 128, false>), grid, block, 0, st, d); break;
     default: return GLA_ERR_UNSUPPORTED_SHAPE;
