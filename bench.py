@@ -350,7 +350,7 @@ def main() -> int:
     prm = [gla.make_params(*d.args()[:6], d.p.scale, out=out, lse=lse, workspace=None,
                            causal=bool(d.p.causal), num_splits=args.num_splits, impl=args.impl)
            for d in (d0, d1)]
-    need = gla.gla_decode_workspace_size(prm[0], is_gta)
+    need = max(gla.gla_decode_workspace_size(q, is_gta) for q in prm)  # (the two draws differ in their longest sequence)
     ws = torch.empty(need, dtype=torch.uint8, device=dev)
     impl = gla.gla_decode_select_impl(prm[0], is_gta)
     for q in prm:

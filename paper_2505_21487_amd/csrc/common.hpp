@@ -52,9 +52,10 @@ struct DevParams {
   int32_t P, max_pages;
   int32_t causal, out_fp32;
   float scale;
-  // generic kernel: uniform split of every sequence's page range (flex kernel: pages_per_split counts tiles of 32 tokens)
+  // generic kernel: uniform split of every sequence's page range
   int32_t splits, pages_per_split;
   int32_t flex_rb;          // flex kernel: blocks of 16 query rows per group
+  int32_t* flex_rng;        // flex kernel: per (sequence, strand) the first chunk holding a piece of it (x 2 + its slot) and the last
   // tuned kernel: flat partition of all key tiles of the batch into chunks
   int32_t num_chunks;       // chunks of the tile list (the main kernel runs one workgroup per chunk and row block)
   int32_t chunk_tiles;      // > 0: fixed tiles per chunk; 0: ceil(total / num_chunks)

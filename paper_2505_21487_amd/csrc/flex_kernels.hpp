@@ -8,24 +8,32 @@
 // cache of its own (SEPK).
 //
 // These shapes have few query rows per group and little arithmetic per cache
-// byte, so the design is the simplest one that streams well: ONE WAVE per
-// (sequence, group, block of 16 query rows, key range), no cooperation between
-// waves, hence no barriers.  A wave moves its tiles of 32 tokens global -> LDS
-// with direct-to-LDS loads of whole cache rows through its own ring of stages
-// and works in the transposed form on 16x16x16 bf16 MFMAs:
+// byte, so the design is the simplest one that streams well: ONE WAVE per piece
+// of work, no cooperation between waves, hence no barriers.  The key tiles of
+// all sequences form one flat list, cut into equal chunks; a wave takes one
+// chunk for one (group block, block of 16 query rows) and walks through the
+// sequences its chunk touches, so ragged batches balance by construction.  It
+// moves its tiles of 32 tokens global -> LDS with direct-to-LDS loads of whole
+// cache rows through its own ring of stages (the fetch runs ahead across the
+// boundaries between sequences) and works in the transposed form on 16x16x16
+// bf16 MFMAs:
 //     S^T = K . Q^T       A operand: key rows from LDS (8 bytes per lane), B: query fragments in registers
 //     O^T += V^T . P^T    A: value tile read with transposing LDS reads, B: the score accumulators, which
 //                         already have the B-operand layout (key 4 * (lane / 16) + i of query row lane % 16)
 // Softmax statistics of a row live in the four lanes {r, r + 16, r + 32, r + 48}.
-// Weights enter the value product as bf16 pairs hi + lo (two MFMAs): they carry
-// 16 significant bits, so no row, however few keys carry it, is limited by the
-// weight rounding.  16-byte chunks of a cache row are rotated by the row index
-// inside LDS (slot = (chunk + row) mod chunks per row) so that reads of one
-// column over 16 rows spread over the banks; each lane of a load fetches the
-// chunk whose rotated home is its slot.
+// Weights are taken relative to a lazily moved reference, rounded to bf16 and
+// normalised by the sum of the rounded weights (a ones-valued MFMA); a tile in
+// which one weight holds more than a quarter of its row's running sum gets a
+// second pass with the rounding residuals, so no row, however few keys carry
+// it, is limited by the weight rounding.  16-byte chunks of a cache row are
+// rotated by the row index inside LDS (slot = (chunk + row) mod chunks per row)
+// so that reads of one column over 16 rows spread over the banks; each lane of
+// a load fetches the chunk whose rotated home is its slot.
 //
-// Partial results of the key ranges use the layout of the generic kernel
-// ([range][row][d_v] fp32 + log-sum-exp) and are merged by generic_combine_kernel.
+// A sequence that one chunk holds entirely is written directly.  Otherwise each
+// chunk leaves its piece (16 rows x d_v fp32, normalised, + log-sum-exp) in one
+// of its two slots, the waves holding a sequence's first and last piece note
+// their chunk numbers, and flex_combine_kernel merges the pieces.
 #pragma once
 
 #include "common.hpp"
@@ -128,65 +136,35 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
   const unsigned ring_addr =
       (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + (unsigned)(wave * (NST * STAGE));
 
-  // ---- this wave's unit: groups fastest, so the waves of a workgroup fetch the
-  //      SAME shared RoPE-key rows at about the same time (one trip to HBM for all of them)
+  // ---- this wave's share of the work.  A "strand" is one (group block, block of 16 query rows); every
+  //      strand walks the same flat list of key tiles (all tiles of sequence 0, of sequence 1, ...), cut
+  //      into num_chunks equal chunks, one wave per (chunk, strand): ragged batches balance by
+  //      construction.  Strands are numbered fastest, group blocks first, so the waves of a workgroup
+  //      fetch the SAME shared RoPE-key rows at about the same time (one trip to HBM for all of them).
   const int rows_group = p.g_q * p.T;
-  const int RBK = p.flex_rb;            // blocks of 16 rows per group (GPW == 2: one)
-  const unsigned HB = (unsigned)p.h_c / GPW;  // group blocks
+  const unsigned HB = (unsigned)p.h_c / GPW;             // group blocks
+  const unsigned NSTR = HB * (unsigned)p.flex_rb;        // strands
   const unsigned unit = blockIdx.x * 4u + (unsigned)wave;  // (the host keeps the number of waves below 2^31)
-  if (unit >= (unsigned)p.B * HB * (unsigned)RBK * (unsigned)p.splits) return;
-  const unsigned u1 = unit / HB, u2 = u1 / (unsigned)p.splits;
-  const int g0 = (int)(unit - u1 * HB) * GPW;  // first group of this wave
-  const int s = (int)(u1 - u2 * (unsigned)p.splits);
-  const int b = (int)(u2 / (unsigned)RBK);
-  const int rb = (int)(u2 - (unsigned)b * (unsigned)RBK);
-  const int L = uniform(p.seq_lens[b]);
-  const int tiles_b = L > 0 ? (L + 31) >> 5 : 0;
-  const int t0 = min(s * p.pages_per_split, tiles_b);  // (for this kernel: tiles per range)
-  const int t1 = min(t0 + p.pages_per_split, tiles_b);
-  const int n_t = t1 - t0;
+  if (unit >= NSTR * (unsigned)p.num_chunks) return;
+  const int chunk = (int)(unit / NSTR);
+  const int strand = (int)(unit - (unsigned)chunk * NSTR);
+  const int rb = (int)((unsigned)strand / HB);
+  const int g0 = (strand - rb * (int)HB) * GPW;  // first group of this wave
+  const int L_first = lane < p.B ? p.seq_lens[lane] : 0;
+  const int incl0 = wave_incl_scan(tiles_of<32>(L_first));
+  const int total = total_tiles<32>(p, 1, lane, incl0);
+  const int C = p.chunk_tiles > 0 ? p.chunk_tiles : max(1, (int)(((unsigned)total + (unsigned)p.num_chunks - 1) / (unsigned)p.num_chunks));
+  const int pos0 = chunk * C;  // (the host keeps num_chunks * max tiles per chunk below 2^31)
+  if (pos0 >= total) return;
+  int left = min(C, total - pos0);  // tiles of this chunk not yet worked on
 
-  // ---- the query row of this lane (rows past the end of the group repeat the last one, never stored)
+  // ---- the query row of this lane within its group (rows past the end repeat the last one, never stored)
   const int jg = GPW == 2 ? r16 >> 3 : 0;                  // which of the wave's groups the row belongs to
   const int R = GPW == 2 ? (r16 & 7) : rb * 16 + r16;      // row within the group
   const bool row_valid = R < rows_group;
   const int Rc = row_valid ? R : rows_group - 1;
   const int t = Rc / p.g_q;
   const int h = (g0 + jg) * p.g_q + (Rc - t * p.g_q);
-  const int n_vis = p.causal ? L - p.T + 1 + t : L;
-  const int n_vis_min = uniform(n_vis);  // lane 0 holds the block's first row, which sees the fewest keys
-  const int64_t row_idx = ((int64_t)b * p.T + t) * p.h_q + h;
-
-  // ---- query fragments: B operand of the score MFMAs, dims 16 * ks + 4 * q .. + 3 of row r16; the
-  //      non-RoPE part once per group of the wave, zero in the rows of the other group
-  u32x2_t qn[GPW][NKN], qr[NKR > 0 ? NKR : 1];
-  {
-    const uint16_t* src = p.q_nope + b * p.qn_s[0] + t * p.qn_s[1] + h * p.qn_s[2] + 4 * q;
-#pragma unroll
-    for (int ks = 0; ks < NKN; ++ks) {
-      const u32x2_t v = *reinterpret_cast<const u32x2_t*>(src + 16 * ks);
-#pragma unroll
-      for (int j = 0; j < GPW; ++j) qn[j][ks] = (GPW == 1 || jg == j) ? v : u32x2_t{0u, 0u};
-    }
-    if constexpr (NKR > 0) {
-      const uint16_t* srcr = p.q_rope + b * p.qr_s[0] + t * p.qr_s[1] + h * p.qr_s[2] + 4 * q;
-#pragma unroll
-      for (int ks = 0; ks < NKR; ++ks) qr[ks] = *reinterpret_cast<const u32x2_t*>(srcr + 16 * ks);
-    }
-  }
-
-  // ---- page ids of this wave's key range: 64 at a time, one per lane
-  const int lgP = p.lg_page;             // page size is a power of two of at least 32 tokens
-  const int tpp_lg = lgP - 5;            // log2(tiles per page)
-  int pt_base = -1, pt_vec = 0;
-  auto page_of_tile = [&](int tile) -> int {
-    const int pg = tile >> tpp_lg;
-    if (pt_base < 0 || pg < pt_base || pg >= pt_base + 64) {
-      pt_base = pg;
-      pt_vec = load_i32_sync(p.page_table + (int64_t)b * p.max_pages + min(pg + lane, p.max_pages - 1));
-    }
-    return __builtin_amdgcn_readlane(pt_vec, pg - pt_base);
-  };
 
   // ---- tile loads.  A tile of 32 rows of LPR 16-byte chunks is 32 * LPR consecutive LDS slots, 64 per
   //      load instruction (LPR is even: every instruction is full).  Slot n belongs to row n / LPR and holds
@@ -200,9 +178,9 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
 #pragma unroll
     for (int j = 0; j < LPR / 2; ++j) {
       const int n = j * 64 + lane, row = n / LPR, slot = n % LPR;
-      int chunk = slot - row % LPR;
-      chunk += chunk < 0 ? LPR : 0;
-      goff[j] = (unsigned)(row * RBY + chunk * 16);
+      int chunk_i = slot - row % LPR;
+      chunk_i += chunk_i < 0 ? LPR : 0;
+      goff[j] = (unsigned)(row * RBY + chunk_i * 16);
     }
   };
   lane_offsets(std::integral_constant<int, VB>{}, goff_v);
@@ -211,28 +189,49 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
   const unsigned char* const state_b = (const unsigned char*)(p.state + g0 * p.st_s[1]);
   const unsigned char* const key_b = SEPK ? (const unsigned char*)(p.kstate + g0 * p.k_s[1]) : nullptr;
   const unsigned char* const rope_b = (const unsigned char*)p.rope;
-  auto issue_tile = [&](int tile, int stage) {
-    const int64_t page = page_of_tile(tile);
-    const int tok = (tile << 5) & ((1 << lgP) - 1);  // first token of the tile inside its page
+
+  // ---- two cursors over the chunk: `cur`, the tile being worked on, and `pre`, NST - 1 tiles ahead,
+  //      the tile being fetched (it crosses into the next sequence without the ring running dry)
+  TileCursor cur = locate_tile<32>(p, 1, pos0, lane, L_first, incl0);
+  TileCursor pre = cur;
+  int pre_left = left;
+  const int lgP = p.lg_page;             // page size is a power of two of at least 32 tokens
+  const int tpp_lg = lgP - 5;            // log2(tiles per page)
+  int pt_b = -1, pt_base = 0, pt_vec = 0;  // 64 page ids of sequence pt_b from page pt_base on, one per lane
+  const unsigned char *src_v = state_b, *src_k = key_b, *src_r = rope_b;
+  // fetch the tile at `pre` into a stage and step `pre`; past the end of the chunk: the last tile again
+  // (keeps the count of loads in flight the same in every iteration)
+  auto issue_next = [&](int stage) {
+    if (pre_left > 0) {
+      const int pg = pre.j >> tpp_lg;
+      if (pre.b != pt_b || pg < pt_base || pg >= pt_base + 64) {
+        pt_b = pre.b;
+        pt_base = pg;
+        pt_vec = load_i32_sync(p.page_table + (int64_t)pre.b * p.max_pages + min(pg + lane, p.max_pages - 1));
+      }
+      const int64_t page = __builtin_amdgcn_readlane(pt_vec, pg - pt_base);
+      const int tok = (pre.j << 5) & ((1 << lgP) - 1);  // first token of the tile inside its page
+      src_v = state_b + (page * p.st_s[0] + (int64_t)tok * DV) * 2;
+      if constexpr (SEPK) src_k = key_b + (page * p.k_s[0] + (int64_t)tok * DN) * 2;
+      if constexpr (DR > 0) src_r = rope_b + (page * p.rp_s[0] + (int64_t)tok * DR) * 2;
+      if (--pre_left > 0) advance<32>(p, 1, pre);
+    }
     unsigned char* dst = smem + wave * (NST * STAGE) + stage * STAGE;
-    const unsigned char* v = state_b + (page * p.st_s[0] + (int64_t)tok * DV) * 2;
 #pragma unroll
     for (int j = 0; j < GPW; ++j)
 #pragma unroll
       for (int i = 0; i < NLV; ++i)
-        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(v + j * p.st_s[1] * 2 + goff_v[i]),
+        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_v + j * p.st_s[1] * 2 + goff_v[i]),
                                          (lds_void_t*)(dst + j * 32 * VB + i * 1024), 16, 0, 0);
     if constexpr (SEPK) {
-      const unsigned char* k = key_b + (page * p.k_s[0] + (int64_t)tok * DN) * 2;
 #pragma unroll
       for (int j = 0; j < NLK; ++j)
-        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(k + goff_k[j]), (lds_void_t*)(dst + OFF_K + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_k + goff_k[j]), (lds_void_t*)(dst + OFF_K + j * 1024), 16, 0, 0);
     }
     if constexpr (DR > 0) {
-      const unsigned char* rp = rope_b + (page * p.rp_s[0] + (int64_t)tok * DR) * 2;
 #pragma unroll
       for (int j = 0; j < NLR; ++j)
-        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(rp + goff_r[j]), (lds_void_t*)(dst + OFF_R + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_r + goff_r[j]), (lds_void_t*)(dst + OFF_R + j * 1024), 16, 0, 0);
     }
   };
 
@@ -270,19 +269,12 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
       }
   }
 
-  // ---- per-row state.  Weights are taken relative to a reference m_ref (log2 domain, the same in the four
-  //      lanes of a row) that is moved up only when a score exceeds it by more than kRebase: most tiles
-  //      need no cross-lane traffic and no rescaling.  m_ref starts finite so that a masked score
-  //      (-inf) gives weight exp2(-inf) = 0 and never inf - inf.
   constexpr float kRebase = 8.f;
   constexpr float kLogHeavyShare = -2.f;  // a weight above a quarter of its row's running sum gets its rounding residual added
-  f32x4_t o[GPW * NDB], o_one = {0.f, 0.f, 0.f, 0.f};  // o_one: row sum of the weights as the MFMAs saw them (bf16-rounded)
-#pragma unroll
-  for (int db = 0; db < GPW * NDB; ++db) o[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  float m_ref = -1e30f, l_run = 0.f;  // l_run: this lane's share of the exact fp32 row sum
-  float heavy_thr = -INFINITY;        // refreshed lazily; the running sum only grows, so a stale value errs on the safe side
   const float sc2 = p.scale * 1.4426950408889634f;
-  const u32x2_t ones = {0x3f803f80u, 0x3f803f80u};  // four bf16 ones
+  u32x2_t ones = {0x3f803f80u, 0x3f803f80u};  // four bf16 ones
+  flex_tie(ones);  // (opaque from here on: a constant would be re-created by a vector move right in front of the MFMA that reads it)
+  f32x4_t o[GPW * NDB], o_one;  // o_one: row sum of the weights as the MFMAs saw them (bf16-rounded)
 
   // value MFMAs of one pass over the tile: every group's accumulators against that group's values
   auto value_mfmas = [&](u32x2_t (&vf)[2 * GPW * NDB], const u32x2_t (&pb)[2]) {
@@ -291,155 +283,289 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
       flex_mfma_fresh(o[0], vf[kb * GPW * NDB], pb[kb]);
 #pragma unroll
       for (int d = 1; d < GPW * NDB; ++d) flex_mfma(o[d], vf[kb * GPW * NDB + d], pb[kb]);
-      flex_mfma(o_one, ones, pb[kb]);
+      flex_mfma_fresh(o_one, ones, pb[kb]);
     }
   };
-
-  if (n_t > 0) {
-#pragma unroll
-    for (int st = 0; st < NST - 1; ++st) issue_tile(t0 + min(st, n_t - 1), st);  // (tiles past the end: the last one again)
-  }
-  int st_cur = 0, st_load = NST - 1;
-  for (int i = 0; i < n_t; ++i) {
-    issue_tile(t0 + min(i + NST - 1, n_t - 1), st_load);
-    st_load = st_load == NST - 1 ? 0 : st_load + 1;
-    wait_vmcnt<LPT * (NST - 1)>();  // all but the NST - 1 newest tiles have landed: tile i is in LDS
-    const int tile = t0 + i;
-    const unsigned st_addr = ring_addr + (unsigned)(st_cur * STAGE);
-    st_cur = st_cur == NST - 1 ? 0 : st_cur + 1;
-    // value rows at or past the end of the sequence may hold anything: zero them (weight 0 x NaN must not leak)
-    if ((tile << 5) + 32 > L) {
-      const int valid = L - (tile << 5);
-#pragma unroll
-      for (int j = 0; j < GPW; ++j)
-        for (int off = valid * VB + lane * 16; off < 32 * VB; off += 64 * 16) flex_lds_zero_b128(st_addr + j * 32 * VB + off);
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    }
-
-    // ---- scores of the two 16-key blocks: S^T[key 4q + i][row r16]
-    u32x2_t kf[2 * NKF];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int ks = 0; ks < NKF; ++ks) flex_lds_read_b64(kf[kb * NKF + ks], st_addr + koff[kb][ks]);
-    flex_lds_wait_all(kf);
-    f32x4_t sc[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) flex_mfma0(sc[kb], kf[kb * NKF], qn[0][0]);
-    static_for<1, NKF>([&](auto ksc) {
-      constexpr int ks = decltype(ksc)::value;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        if constexpr (ks < GPW * NKN)
-          flex_mfma(sc[kb], kf[kb * NKF + ks], qn[ks / NKN][ks % NKN]);
-        else
-          flex_mfma(sc[kb], kf[kb * NKF + ks], qr[ks - GPW * NKN]);
-      }
-    });
-    flex_mfma_settle(sc[0], sc[1]);
-    // ---- mask by select (last tiles only), then this lane's largest score
-    if ((tile << 5) + 32 > n_vis_min) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          sc[kb][e] = (tile << 5) + 16 * kb + 4 * q + e < n_vis ? sc[kb][e] : -INFINITY;
-    }
-    const float mx = flex_max3(flex_max3(flex_max3(sc[0][0], sc[0][1], sc[0][2]), sc[0][3], sc[1][0]),
-                               flex_max3(sc[1][1], sc[1][2], sc[1][3]), -INFINITY);
-    float lg = __builtin_fmaf(mx, sc2, -m_ref);  // log2 of this lane's largest weight
-    if (__ballot(lg > kRebase) != 0) {
-      flex_mfma_settle(o, o_one);  // (the value MFMAs of the tile before may still be on their way)
-      float mrow = mx * sc2;
-      mrow = fmaxf(mrow, __shfl_xor(mrow, 16, 64));
-      mrow = fmaxf(mrow, __shfl_xor(mrow, 32, 64));
-      const float m_new = fmaxf(m_ref, mrow);
-      const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
-      m_ref = m_new;
-      l_run *= alpha;
-      o_one *= alpha;
-#pragma unroll
-      for (int db = 0; db < GPW * NDB; ++db) o[db] *= alpha;
-      heavy_thr = -INFINITY;
-      lg = __builtin_fmaf(mx, sc2, -m_ref);
-    }
-    // ---- value operands on their way while the weights are computed
-    u32x2_t vf[2 * GPW * NDB];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int d = 0; d < GPW * NDB; ++d) flex_lds_read_tr(vf[kb * GPW * NDB + d], st_addr + voff[kb][d]);
-    asm volatile("" : "+v"(sc[0]), "+v"(sc[1]));  // (keeps the reads above ahead of the arithmetic below)
-    float pw[8], psum = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      pw[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e >> 2][e & 3], sc2, -m_ref));
-      psum += pw[e];
-    }
-    l_run += psum;
-    u32x2_t p_hi[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e2 = 0; e2 < 2; ++e2) p_hi[kb][e2] = cvt_pk_bf16(pw[4 * kb + 2 * e2], pw[4 * kb + 2 * e2 + 1]);
-    flex_lds_wait_all(vf);
-    // ---- O^T += V^T . P^T, and the row sums of the rounded weights through a ones-valued operand
-    value_mfmas(vf, p_hi);
-    // ---- rows that put much of their weight on one key of this tile: add the rounding residuals
-    //      p - bf16(p) (as bf16) in a second pass, so those weights carry 16 significant bits
-    if (__builtin_expect(__ballot(lg > heavy_thr) != 0, 0)) {
-      float l_row = l_run + __shfl_xor(l_run, 16, 64);
-      l_row += __shfl_xor(l_row, 32, 64);
-      heavy_thr = __builtin_amdgcn_logf(l_row) + kLogHeavyShare;
-      if (__ballot(lg > heavy_thr) != 0) {
-        u32x2_t p_lo[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int e2 = 0; e2 < 2; ++e2) {
-            const float a0 = pw[4 * kb + 2 * e2], a1 = pw[4 * kb + 2 * e2 + 1];
-            const uint32_t hi = p_hi[kb][e2];
-            p_lo[kb][e2] = cvt_pk_bf16(a0 - __builtin_bit_cast(float, hi << 16), a1 - __builtin_bit_cast(float, hi & 0xffff0000u));
-          }
-        value_mfmas(vf, p_lo);
-      }
-    }
-  }
-  wait_vmcnt<0>();  // (tiles fetched again past the end of the range: let them land before the wave leaves)
-  flex_mfma_settle(o, o_one);
   auto own = [&](int db) -> f32x4_t {  // the accumulators of this lane's own group
     if constexpr (GPW == 2) return jg ? o[NDB + db] : o[db];
     else return o[db];
   };
 
-  // ---- result of this key range: O^T[dim 16 * db + 4q + i][row r16]
-  float l_tot = l_run + __shfl_xor(l_run, 16, 64);
-  l_tot += __shfl_xor(l_tot, 32, 64);
-  const float inv = o_one[0] > 0.f ? 1.f / o_one[0] : 0.f;
-  const float lse = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
-  if (!row_valid) return;
-  if (p.splits == 1) {
-    if (q == 0) p.lse[row_idx] = lse;
-    const int64_t ob = b * p.out_s[0] + t * p.out_s[1] + h * p.out_s[2];
 #pragma unroll
-    for (int db = 0; db < NDB; ++db) {
-      const int dim = 16 * db + 4 * q;
-      const f32x4_t v = own(db) * inv;
-      if (p.out_fp32) {
-        *(f32x4_t*)((float*)p.out + ob + dim) = v;
-      } else {
-        u32x2_t pk;
-        pk[0] = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
-        pk[1] = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
-        *(u32x2_t*)((uint16_t*)p.out + ob + dim) = pk;
+  for (int st = 0; st < NST - 1; ++st) issue_next(st);
+  int st_cur = 0, st_load = NST - 1;
+  bool first_segment = true;
+
+  // ---- one segment per sequence that the chunk touches
+  while (left > 0) {
+    const int b = cur.b, L = cur.L, j0 = cur.j;
+    const int seg = min(cur.tiles_b - j0, left);
+    if (seg <= 0) break;  // (cannot happen while the lengths stay what they were when the chunk was located)
+    const int n_vis = p.causal ? L - p.T + 1 + t : L;
+    const int n_vis_min = uniform(n_vis);  // lane 0 holds the block's first row, which sees the fewest keys
+    const int64_t row_idx = ((int64_t)b * p.T + t) * p.h_q + h;
+
+    // query fragments: B operand of the score MFMAs, dims 16 * ks + 4 * q .. + 3 of row r16; the
+    // non-RoPE part once per group of the wave, zero in the rows of the other group
+    u32x2_t qn[GPW][NKN], qr[NKR > 0 ? NKR : 1];
+    {
+      const uint16_t* src = p.q_nope + b * p.qn_s[0] + t * p.qn_s[1] + h * p.qn_s[2] + 4 * q;
+#pragma unroll
+      for (int ks = 0; ks < NKN; ++ks) {
+        const u32x2_t v = *reinterpret_cast<const u32x2_t*>(src + 16 * ks);
+#pragma unroll
+        for (int j = 0; j < GPW; ++j) qn[j][ks] = (GPW == 1 || jg == j) ? v : u32x2_t{0u, 0u};
+      }
+      if constexpr (NKR > 0) {
+        const uint16_t* srcr = p.q_rope + b * p.qr_s[0] + t * p.qr_s[1] + h * p.qr_s[2] + 4 * q;
+#pragma unroll
+        for (int ks = 0; ks < NKR; ++ks) qr[ks] = *reinterpret_cast<const u32x2_t*>(srcr + 16 * ks);
+      }
+      // (pinned here: nothing that produces these operands may move down to the MFMAs that read them)
+#pragma unroll
+      for (int j = 0; j < GPW; ++j)
+#pragma unroll
+        for (int ks = 0; ks < NKN; ++ks) flex_tie(qn[j][ks]);
+#pragma unroll
+      for (int ks = 0; ks < NKR; ++ks) flex_tie(qr[ks]);
+    }
+
+    // per-row state.  Weights are taken relative to a reference m_ref (log2 domain, the same in the four
+    // lanes of a row) that is moved up only when a score exceeds it by more than kRebase: most tiles
+    // need no cross-lane traffic and no rescaling.  m_ref starts finite so that a masked score
+    // (-inf) gives weight exp2(-inf) = 0 and never inf - inf.
+    o_one = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int db = 0; db < GPW * NDB; ++db) o[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m_ref = -1e30f, l_run = 0.f;  // l_run: this lane's share of the exact fp32 row sum
+    float heavy_thr = -INFINITY;        // refreshed lazily; the running sum only grows, so a stale value errs on the safe side
+
+    for (int i = 0; i < seg; ++i) {
+      issue_next(st_load);
+      st_load = st_load == NST - 1 ? 0 : st_load + 1;
+      wait_vmcnt<LPT * (NST - 1)>();  // all but the NST - 1 newest tiles have landed: this tile is in LDS
+      const int tile = j0 + i;
+      const unsigned st_addr = ring_addr + (unsigned)(st_cur * STAGE);
+      st_cur = st_cur == NST - 1 ? 0 : st_cur + 1;
+      // value rows at or past the end of the sequence may hold anything: zero them (weight 0 x NaN must not leak)
+      if ((tile << 5) + 32 > L) {
+        const int valid = L - (tile << 5);
+#pragma unroll
+        for (int j = 0; j < GPW; ++j)
+          for (int off = valid * VB + lane * 16; off < 32 * VB; off += 64 * 16) flex_lds_zero_b128(st_addr + j * 32 * VB + off);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      }
+
+      // ---- scores of the two 16-key blocks: S^T[key 4q + i][row r16]
+      u32x2_t kf[2 * NKF];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int ks = 0; ks < NKF; ++ks) flex_lds_read_b64(kf[kb * NKF + ks], st_addr + koff[kb][ks]);
+      flex_lds_wait_all(kf);
+      f32x4_t sc[2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) flex_mfma0(sc[kb], kf[kb * NKF], qn[0][0]);
+      static_for<1, NKF>([&](auto ksc) {
+        constexpr int ks = decltype(ksc)::value;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          if constexpr (ks < GPW * NKN)
+            flex_mfma(sc[kb], kf[kb * NKF + ks], qn[ks / NKN][ks % NKN]);
+          else
+            flex_mfma(sc[kb], kf[kb * NKF + ks], qr[ks - GPW * NKN]);
+        }
+      });
+      flex_mfma_settle(sc[0], sc[1]);
+      // ---- mask by select (last tiles only), then this lane's largest score
+      if ((tile << 5) + 32 > n_vis_min) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            sc[kb][e] = (tile << 5) + 16 * kb + 4 * q + e < n_vis ? sc[kb][e] : -INFINITY;
+      }
+      const float mx = flex_max3(flex_max3(flex_max3(sc[0][0], sc[0][1], sc[0][2]), sc[0][3], sc[1][0]),
+                                 flex_max3(sc[1][1], sc[1][2], sc[1][3]), -INFINITY);
+      float lg = __builtin_fmaf(mx, sc2, -m_ref);  // log2 of this lane's largest weight
+      if (__ballot(lg > kRebase) != 0) {
+        flex_mfma_settle(o, o_one);  // (the value MFMAs of the tile before may still be on their way)
+        float mrow = mx * sc2;
+        mrow = fmaxf(mrow, __shfl_xor(mrow, 16, 64));
+        mrow = fmaxf(mrow, __shfl_xor(mrow, 32, 64));
+        const float m_new = fmaxf(m_ref, mrow);
+        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+        m_ref = m_new;
+        l_run *= alpha;
+        o_one *= alpha;
+#pragma unroll
+        for (int db = 0; db < GPW * NDB; ++db) o[db] *= alpha;
+        heavy_thr = -INFINITY;
+        lg = __builtin_fmaf(mx, sc2, -m_ref);
+      }
+      // ---- value operands on their way while the weights are computed
+      u32x2_t vf[2 * GPW * NDB];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int d = 0; d < GPW * NDB; ++d) flex_lds_read_tr(vf[kb * GPW * NDB + d], st_addr + voff[kb][d]);
+      asm volatile("" : "+v"(sc[0]), "+v"(sc[1]));  // (keeps the reads above ahead of the arithmetic below)
+      float pw[8], psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        pw[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e >> 2][e & 3], sc2, -m_ref));
+        psum += pw[e];
+      }
+      l_run += psum;
+      u32x2_t p_hi[2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int e2 = 0; e2 < 2; ++e2) p_hi[kb][e2] = cvt_pk_bf16(pw[4 * kb + 2 * e2], pw[4 * kb + 2 * e2 + 1]);
+      flex_lds_wait_all(vf);
+      // ---- O^T += V^T . P^T, and the row sums of the rounded weights through a ones-valued operand
+      value_mfmas(vf, p_hi);
+      // ---- rows that put much of their weight on one key of this tile: add the rounding residuals
+      //      p - bf16(p) (as bf16) in a second pass, so those weights carry 16 significant bits
+      if (__builtin_expect(__ballot(lg > heavy_thr) != 0, 0)) {
+        float l_row = l_run + __shfl_xor(l_run, 16, 64);
+        l_row += __shfl_xor(l_row, 32, 64);
+        heavy_thr = __builtin_amdgcn_logf(l_row) + kLogHeavyShare;
+        if (__ballot(lg > heavy_thr) != 0) {
+          u32x2_t p_lo[2];
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int e2 = 0; e2 < 2; ++e2) {
+              const float a0 = pw[4 * kb + 2 * e2], a1 = pw[4 * kb + 2 * e2 + 1];
+              const uint32_t hi = p_hi[kb][e2];
+              p_lo[kb][e2] = cvt_pk_bf16(a0 - __builtin_bit_cast(float, hi << 16), a1 - __builtin_bit_cast(float, hi & 0xffff0000u));
+            }
+          value_mfmas(vf, p_lo);
+        }
       }
     }
-  } else {
-    const int64_t rows = (int64_t)p.B * p.T * p.h_q;
-    if (q == 0) p.ws_lse[(int64_t)s * rows + row_idx] = lse;
-    float* dst = p.ws_out + ((int64_t)s * rows + row_idx) * DV;
+    flex_mfma_settle(o, o_one);
+
+    // ---- result of this segment: O^T[dim 16 * db + 4q + i][row r16]
+    float l_tot = l_run + __shfl_xor(l_run, 16, 64);
+    l_tot += __shfl_xor(l_tot, 32, 64);
+    const float inv = o_one[0] > 0.f ? 1.f / o_one[0] : 0.f;
+    const float lse = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
+    const bool whole = j0 == 0 && seg == cur.tiles_b;
+    if (whole) {
+      if (row_valid) {
+        if (q == 0) p.lse[row_idx] = lse;
+        const int64_t ob = b * p.out_s[0] + t * p.out_s[1] + h * p.out_s[2];
 #pragma unroll
-    for (int db = 0; db < NDB; ++db) *(f32x4_t*)(dst + 16 * db + 4 * q) = own(db) * inv;
+        for (int db = 0; db < NDB; ++db) {
+          const int dim = 16 * db + 4 * q;
+          const f32x4_t v = own(db) * inv;
+          if (p.out_fp32) {
+            *(f32x4_t*)((float*)p.out + ob + dim) = v;
+          } else {
+            u32x2_t pk;
+            pk[0] = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
+            pk[1] = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
+            *(u32x2_t*)((uint16_t*)p.out + ob + dim) = pk;
+          }
+        }
+      }
+    } else {
+      // a piece of a sequence that other chunks share: slot 0 of this (chunk, strand) for the segment the
+      // chunk begins with, slot 1 for a later one (only the chunk's last segment can be such a piece)
+      const int64_t slot = ((int64_t)unit * 2 + (first_segment ? 0 : 1)) * 16 + r16;
+      if (row_valid) {
+        if (q == 0) p.ws_lse[slot] = lse;
+        float* dst = p.ws_out + slot * DV;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) *(f32x4_t*)(dst + 16 * db + 4 * q) = own(db) * inv;
+      }
+    }
+    // which chunks hold the pieces of (sequence, strand): the first one with its slot, and the last one
+    if (lane == 0) {
+      int32_t* rng = p.flex_rng + ((int64_t)b * NSTR + strand) * 2;
+      if (j0 == 0) rng[0] = chunk * 2 + (first_segment ? 0 : 1);
+      if (j0 + seg == cur.tiles_b) rng[1] = chunk;
+    }
+    left -= seg;
+    first_segment = false;
+    if (left > 0) {
+      cur.j = j0 + seg - 1;
+      advance<32>(p, 1, cur);
+    }
+  }
+  wait_vmcnt<0>();  // (tiles fetched again past the end of the chunk: let them land before the wave leaves)
+}
+
+// Merge of the pieces of the rows whose sequence was cut between chunks: one wave per output row.
+// Rows of sequences that one chunk held entirely were written by the main kernel; empty sequences
+// are filled here (out = 0, lse = -inf).
+template <int GPW>
+__global__ __launch_bounds__(64) void flex_combine_kernel(DevParams p) {
+  const int row = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int h = row % p.h_q;
+  const int t = (row / p.h_q) % p.T;
+  const int b = row / (p.h_q * p.T);
+  const int64_t base = b * p.out_s[0] + t * p.out_s[1] + h * p.out_s[2];
+  const int L = p.seq_lens[b];
+  if (L <= 0) {
+    if (lane == 0) p.lse[row] = -INFINITY;
+    for (int d = lane; d < p.d_v; d += 64) {
+      if (p.out_fp32) ((float*)p.out)[base + d] = 0.f;
+      else ((uint16_t*)p.out)[base + d] = 0;
+    }
+    return;
+  }
+  const int g = h / p.g_q;
+  const int lr = t * p.g_q + (h - g * p.g_q);  // row within the group
+  const int HB = p.h_c / GPW, NSTR = HB * p.flex_rb;
+  const int strand = GPW == 2 ? g / 2 : (lr / 16) * HB + g;
+  const int r16 = GPW == 2 ? (g % 2) * 8 + lr : lr % 16;
+  const int32_t* rng = p.flex_rng + ((int64_t)b * NSTR + strand) * 2;
+  const int c_first = rng[0] >> 1, slot_first = rng[0] & 1, c_last = rng[1];
+  if (c_first == c_last) return;  // one chunk held the whole sequence: written by the main kernel
+  auto slot_of = [&](int c) -> int64_t {
+    return (((int64_t)c * NSTR + strand) * 2 + (c == c_first ? slot_first : 0)) * 16 + r16;
+  };
+  float m = -INFINITY;
+  for (int c = c_first + lane; c <= c_last; c += 64) m = fmaxf(m, p.ws_lse[slot_of(c)]);
+  for (int sh = 32; sh > 0; sh >>= 1) m = fmaxf(m, __shfl_xor(m, sh, 64));
+  float z = 0.f;
+  if (m != -INFINITY)
+    for (int c = c_first + lane; c <= c_last; c += 64) z += expf(p.ws_lse[slot_of(c)] - m);
+  for (int sh = 32; sh > 0; sh >>= 1) z += __shfl_xor(z, sh, 64);
+  const float lse = (m == -INFINITY) ? -INFINITY : m + logf(z);
+  if (lane == 0) p.lse[row] = lse;
+  // four dims per lane; the lanes left over take every pgs-th piece each, summed at the end
+  const int nd4 = p.d_v / 4, pgs = 64 / nd4;
+  const int pg = lane / nd4, d4 = lane - pg * nd4;
+  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+  if (m != -INFINITY && pg < pgs) {
+    for (int c = c_first + pg; c <= c_last; c += pgs) {
+      const int64_t sl = slot_of(c);
+      const float ls = p.ws_lse[sl];
+      if (ls != -INFINITY) acc += *(const f32x4_t*)(p.ws_out + sl * p.d_v + 4 * d4) * expf(ls - lse);
+    }
+  }
+  for (int g = 1; g < pgs; ++g) {
+    const int src = d4 + g * nd4;  // (the same for every lane of a piece group; lanes of group 0 keep the sum)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float v = __shfl(acc[e], src & 63, 64);
+      if (pg == 0) acc[e] += v;
+    }
+  }
+  if (pg == 0) {
+    if (p.out_fp32) {
+      *(f32x4_t*)((float*)p.out + base + 4 * d4) = acc;
+    } else {
+      u32x2_t pk;
+      pk[0] = (uint32_t)f32_to_bf16_bits(acc[0]) | ((uint32_t)f32_to_bf16_bits(acc[1]) << 16);
+      pk[1] = (uint32_t)f32_to_bf16_bits(acc[2]) | ((uint32_t)f32_to_bf16_bits(acc[3]) << 16);
+      *(u32x2_t*)((uint16_t*)p.out + base + 4 * d4) = pk;
+    }
   }
 }
 

@@ -54,12 +54,14 @@ int check_shape(const gla_decode_params* p, int is_gta) {
 
 bool generic_supported(const gla_decode_params* p) { return p->d_v <= 1024 && p->d_nope <= 1024 && p->d_rope <= 128; }
 
-// ---- flex kernel (flex_kernels.hpp): which instantiation, how many key ranges
+// ---- flex kernel (flex_kernels.hpp): which instantiation, how the key tiles are cut into chunks
 struct FlexPlan {
-  int id;       // index into the instantiation list below, -1: none
-  int gpw;      // groups per wave (2: two groups of at most eight rows share a wave's 16 rows)
-  int rb;       // blocks of 16 rows per group
-  int splits, tiles_per_split;
+  int id;           // index into the instantiation list below, -1: none
+  int gpw;          // groups per wave (2: two groups of at most eight rows share a wave's 16 rows)
+  int rb;           // blocks of 16 rows per group
+  int strands;      // (group block, row block) pairs: each walks the whole tile list
+  int chunks;       // chunks of the tile list (one wave per chunk and strand)
+  int chunk_tiles;  // > 0: fixed tiles per chunk; 0: ceil(total / chunks), worked out on the device
 };
 
 int flex_variant(const gla_decode_params* p, int mode) {
@@ -96,28 +98,31 @@ bool flex_plan(const gla_decode_params* p, int mode, const KeyCache* kc, FlexPla
   const int rows_group = (p->num_q_heads / p->num_groups) * p->q_len;
   plan->rb = (rows_group + 15) / 16;
   plan->gpw = (plan->id == 2 && rows_group <= 8 && p->num_groups % 2 == 0) ? 2 : 1;
-  const int64_t units = (int64_t)p->batch * (p->num_groups / plan->gpw) * plan->rb;
+  plan->strands = (p->num_groups / plan->gpw) * plan->rb;
+  // the tile list holds every sequence once; its length is known on the device only, here its upper bound
   const int64_t max_tiles = std::max<int64_t>(1, ((int64_t)p->max_pages_per_seq * ps + 31) / 32);
-  int64_t sp;
+  const int64_t bound = (int64_t)p->batch * max_tiles;
+  int64_t chunks;
   if (p->num_splits > 0) {
-    sp = p->num_splits;
+    plan->chunk_tiles = (int)((max_tiles + p->num_splits - 1) / p->num_splits);
+    chunks = (bound + plan->chunk_tiles - 1) / plan->chunk_tiles;
   } else {
-    // about four waves per compute unit (what is resident at once), ranges of at least eight tiles:
+    // one wave per SIMD (what is resident at once), chunks of at least eight tiles (by the upper bound):
     // a wave's start (lengths, page ids, queries, first tiles) costs several tiles' worth of time
-    sp = (4 * (int64_t)device_cu_count() + units - 1) / std::max<int64_t>(units, 1);
-    sp = std::min<int64_t>(sp, std::max<int64_t>(1, max_tiles / 8));
+    plan->chunk_tiles = 0;
+    chunks = std::min<int64_t>((4 * (int64_t)device_cu_count() + plan->strands - 1) / plan->strands, bound / 8);
   }
-  sp = std::max<int64_t>(1, std::min<int64_t>(sp, std::min<int64_t>(max_tiles, 65535)));
-  plan->tiles_per_split = (int)((max_tiles + sp - 1) / sp);
-  plan->splits = (int)((max_tiles + plan->tiles_per_split - 1) / plan->tiles_per_split);
-  if (units * plan->splits > (int64_t)0x7fffffff) return false;  // (one wave each; the kernel counts them in 32 bits)
+  chunks = std::max<int64_t>(1, chunks);
+  if (chunks * plan->strands > (int64_t)0x3fffffff || bound + chunks > (int64_t)0x7fffffff) return false;
+  plan->chunks = (int)chunks;
   return true;
 }
 
+// Workspace: two partial slots of 16 rows per wave, then per (sequence, strand) the chunks holding its pieces.
+size_t flex_slots(const FlexPlan& plan) { return (size_t)plan.chunks * plan.strands * 2 * 16; }
 size_t flex_workspace(const gla_decode_params* p, const FlexPlan& plan) {
-  if (plan.splits == 1) return 0;
-  const size_t rows = (size_t)p->batch * p->q_len * p->num_q_heads;
-  return align_up((size_t)plan.splits * rows * p->d_v * sizeof(float), 256) + align_up((size_t)plan.splits * rows * sizeof(float), 256);
+  return align_up(flex_slots(plan) * p->d_v * sizeof(float), 256) + align_up(flex_slots(plan) * sizeof(float), 256) +
+         align_up((size_t)p->batch * plan.strands * 2 * sizeof(int32_t), 256);
 }
 
 int generic_splits(const gla_decode_params* p) {
@@ -166,18 +171,22 @@ int check_pointers(const gla_decode_params* p) {
 }
 
 int launch_flex(const gla_decode_params* p, const FlexPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
-  d.splits = plan.splits;
-  d.pages_per_split = plan.tiles_per_split;
+  d.num_chunks = plan.chunks;
+  d.chunk_tiles = plan.chunk_tiles;
   d.flex_rb = plan.rb;
   int lg = 0;
   while ((1 << lg) < p->page_size) ++lg;
   d.lg_page = lg;
   const size_t rows = (size_t)p->batch * p->q_len * p->num_q_heads;
-  if (plan.splits > 1) {
-    d.ws_out = (float*)p->workspace;
-    d.ws_lse = (float*)((char*)p->workspace + align_up((size_t)plan.splits * rows * p->d_v * sizeof(float), 256));
+  {
+    char* w = (char*)p->workspace;
+    d.ws_out = (float*)w;
+    w += align_up(flex_slots(plan) * p->d_v * sizeof(float), 256);
+    d.ws_lse = (float*)w;
+    w += align_up(flex_slots(plan) * sizeof(float), 256);
+    d.flex_rng = (int32_t*)w;
   }
-  const int64_t waves = (int64_t)p->batch * (p->num_groups / plan.gpw) * plan.rb * plan.splits;
+  const int64_t waves = (int64_t)plan.chunks * plan.strands;
   const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
   if (ev) (void)hipEventRecord(ev[0], st);
   switch (plan.id) {
@@ -195,10 +204,12 @@ int launch_flex(const gla_decode_params* p, const FlexPlan& plan, DevParams& d, 
   }
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[1], st);
-  if (plan.splits > 1) {
-    hipLaunchKernelGGL(generic_combine_kernel, dim3((unsigned)rows), dim3(64), 0, st, d);
-    if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
-  }
+  // (always: it also fills the rows of empty sequences, which no chunk holds)
+  if (plan.gpw == 2)
+    hipLaunchKernelGGL(flex_combine_kernel<2>, dim3((unsigned)rows), dim3(64), 0, st, d);
+  else
+    hipLaunchKernelGGL(flex_combine_kernel<1>, dim3((unsigned)rows), dim3(64), 0, st, d);
+  if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[2], st);
   return GLA_OK;
 }

@@ -66,10 +66,31 @@ def test_few_keys_and_peaky_rows(shape):
         check_problem(p, impl=TUNED, what=f"{shape} seed {seed}")
 
 
+@pytest.mark.parametrize("shape,T", [("gta64", 1), ("gta64", 2), ("gta96", 2), ("gqa128", 1)])
+def test_repeat_calls_agree_bit_for_bit(shape, T):
+    """Many short chunks with several sequences each (every chunk starts and ends
+    inside a sequence, residual passes on most tiles): the result must not depend
+    on timing.  The same call twenty times, every result equal to the first one
+    and within tolerance of the oracle."""
+    from gpu_util import run_gpu, compare
+    p = make_problem(f"flex_rep_{shape}", seq_lens=LENS, T=T, page_size=64, num_pages=4096, seed=1707, poison_tail=True,
+                     extra_table_cols=1, **SHAPES[shape])
+    dp = DeviceProblem(p, poison_unused=True)
+    ref_out, ref_lse = oracle.decode_problem(p)
+    first = None
+    for rep in range(20):
+        out, lse = run_gpu(p, dp=dp, out_dtype=torch.float32, impl=TUNED)
+        if first is None:
+            first = (out, lse)
+            compare(out, lse, ref_out, ref_lse, what=f"{shape} T={T}", bf16_out_allowance=False)
+        else:
+            assert np.array_equal(out, first[0]) and np.array_equal(lse, first[1]), f"{shape} T={T}: call {rep} differs from the first"
+
+
 @pytest.mark.parametrize("shape", ["gta64", "gqa128"])
 def test_large_ragged_batch_on_sampled_rows(shape):
     """A ragged batch of the size class of the benchmark's GTA configuration
-    (64 sequences of 1000 to 12000 tokens), the automatic choice of key ranges."""
+    (64 sequences of 1000 to 12000 tokens), the automatic choice of chunks."""
     lens = uniform_lengths(64, 1000, 12000, 77)
     p = make_problem(f"flex_big_{shape}", seq_lens=lens, T=1, num_pages=16384, seed=1400, poison_tail=True, **SHAPES[shape])
     rng = np.random.default_rng(5)
