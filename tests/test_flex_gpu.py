@@ -9,7 +9,7 @@ import torch
 import oracle
 import paper_2505_21487_amd as gla
 from paper_2505_21487_amd.harness import DeviceProblem
-from workloads import make_problem, uniform_lengths
+from workloads import config, make_problem, uniform_lengths
 
 from gpu_util import check_problem
 
@@ -96,6 +96,33 @@ def test_large_ragged_batch_on_sampled_rows(shape):
     rng = np.random.default_rng(5)
     sel = sorted({(int(rng.integers(p.B)), 0, int(rng.integers(p.h_q))) for _ in range(300)})
     check_problem(p, sel=sel, impl=TUNED, what=f"{shape} large batch")
+
+
+@pytest.mark.parametrize("shape,T", [("gta64", 1), ("gta64", 4), ("gta96", 1), ("gqa64", 2), ("gla128", 1)])
+def test_hundreds_of_short_and_empty_sequences(shape, T):
+    """More sequences than one pass of the prefix sums covers (64), most of them
+    shorter than a chunk, every fifth one empty: chunks that hold many whole
+    sequences, sequences cut at every position, empty rows filled by the merge
+    kernel.  Every row against the oracle."""
+    lens = uniform_lengths(333, 1, 400, 91 + T)
+    lens[::5] = 0
+    lens[7], lens[150], lens[332] = 5000, 2500, 3100
+    p = make_problem(f"flex_many_{shape}", seq_lens=lens, T=T, page_size=32, num_pages=8192, seed=1800 + T, poison_tail=True,
+                     extra_table_cols=1, **SHAPES[shape])
+    assert mfma_kernel_selected(p)
+    check_problem(p, impl=TUNED, what=f"{shape} many sequences T={T}")
+
+
+@pytest.mark.parametrize("index", [6, 7, 8])
+def test_full_size_configs_on_sampled_rows(index):
+    """The configurations the benchmark times on this kernel, at full size
+    (128 sequences of 4096 to 32768 tokens), automatic chunks; seeded samples of
+    rows, which the oracle computes one by one."""
+    p = config(index)
+    assert mfma_kernel_selected(p)
+    rng = np.random.default_rng(600 + index)
+    sel = sorted({(int(rng.integers(p.B)), 0, int(rng.integers(p.h_q))) for _ in range(160)})
+    check_problem(p, sel=sel, impl=TUNED, what=f"cfg{index}")
 
 
 def test_gqa_strided_caches_and_argument_checks():
