@@ -113,6 +113,31 @@ def test_hundreds_of_short_and_empty_sequences(shape, T):
     check_problem(p, impl=TUNED, what=f"{shape} many sequences T={T}")
 
 
+@pytest.mark.parametrize("case", range(30))
+def test_seeded_random_shapes(case):
+    """Seeded sweep over the shapes of this kernel with other head counts (one to
+    sixteen rows per group and query position, one or two groups per wave, several
+    row blocks per group), query lengths, page sizes, batch sizes beyond one pass
+    of the prefix sums, length mixes with empty sequences, chunk lengths and masks."""
+    rng = np.random.default_rng(9500 + case)
+    kind, h_c, d_v, d_r = [("gta", 4, 64, 32), ("gta", 2, 64, 32), ("gta", 4, 96, 48), ("gla", 2, 128, 32),
+                           ("gqa", 4, 128, 0), ("gqa", 8, 64, 0), ("gta", 3, 64, 32), ("gla", 1, 128, 32),
+                           ("gta", 1, 96, 48), ("gqa", 1, 128, 0)][case % 10]
+    g_q = int(rng.choice([1, 3, 6, 8, 12, 16]))
+    T = int(rng.integers(1, 5))
+    B = int(rng.choice([1, 2, 5, 17, 70, 130]))
+    lens = [int(x) for x in rng.choice([0, 0, 1, 2, 31, 32, 33, 64, 65, 127, 300, 900], size=B)]
+    lens[int(rng.integers(B))] = int(rng.integers(1, 4000))
+    page = int(rng.choice([32, 64]))
+    kw = dict(d_r=d_r) if kind != "gqa" else {}
+    p = make_problem(f"flex_rand{case}", kind=kind, seq_lens=lens, T=T, h_q=h_c * g_q, h_c=h_c, d_v=d_v, page_size=page,
+                     num_pages=8192, seed=9600 + case, causal=int(rng.integers(0, 2)), poison_tail=True,
+                     extra_table_cols=int(rng.integers(0, 3)), **kw)
+    assert mfma_kernel_selected(p)
+    check_problem(p, impl=TUNED, num_splits=int(rng.choice([0, 0, 1, 2, 7, 40])),
+                  what=f"case {case} {kind} h_c={h_c} g_q={g_q} d_v={d_v} T={T} B={B} page={page}")
+
+
 @pytest.mark.parametrize("index", [6, 7, 8])
 def test_full_size_configs_on_sampled_rows(index):
     """The configurations the benchmark times on this kernel, at full size
