@@ -28,6 +28,10 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv& f) {
   return (t + ((n - t) >> f.s1)) >> f.s2;
 }
 
+// Cache bytes of a batch from which the MFMA kernels fetch the cache with the streaming hint: the 256 MB
+// of the chip's last-level cache (a smaller cache can still be there at the next decode step).
+constexpr int64_t kLastLevelCacheBytes = 256ll << 20;
+
 // Kernel-argument block: a flattened copy of the caller's parameter struct.
 struct DevParams {
   const uint16_t* q_nope;
@@ -54,6 +58,7 @@ struct DevParams {
   float scale;
   // generic kernel: uniform split of every sequence's page range
   int32_t splits, pages_per_split;
+  int64_t stream_min_bytes; // second MFMA kernel: a batch with more cache bytes than this is fetched with the streaming hint
   int32_t flex_rb;          // flex kernel: blocks of 16 query rows per group
   int32_t* flex_rng;        // flex kernel: per (sequence, strand) the first chunk holding a piece of it (x 2 + its slot) and the last
   // tuned kernel: flat partition of all key tiles of the batch into chunks

@@ -157,6 +157,9 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
   const int pos0 = chunk * C;  // (the host keeps num_chunks * max tiles per chunk below 2^31)
   if (pos0 >= total) return;
   int left = min(C, total - pos0);  // tiles of this chunk not yet worked on
+  // a cache larger than the chip's last-level cache is fetched with the streaming hint (read once per call, it
+  // would only push the page table, the queries and the partial results out of the caches)
+  const bool stream_hint = (int64_t)total * 32 * (p.h_c * (VB + (SEPK ? KB : 0)) + RB) > p.stream_min_bytes;
 
   // ---- the query row of this lane within its group (rows past the end repeat the last one, never stored)
   const int jg = GPW == 2 ? r16 >> 3 : 0;                  // which of the wave's groups the row belongs to
@@ -217,22 +220,27 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
       if (--pre_left > 0) advance<32>(p, 1, pre);
     }
     unsigned char* dst = smem + wave * (NST * STAGE) + stage * STAGE;
+    auto loads = [&](auto hint) {
+      constexpr int aux = decltype(hint)::value;
 #pragma unroll
-    for (int j = 0; j < GPW; ++j)
+      for (int j = 0; j < GPW; ++j)
 #pragma unroll
-      for (int i = 0; i < NLV; ++i)
-        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_v + j * p.st_s[1] * 2 + goff_v[i]),
-                                         (lds_void_t*)(dst + j * 32 * VB + i * 1024), 16, 0, 0);
-    if constexpr (SEPK) {
+        for (int i = 0; i < NLV; ++i)
+          __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_v + j * p.st_s[1] * 2 + goff_v[i]),
+                                           (lds_void_t*)(dst + j * 32 * VB + i * 1024), 16, 0, aux);
+      if constexpr (SEPK) {
 #pragma unroll
-      for (int j = 0; j < NLK; ++j)
-        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_k + goff_k[j]), (lds_void_t*)(dst + OFF_K + j * 1024), 16, 0, 0);
-    }
-    if constexpr (DR > 0) {
+        for (int j = 0; j < NLK; ++j)
+          __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_k + goff_k[j]), (lds_void_t*)(dst + OFF_K + j * 1024), 16, 0, aux);
+      }
+      if constexpr (DR > 0) {
 #pragma unroll
-      for (int j = 0; j < NLR; ++j)
-        __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_r + goff_r[j]), (lds_void_t*)(dst + OFF_R + j * 1024), 16, 0, 0);
-    }
+        for (int j = 0; j < NLR; ++j)
+          __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_r + goff_r[j]), (lds_void_t*)(dst + OFF_R + j * 1024), 16, 0, aux);
+      }
+    };
+    if (stream_hint) loads(std::integral_constant<int, 2>{});
+    else loads(std::integral_constant<int, 0>{});
   };
 
   // ---- LDS offsets of this lane's operand reads inside a stage (the same for every tile)

@@ -245,6 +245,7 @@ void fill_dev(const gla_decode_params* p, DevParams* d) {
   d->causal = p->causal ? 1 : 0;
   d->out_fp32 = p->out_dtype == GLA_OUT_FP32;
   d->scale = p->softmax_scale;
+  d->stream_min_bytes = kLastLevelCacheBytes;
 }
 
 int launch_generic(const gla_decode_params* p, DevParams& d, hipStream_t st, hipEvent_t* ev) {

@@ -22,6 +22,7 @@ struct TunedPlan {
   int num_chunks;  // chunks of the tile list; the main-kernel grid is num_chunks * mb
   int chunk_tiles; // fixed tiles per chunk, 0: derived on the device
   size_t slot_floats;
+  bool stream;     // fetch the cache with the streaming hint
 };
 
 inline int device_cu_count() {
@@ -119,6 +120,9 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
     plan->num_chunks = (int)std::max<int64_t>(1, std::min<int64_t>(by_length, resident));
   }
   plan->slot_floats = (size_t)plan->rows * p->d_v + (size_t)32 * ng * wpg * ks;
+  // upper bound of the batch's cache bytes (the lengths are known on the device only) against the chip's
+  // last-level cache
+  plan->stream = bound * tok * 2 * ((int64_t)ng * p->d_v + p->d_rope) > kLastLevelCacheBytes;
   return true;
 }
 
@@ -138,23 +142,32 @@ inline size_t tuned_workspace(const gla_decode_params* p, int is_gta) {
   return tuned_slots_bytes(plan) + (size_t)plan.units * 2 * sizeof(int32_t);
 }
 
-template <int DV, int DN, int NG, int WPG, int KS, int TOK>
-inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
+template <int DV, int DN, int NG, int WPG, int KS, int TOK, bool STREAM>
+inline int launch_tuned_main(const DevParams& d, dim3 mgrid, dim3 mblock, hipStream_t st) {
   constexpr int STAGES = tuned_stages(DV, NG, WPG, KS), STAGES_LANE = tuned_stages(DV, NG, WPG, KS, true);
   constexpr bool kLaneFits = STAGES_LANE * (NG * TOK * DV * 2 + TOK * 128) + (KS > 1 ? NG * WPG * KS * 4096 : 0) +
                              NG * WPG * KS * 2 * kPageWindow * 4 <= 160 * 1024;
-  if (ev) (void)hipEventRecord(ev[0], st);
-  const dim3 mgrid(plan.num_chunks * plan.mb), mblock(64 * NG * WPG * KS);
   if (d.lg_page == 6) {
-    hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, 0>), mgrid, mblock, 0, st, d);
+    hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, 0, STREAM>), mgrid, mblock, 0, st, d);
   } else if (d.lg_page >= 4) {
-    hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, 1>), mgrid, mblock, 0, st, d);
+    hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, 1, STREAM>), mgrid, mblock, 0, st, d);
   } else {
     if constexpr (kLaneFits)
-      hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES_LANE, 2>), mgrid, mblock, 0, st, d);
+      hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES_LANE, 2, STREAM>), mgrid, mblock, 0, st, d);
     else
       return GLA_ERR_UNSUPPORTED_SHAPE;  // (the planner does not choose this variant for small pages)
   }
+  return GLA_OK;
+}
+
+template <int DV, int DN, int NG, int WPG, int KS, int TOK>
+inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
+  if (ev) (void)hipEventRecord(ev[0], st);
+  const dim3 mgrid(plan.num_chunks * plan.mb), mblock(64 * NG * WPG * KS);
+  // (plan.stream: the cache of this batch can be larger than the last-level cache: fetch it with the streaming hint)
+  const int lrc = plan.stream ? launch_tuned_main<DV, DN, NG, WPG, KS, TOK, true>(d, mgrid, mblock, st)
+                              : launch_tuned_main<DV, DN, NG, WPG, KS, TOK, false>(d, mgrid, mblock, st);
+  if (lrc != GLA_OK) return lrc;
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (ev) (void)hipEventRecord(ev[1], st);
   // waves per merge task from the expected number of chunks per unit
