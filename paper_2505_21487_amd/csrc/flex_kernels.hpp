@@ -236,7 +236,7 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
       if constexpr (DR > 0) {
 #pragma unroll
         for (int j = 0; j < NLR; ++j)
-          __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_r + goff_r[j]), (lds_void_t*)(dst + OFF_R + j * 1024), 16, 0, aux);
+          __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_r + goff_r[j]), (lds_void_t*)(dst + OFF_R + j * 1024), 16, 0, 0);  // (shared by the strands: left cacheable)
       }
     };
     if (stream_hint) loads(std::integral_constant<int, 2>{});

@@ -368,6 +368,11 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   // last-level cache (measured on the benchmark shapes: 5-6 % per call); a smaller cache is left
   // cacheable, since the next decode step reads it again.  (A compile-time choice: a branch on every
   // load cost the issue-bound variants 1-3 %.)
+  // (the RoPE-key tile, a ninth of the bytes and the part that group blocks of a sequence share, stays cacheable)
+  auto rope_dma = [&](auto immc, const unsigned char* src, unsigned char* dst) {
+    constexpr int imm = decltype(immc)::value;
+    __builtin_amdgcn_global_load_lds((global_cvoid_t*)src, (lds_void_t*)dst, 16, imm, 0);
+  };
   auto tile_dma = [&](auto immc, const unsigned char* src, unsigned char* dst) {
     constexpr int imm = decltype(immc)::value;
     if constexpr (STREAM)
@@ -392,14 +397,14 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
         const unsigned rho = (unsigned)((wave * RLW + ir) * 8 + r_rl);
         const unsigned off = (rho & dma_pmask) * rrb + (r_voff[ir & 1] - (unsigned)r_rl * rrb);
         const unsigned char* src = rope_w + ((uint64_t)(uint32_t)pg_r[ir] * rp_page_bytes + off);
-        tile_dma(std::integral_constant<int, 0>{}, src, dma_lr + ir * 1024);
+        rope_dma(std::integral_constant<int, 0>{}, src, dma_lr + ir * 1024);
       }
     } else if constexpr (i < SLW) {
       const unsigned voff = s_lane_w ^ ((unsigned)swz16(i * RPL) << 4);
       tile_dma(std::integral_constant<int, (i % 4) * 1024>{}, dma_s[i / 4] + voff, dma_ls + (i / 4) * 4096);
     } else {
       constexpr int ir = i - SLW;
-      tile_dma(std::integral_constant<int, 0>{}, dma_r[ir] + r_voff[ir & 1], dma_lr + ir * 1024);
+      rope_dma(std::integral_constant<int, 0>{}, dma_r[ir] + r_voff[ir & 1], dma_lr + ir * 1024);
     }
   };
 
