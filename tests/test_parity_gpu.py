@@ -354,10 +354,12 @@ def test_full_size_configs_every_row(index, T):
     check_problem(p, impl=TUNED, what=f"cfg{index} T={T}")
 
 
-@pytest.mark.parametrize("index,T,page_size", [(1, 1, 1), (2, 2, 8), (4, 1, 2)])
+@pytest.mark.parametrize("index,T,page_size", [(1, 1, 1), (2, 2, 8), (4, 1, 2), (1, 1, 32), (3, 1, 16)])
 def test_full_size_small_pages_on_sampled_rows(index, T, page_size):
     """Full-size configurations with the same pool cut into small pages (the
-    per-lane address path, page-id windows crossed hundreds of times)."""
+    per-lane address path, page-id windows crossed hundreds of times; pages of 32
+    and 16 tokens: the per-run address path), all of them large enough to take
+    the kernel variants that fetch the cache with the streaming hint."""
     p = config(index, T=T, page_size=page_size)
     sel = sample_rows(p, 64, 2000 + index)
     b_long = int(np.argmax(p.seq_lens))
