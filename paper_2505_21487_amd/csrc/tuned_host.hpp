@@ -175,6 +175,8 @@ inline int launch_tuned_variant(const TunedPlan& plan, DevParams& d, hipStream_t
   const dim3 cgrid(plan.units, NG * WPG * (DV / 32));
   if (span_est <= 2)
     hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 1, 1, 2>), cgrid, dim3(64), 0, st, d);
+  else if (span_est <= 6)  // (one wave with four chunks in flight: a fourth of the waves to launch, no merge through LDS)
+    hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 1, 1, 4>), cgrid, dim3(64), 0, st, d);
   else if (span_est <= 12)
     hipLaunchKernelGGL((tuned_combine_kernel<DV, NG, WPG, KS, TOK, 4, 1, 2>), cgrid, dim3(256), 0, st, d);
   else if (span_est <= 64)  // (a wave folds eight chunks per round trip: four waves do for fairly long lists)
