@@ -160,6 +160,39 @@ __device__ __forceinline__ void load_b128_async(u32x4_t& dst, const void* ptr) {
   asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(dst) : "v"(ptr) : "memory");
 }
 
+// Predicated 32-bit global loads into N registers the caller keeps: issued when
+// `cond` (uniform) is not zero, complete after a wait_vmcnt that covers them.
+// One statement that is executed either way, with the registers as read-write
+// operands: each keeps its place whether or not it is loaded.  row: uniform
+// base address; o0..o3: byte offsets per lane (non-negative, below 2^31).
+template <int N>
+__device__ __forceinline__ void load_window(int cond, const int32_t* row, int o0, int o1, int o2, int o3, int& w0,
+                                            int& w1, int& w2, int& w3) {
+  static_assert(N == 2 || N == 4, "registers per window");
+  if constexpr (N == 2)
+    asm volatile(
+        "s_cmp_eq_u32 %[c], 0\n\t"
+        "s_cbranch_scc1 .Lgla_win_skip%=\n\t"
+        "global_load_dword %[w0], %[o0], %[row]\n\t"
+        "global_load_dword %[w1], %[o1], %[row]\n"
+        ".Lgla_win_skip%=:"
+        : [w0] "+v"(w0), [w1] "+v"(w1)
+        : [c] "s"(cond), [row] "s"(row), [o0] "v"(o0), [o1] "v"(o1)
+        : "memory", "scc");
+  else
+    asm volatile(
+        "s_cmp_eq_u32 %[c], 0\n\t"
+        "s_cbranch_scc1 .Lgla_win_skip%=\n\t"
+        "global_load_dword %[w0], %[o0], %[row]\n\t"
+        "global_load_dword %[w1], %[o1], %[row]\n\t"
+        "global_load_dword %[w2], %[o2], %[row]\n\t"
+        "global_load_dword %[w3], %[o3], %[row]\n"
+        ".Lgla_win_skip%=:"
+        : [w0] "+v"(w0), [w1] "+v"(w1), [w2] "+v"(w2), [w3] "+v"(w3)
+        : [c] "s"(cond), [row] "s"(row), [o0] "v"(o0), [o1] "v"(o1), [o2] "v"(o2), [o3] "v"(o3)
+        : "memory", "scc");
+}
+
 // A 32-bit global load that is complete when the statement ends.  Used for the
 // rare bookkeeping reads inside the tile loop (page ids, next sequence length):
 // being opaque to the compiler's memory-counter tracking, it cannot make the

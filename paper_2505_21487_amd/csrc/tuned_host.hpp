@@ -55,6 +55,11 @@ constexpr int tuned_stages(int dv, int ng, int wpg, int ks, bool lane = false) {
   return st;
 }
 
+constexpr bool tuned_windows_fit(int dv, int ng, int wpg, int ks) {
+  return tuned_stages(dv, ng, wpg, ks, true) * (ng * kTok * dv * 2 + kTok * 128) + (ks > 1 ? ng * wpg * ks * 4096 : 0) +
+             ng * wpg * ks * 2 * kPageWindow * 4 <= 160 * 1024;
+}
+
 inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) {
   const int ps = p->page_size;
   if (ps < 1 || ps > 64 || (ps & (ps - 1))) return false;  // 64, 32, ..., 1 tokens
@@ -80,10 +85,7 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
   // A latent of 512 dims needs two waves per row slab: 32 rows x 512 fp32
   // output accumulators alone would fill a wave's accumulation registers.
   const int ks = p->d_v > 256 ? 2 : 1;
-  // (a 512-dim latent with small pages: one row slab per workgroup, because the
-  // tile ring and the score mailboxes of two slabs leave no LDS for the page-id
-  // windows; the row blocks of a group then run as separate workgroups)
-  const int wpg = (rows_group <= 32 || (ks == 2 && lane)) ? 1 : ((rows_group <= 64 || ks == 2) ? 2 : 4);
+  const int wpg = rows_group <= 32 ? 1 : ((rows_group <= 64 || ks == 2) ? 2 : 4);
   int ng = 4 / (wpg * ks);
   while (ng > 1 && (p->num_groups % ng || 4 * (ng * 32 * p->d_v * 2 + 32 * 128) > 160 * 1024)) ng >>= 1;
   plan->dv = p->d_v;
@@ -94,11 +96,13 @@ inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) 
   plan->rows = 32 * ng * wpg;
   plan->mb = (rows_group + 32 * wpg - 1) / (32 * wpg);
   plan->units = p->batch * (p->num_groups / ng) * plan->mb;
-  const int tok = kTok, stages = tuned_stages(p->d_v, ng, wpg, ks, lane);
+  // (small pages: page-id windows in LDS where tiles and mailboxes leave room for them, else in registers)
+  const bool lds_windows = lane && tuned_windows_fit(p->d_v, ng, wpg, ks);
+  const int tok = kTok, stages = tuned_stages(p->d_v, ng, wpg, ks, lds_windows);
   // co-resident workgroups per CU: one wave per SIMD, 160 KiB of LDS
   const int smem = stages * (ng * tok * p->d_v * 2 + tok * 128) + (ks > 1 ? ng * wpg * ks * 4096 : 0) +
-                   (lane ? ng * wpg * ks * 2 * kPageWindow * 4 : 0);
-  if (smem > 160 * 1024) return false;  // (512-dim latent, two row slabs, small pages: no room for the page-id windows)
+                   (lds_windows ? ng * wpg * ks * 2 * kPageWindow * 4 : 0);
+  if (smem > 160 * 1024) return false;
   const int per_cu = std::max(1, std::min((160 * 1024) / smem, 4 / (ng * wpg * ks)));
   plan->tok = tok;
   plan->stages = stages;
@@ -145,8 +149,7 @@ inline size_t tuned_workspace(const gla_decode_params* p, int is_gta) {
 template <int DV, int DN, int NG, int WPG, int KS, int TOK, bool STREAM>
 inline int launch_tuned_main(const DevParams& d, dim3 mgrid, dim3 mblock, hipStream_t st) {
   constexpr int STAGES = tuned_stages(DV, NG, WPG, KS), STAGES_LANE = tuned_stages(DV, NG, WPG, KS, true);
-  constexpr bool kLaneFits = STAGES_LANE * (NG * TOK * DV * 2 + TOK * 128) + (KS > 1 ? NG * WPG * KS * 4096 : 0) +
-                             NG * WPG * KS * 2 * kPageWindow * 4 <= 160 * 1024;
+  constexpr bool kLaneFits = tuned_windows_fit(DV, NG, WPG, KS);
   if (d.lg_page == 6) {
     hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, 0, STREAM>), mgrid, mblock, 0, st, d);
   } else if (d.lg_page >= 4) {
@@ -154,8 +157,8 @@ inline int launch_tuned_main(const DevParams& d, dim3 mgrid, dim3 mblock, hipStr
   } else {
     if constexpr (kLaneFits)
       hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES_LANE, 2, STREAM>), mgrid, mblock, 0, st, d);
-    else
-      return GLA_ERR_UNSUPPORTED_SHAPE;  // (the planner does not choose this variant for small pages)
+    else  // (no LDS left for the page-id windows: kept in registers)
+      hipLaunchKernelGGL((tuned_main_kernel<DV, DN, 64, NG, WPG, KS, TOK, STAGES, 3, STREAM>), mgrid, mblock, 0, st, d);
   }
   return GLA_OK;
 }

@@ -53,15 +53,19 @@ struct TunedTraits {
 //   0: pages of 64 tokens (a tile is half a page: one base address per tile),
 //   1: pages of 32 or 16 tokens (one base address per run of up to 16 rows),
 //   2: pages of 8, 4, 2 or 1 tokens (one address per row and lane, from page ids
-//      that each wave keeps in a window of the page table in LDS).
+//      that each wave keeps in windows of the page table in LDS),
+//   3: the same with the windows in registers, one entry per lane and register,
+//      for the shape whose tiles and mailboxes leave no LDS for them (a few
+//      per cent slower where both fit).
 constexpr int kPageWindow = 256;  // page-table entries per window (PM == 2)
 template <int DV, int DN, int DR, int NG, int WPG, int KS, int TOK, int STAGES, int PM, bool STREAM>
 __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParams p) {
   using TT = TunedTraits<DV, DN, DR, NG, WPG, KS, TOK, STAGES>;
   constexpr int NWAVES = NG * WPG * KS;
-  constexpr bool kLane = PM == 2;
+  constexpr bool kLane = PM >= 2;
+  constexpr bool kRegWin = PM == 3;
   constexpr int kWinBase = TT::kSmemBytes;                                     // two windows per wave
-  constexpr int kSmemAll = TT::kSmemBytes + (kLane ? NWAVES * 2 * kPageWindow * 4 : 0);
+  constexpr int kSmemAll = TT::kSmemBytes + (PM == 2 ? NWAVES * 2 * kPageWindow * 4 : 0);
   static_assert(kSmemAll <= 160 * 1024, "LDS capacity");
   constexpr int ROWB = TT::kRowBytes;
   constexpr int STB = TT::kStateBytes;   // state tile bytes
@@ -224,7 +228,21 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   // when the first is entered, so a window has long arrived when the prefetch
   // cursor reaches it.  Only the first window of a sequence, and windows
   // entered within a few tiles of their request, are waited for.
+  //   With the windows in registers (PM == 3) a window is kWinRegs registers,
+  // lane l of register r holding entry 64 r + l, and spans at least STAGES
+  // tiles at one token per page.  A tile's pages lie in one aligned block of 32
+  // entries, hence in one register: that register is chosen when the tiles enter
+  // a new block of 64 entries, and every load takes its row's id from it with a
+  // cross-lane read.  (Named scalars, read through pinned copies: an array, or a
+  // choice between the variables themselves, would be placed in scratch memory.
+  // The loads into them are predicated inside one assembly statement with the
+  // registers as read-write operands, and the registers have no other writer: a
+  // register whose load is in flight must never be copied.)
+  constexpr int kWinRegs = STAGES <= 4 ? 2 : 4;
+  constexpr int kWinEntries = kRegWin ? 64 * kWinRegs : kPageWindow;
   unsigned char* const win_w = smem + kWinBase + wave * (2 * kPageWindow * 4);
+  int win_a0 = 0, win_a1 = 0, win_a2 = 0, win_a3 = 0, win_b0 = 0, win_b1 = 0, win_b2 = 0, win_b3 = 0;
+  int ids = 0, ids_key = -1;  // the register's worth of entries the tiles being prepared lie in: [64 * ids_key, +64)
   int win_b = -1, win_id0 = -1, win_id1 = -1, win_at0 = 0, win_at1 = 0, win_sel = 0;
   int pg_s[SLW] = {}, pg_r[RLW] = {};  // page id of this lane's row, per load of the prepared tile
   uint64_t dma_goff = 0;               // group-block offset the prepared tile's addresses use
@@ -257,7 +275,47 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
     prep_tip = (tok0 & ((1u << lgP) - 1)) / TOK;  // tile within the page (pages of 64)
     prep_need_page = prep_active && (lgP < 6 || prep_tip == 0 || !pre_page_valid);
     const int last_idx = (int)((tok0 + TOK - 1) >> lgP);
-    if constexpr (kLane) {
+    if constexpr (kRegWin) {
+      // fetch0 / fetch1: request window id0 / id1 into the first / second set of registers
+      int fetch0 = 0, fetch1 = 0, id0 = 0, id1 = 0, last_page = 0;
+      bool wait_before = false, wait_after = false;
+      if (prep_active) {
+        last_page = (pre.L - 1) >> lgP;
+        const int want = (int)prep_page_idx / kWinEntries, nxt = want + 1;
+        const bool has_nxt = nxt * kWinEntries <= last_page;
+        if (pre.b != win_b || (want != win_id0 && want != win_id1)) {
+          // first window of a sequence: it and the one after it, waited for
+          win_b = pre.b;
+          win_sel = 0;
+          ids_key = -1;
+          win_id0 = want;
+          win_id1 = has_nxt ? nxt : -1;
+          win_at0 = win_at1 = issued - STAGES;
+          fetch0 = 1, id0 = want;
+          fetch1 = has_nxt ? 1 : 0, id1 = nxt;
+          wait_after = true;
+        } else {
+          win_sel = want == win_id1 ? 1 : 0;
+          // requested too recently for the rolling waits of the tile loop to have covered it
+          wait_before = issued - (win_sel ? win_at1 : win_at0) < STAGES;
+          if (has_nxt && (win_sel ? win_id0 : win_id1) != nxt) {
+            if (win_sel) { win_id0 = nxt; win_at0 = issued; fetch0 = 1; id0 = nxt; }
+            else { win_id1 = nxt; win_at1 = issued; fetch1 = 1; id1 = nxt; }
+          }
+        }
+      }
+      if (wait_before) wait_vmcnt<0>();
+      if (uniform(fetch0 | fetch1)) {  // (once per window: every fourth tile at most)
+        // entries [id * kWinEntries, +kWinEntries) of the sequence's row, those past its last page replaced by that page
+        const int32_t* const row = p.page_table + (int64_t)pre.b * p.max_pages;
+        const int ea = id0 * kWinEntries + lane, eb = id1 * kWinEntries + lane;
+        load_window<kWinRegs>(uniform(fetch0), row, min(ea, last_page) * 4, min(ea + 64, last_page) * 4,
+                              min(ea + 128, last_page) * 4, min(ea + 192, last_page) * 4, win_a0, win_a1, win_a2, win_a3);
+        load_window<kWinRegs>(uniform(fetch1), row, min(eb, last_page) * 4, min(eb + 64, last_page) * 4,
+                              min(eb + 128, last_page) * 4, min(eb + 192, last_page) * 4, win_b0, win_b1, win_b2, win_b3);
+      }
+      if (wait_after) wait_vmcnt<0>();
+    } else if constexpr (kLane) {
       if (prep_active) {
         const int last_page = (pre.L - 1) >> lgP;
         const int want = (int)prep_page_idx / kPageWindow;
@@ -297,7 +355,41 @@ __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParam
   };
   auto dma_prepare_2 = [&]() {  // base address of every load group; advance the prefetch cursor
     if (!prep_active) return;
-    if constexpr (kLane) {
+    if constexpr (kRegWin) {
+      const unsigned tok0 = (unsigned)pre.j * TOK;
+      const int last_page = (pre.L - 1) >> lgP;
+      // (rows past the end of the sequence take its last page: at or after the tile's first page, same register)
+      if ((int)(prep_page_idx >> 6) != ids_key) {  // (every second tile at most)
+        ids_key = (int)(prep_page_idx >> 6);
+        const int reg = (int)((prep_page_idx & (kWinEntries - 1)) >> 6);
+        // (copies through pins: the reads stay behind the waits of the first piece; the copy of a register
+        // whose load is still in flight is not the one chosen)
+        int a0 = win_a0, a1 = win_a1, b0 = win_b0, b1 = win_b1;
+        asm volatile("" : "+v"(a0), "+v"(a1), "+v"(b0), "+v"(b1));
+        int ia = reg == 1 ? a1 : a0, ib = reg == 1 ? b1 : b0;
+        if constexpr (kWinRegs > 2) {
+          int a2 = win_a2, a3 = win_a3, b2 = win_b2, b3 = win_b3;
+          asm volatile("" : "+v"(a2), "+v"(a3), "+v"(b2), "+v"(b3));
+          ia = reg == 2 ? a2 : (reg == 3 ? a3 : ia);
+          ib = reg == 2 ? b2 : (reg == 3 ? b3 : ib);
+        }
+        ids = win_sel ? ib : ia;
+      }
+#pragma unroll
+      for (int i = 0; i < SLW; ++i) {
+        const unsigned rho = (unsigned)((wpos * SLW + i) * RPL + s_rl);
+        const int e = min((int)((tok0 + rho) >> lgP), last_page);
+        pg_s[i] = __builtin_amdgcn_ds_bpermute((e & 63) << 2, ids);
+      }
+#pragma unroll
+      for (int ir = 0; ir < RLW; ++ir) {
+        const unsigned rho = (unsigned)((wave * RLW + ir) * 8 + r_rl);
+        const int e = min((int)((tok0 + rho) >> lgP), last_page);
+        pg_r[ir] = __builtin_amdgcn_ds_bpermute((e & 63) << 2, ids);
+      }
+      dma_goff = pre_goff;
+      dma_pmask = (1u << lgP) - 1;
+    } else if constexpr (kLane) {
       const unsigned tok0 = (unsigned)pre.j * TOK;
       const int last_page = (pre.L - 1) >> lgP;
       const unsigned char* const win = win_w + win_sel * (kPageWindow * 4);

@@ -125,9 +125,10 @@ def test_small_pages(shape, page_size):
 def test_tiny_pages(shape, page_size):
     """Pages of 8, 4, 2 and 1 tokens: every row of a load may sit in its own
     page, each lane forms its row's address from page ids kept in LDS windows of
-    256 table entries.  Sequences long enough to cross several windows, run
-    both with the automatic split and as one chunk per sequence (windows
-    requested ahead and used many tiles later)."""
+    256 table entries (in register windows of 128 entries for the 512-dim latent
+    with 128 rows, whose tiles leave no LDS for them).  Sequences long enough to
+    cross several windows, run both with the automatic split and as one chunk
+    per sequence (windows requested ahead and used many tiles later)."""
     lens = [0, 1, 7, 8, 9, 31, 33, 64, 65, 255, 257, 700, 1500, 3000]
     kw = dict(seq_lens=lens, page_size=page_size, num_pages=8192, poison_tail=True, extra_table_cols=1)
     if shape == "gla2":
@@ -354,12 +355,13 @@ def test_full_size_configs_every_row(index, T):
     check_problem(p, impl=TUNED, what=f"cfg{index} T={T}")
 
 
-@pytest.mark.parametrize("index,T,page_size", [(1, 1, 1), (2, 2, 8), (4, 1, 2), (1, 1, 32), (3, 1, 16)])
+@pytest.mark.parametrize("index,T,page_size", [(1, 1, 1), (2, 2, 8), (4, 1, 2), (1, 1, 32), (3, 1, 16), (3, 1, 8), (3, 1, 1), (3, 2, 2)])
 def test_full_size_small_pages_on_sampled_rows(index, T, page_size):
     """Full-size configurations with the same pool cut into small pages (the
     per-lane address path, page-id windows crossed hundreds of times; pages of 32
-    and 16 tokens: the per-run address path), all of them large enough to take
-    the kernel variants that fetch the cache with the streaming hint."""
+    and 16 tokens: the per-run address path; configuration 3 at pages of 8 or
+    fewer: the page-id windows held in registers), all of them large enough to
+    take the kernel variants that fetch the cache with the streaming hint."""
     p = config(index, T=T, page_size=page_size)
     sel = sample_rows(p, 64, 2000 + index)
     b_long = int(np.argmax(p.seq_lens))
