@@ -40,25 +40,7 @@ inline int device_cu_count() {
 
 inline bool aligned16(const void* ptr) { return ((uintptr_t)ptr & 15u) == 0; }
 
-// Tile tokens and pipeline depth of the instantiation for a shape: the deepest
-// even ring (at most 8 stages) that fits the LDS and whose loads in flight per
-// wave stay countable by the 6-bit vmcnt.
-constexpr int kTok = 32;
 constexpr int kMinChunkTiles = 4;
-constexpr int tuned_stages(int dv, int ng, int wpg, int ks, bool lane = false) {
-  const int stage_bytes = ng * kTok * dv * 2 + kTok * 128;
-  // besides the tiles: score mailboxes (ks > 1), page-id windows (pages of 8 tokens or fewer)
-  const int mailboxes = (ks > 1 ? ng * wpg * ks * 4096 : 0) + (lane ? ng * wpg * ks * 2 * kPageWindow * 4 : 0);
-  const int loads_per_wave = (kTok * dv * 2 / 1024) / (wpg * ks) + (kTok * 128 / 1024) / (ng * wpg * ks);
-  int st = 8;
-  while (st > 4 && (st * stage_bytes + mailboxes > 160 * 1024 || loads_per_wave * (st - 2) > 63)) st -= 2;
-  return st;
-}
-
-constexpr bool tuned_windows_fit(int dv, int ng, int wpg, int ks) {
-  return tuned_stages(dv, ng, wpg, ks, true) * (ng * kTok * dv * 2 + kTok * 128) + (ks > 1 ? ng * wpg * ks * 4096 : 0) +
-             ng * wpg * ks * 2 * kPageWindow * 4 <= 160 * 1024;
-}
 
 inline bool tuned_plan(const gla_decode_params* p, int is_gta, TunedPlan* plan) {
   const int ps = p->page_size;

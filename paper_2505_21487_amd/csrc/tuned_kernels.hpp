@@ -10,7 +10,7 @@
 // the h_c groups into blocks of NG.  A "unit" of the work list is (sequence b,
 // group block gb): it owns ceil(L_b / TOK) key tiles of TOK = 32 tokens (half
 // a page, a page, two pages ... 32 pages for page sizes 64, 32, 16 ... 1; the
-// address code comes in three forms, see the page modes of the main kernel);
+// address code comes in four forms, see the page modes of the main kernel);
 // a tile is the NG state tiles of its groups plus one RoPE tile.  All tiles of all units, in
 // unit order, form one flat list that is cut into equal chunks, so ragged
 // batches balance by construction and at most two units per chunk are left

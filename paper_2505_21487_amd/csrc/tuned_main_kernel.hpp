@@ -58,6 +58,27 @@ struct TunedTraits {
 //      for the shape whose tiles and mailboxes leave no LDS for them (a few
 //      per cent slower where both fit).
 constexpr int kPageWindow = 256;  // page-table entries per window (PM == 2)
+
+// Tile tokens and pipeline depth of the instantiation for a shape: the deepest
+// even ring (at most 8 stages) that fits the LDS and whose loads in flight per
+// wave stay countable by the 6-bit vmcnt.
+constexpr int kTok = 32;
+constexpr int tuned_stages(int dv, int ng, int wpg, int ks, bool lane = false) {
+  const int stage_bytes = ng * kTok * dv * 2 + kTok * 128;
+  // besides the tiles: score mailboxes (ks > 1), page-id windows (pages of 8 tokens or fewer)
+  const int mailboxes = (ks > 1 ? ng * wpg * ks * 4096 : 0) + (lane ? ng * wpg * ks * 2 * kPageWindow * 4 : 0);
+  const int loads_per_wave = (kTok * dv * 2 / 1024) / (wpg * ks) + (kTok * 128 / 1024) / (ng * wpg * ks);
+  int st = 8;
+  while (st > 4 && (st * stage_bytes + mailboxes > 160 * 1024 || loads_per_wave * (st - 2) > 63)) st -= 2;
+  return st;
+}
+
+// Do the LDS page-id windows of page mode 2 fit beside the tile ring and the mailboxes?  (Else: page mode 3.)
+constexpr bool tuned_windows_fit(int dv, int ng, int wpg, int ks) {
+  return tuned_stages(dv, ng, wpg, ks, true) * (ng * kTok * dv * 2 + kTok * 128) + (ks > 1 ? ng * wpg * ks * 4096 : 0) +
+             ng * wpg * ks * 2 * kPageWindow * 4 <= 160 * 1024;
+}
+
 template <int DV, int DN, int DR, int NG, int WPG, int KS, int TOK, int STAGES, int PM, bool STREAM>
 __global__ __launch_bounds__(64 * NG * WPG * KS) void tuned_main_kernel(DevParams p) {
   using TT = TunedTraits<DV, DN, DR, NG, WPG, KS, TOK, STAGES>;

@@ -183,3 +183,15 @@ def test_workload_generators_build_consistent_problems(page_size):
             n = -(-L // page_size)
             assert set(int(x) for x in p.table_pool[b, :n]) <= set(int(x) for x in p.page_ids)
     assert workloads.parse_lens("1024x15,65536") == [1024] * 15 + [65536]
+
+
+def test_register_page_windows_keep_their_registers():
+    """The kernels that hold page-id windows in registers load them asynchronously
+    from inline assembly; the compiler's output for them must name the same
+    registers at every load site and write them nowhere else (a copy made while a
+    load is in flight would carry stale page ids).  Cross-compiles the two
+    kernels to assembly (no GPU needed, a few seconds) and checks exactly that."""
+    from paper_2505_21487_amd import build
+
+    found = build.check_register_windows(verbose=False)
+    assert len(found) == 2
