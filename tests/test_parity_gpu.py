@@ -414,6 +414,61 @@ def test_tuned_kernel_with_strided_tensors(page_size):
         assert (out_wide[..., p.d_v:] == 0).all()
 
 
+RANDOM_SHAPES = [  # (kind, h_c, d_v, query-head counts, RoPE dims): every shape with an MFMA kernel
+    ("gla", 2, 256, (128, 64, 32, 16, 96), (64, 64, 48, 32)),
+    ("gla", 1, 256, (16, 64, 128, 8), (64, 64, 48, 32)),
+    ("gla", 4, 256, (128, 64, 32), (64, 64, 48, 32)),
+    ("gla", 1, 512, (128, 16, 64, 40), (64, 64, 48, 32)),
+    ("gta", 4, 128, (32, 64, 8, 128), (64, 64, 48, 32)),
+    ("gta", 8, 128, (64, 16), (64, 64, 48, 32)),
+    ("gta", 4, 64, (32, 16, 64), (32,)),
+    ("gta", 4, 96, (32, 48), (48,)),
+    ("gqa", 4, 128, (32, 16, 64), (64,)),
+    ("gla", 8, 128, (128, 64), (32,)),
+]
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_seeded_random_problems_over_every_mfma_shape(seed):
+    """Sixty random problems per seed, drawn over every shape that has an MFMA
+    kernel, every page size, q_len 1-4, RoPE dims, split counts, causal or not,
+    peaky softmax (query gain up to 4) and five length mixes (short, long, around
+    tile and page edges, a handful of keys, one long among short), with the MFMA
+    kernels forced wherever the shape and page size have one (no fallback to the
+    generic kernel can pass for them), bf16 and fp32 output each."""
+    rng = np.random.default_rng(seed)
+    for it in range(60):
+        kind, h_c, d_v, heads, ropes = RANDOM_SHAPES[int(rng.integers(0, len(RANDOM_SHAPES)))]
+        ps = int(rng.choice([64, 64, 32, 16, 8, 4, 2, 1]))
+        T = int(rng.choice([1, 1, 2, 3, 4]))
+        h_q, d_r = int(rng.choice(heads)), int(rng.choice(ropes))
+        B = int(rng.integers(1, 10))
+        mode = int(rng.integers(0, 5))
+        if mode == 0:
+            lens = [int(x) for x in rng.integers(0, 300, size=B)]
+        elif mode == 1:
+            lens = [int(x) for x in rng.integers(100, 4000, size=B)]
+        elif mode == 2:
+            edges = [0, 1, 2, 3, 5, 8, 15, 31, 32, 33, 63, 64, 65, 127, 129, 255, 257, 2047, 2049]
+            lens = [int(rng.choice(edges)) for _ in range(B)]
+        elif mode == 3:
+            lens = [int(x) for x in rng.integers(1, 12, size=B)]
+        else:
+            lens = [int(rng.integers(3000, 12000))] + [int(x) for x in rng.integers(0, 600, size=B - 1)]
+        splits = int(rng.choice([0, 0, 0, 1, 2, 5, 64]))
+        gain = float(rng.choice([1.0, 1.0, 2.0, 4.0]))
+        causal = int(rng.choice([1, 1, 0]))
+        pages = sum(-(-n // ps) for n in lens)
+        p = make_problem(f"rnd{seed}_{it}", kind=kind, seq_lens=lens, T=T, h_q=h_q, h_c=h_c, d_v=d_v, d_r=d_r,
+                         page_size=ps, num_pages=max(1024, 2 * pages + 64), seed=5000 * seed + 7 * it,
+                         poison_tail=True, extra_table_cols=int(rng.integers(0, 3)), q_gain=gain, causal=causal)
+        # (the second MFMA kernel takes pages of 64 and 32 tokens; smaller pages of its shapes run the generic kernel)
+        mfma = (kind, d_v) in TUNED_SHAPES or ps >= 32
+        check_problem(p, impl=TUNED if mfma else AUTO, num_splits=splits,
+                      what=f"seed {seed} case {it}: {kind} h_c={h_c} d_v={d_v} d_r={d_r} h_q={h_q} T={T} page {ps} "
+                           f"splits {splits} gain {gain} causal {causal} lens {lens}")
+
+
 def test_batch_of_empty_sequences():
     """No key anywhere: every output row is zero and every lse is -inf, on both kernels."""
     p = make_problem("all_empty", seq_lens=[0, 0, 0], T=2, h_q=128, h_c=2, d_v=256, seed=520, num_pages=64)
