@@ -32,8 +32,8 @@
  * (paper Section 4.2 for the small ones), state dims (d_v, d_nope) = (256, 256),
  * (512, 512), (128, 64) and RoPE dims 64, 48 or 32.  A second, simpler MFMA
  * kernel covers GTA states of 64 and 96 dims (RoPE key d_v / 2), latent heads of
- * 128 dims with a RoPE key of 32, and gqa_decode, with pages of 32 tokens or
- * more.  Everything else takes the generic kernel.  GLA_IMPL_TUNED means
+ * 128 dims with a RoPE key of 32, and gqa_decode, at any power-of-two
+ * page_size.  Everything else takes the generic kernel.  GLA_IMPL_TUNED means
  * "one of the MFMA kernels".
  *
  * Ownership and execution.  Every pointer in the struct is a DEVICE pointer
@@ -130,8 +130,8 @@ int gta_decode(const gla_decode_params* p);
  *     s_j = softmax_scale * q . key[j],  out = softmax(s) . value
  * Visible keys, empty rows, paging, workspace and errors as for gla_decode
  * (workspace size: gla_decode_workspace_size(p, 2)).  An MFMA kernel runs for
- * head dims (d_nope, d_v) = (128, 128) and (64, 64) with pages of 32 tokens or
- * more; other shapes take the generic kernel. */
+ * head dims (d_nope, d_v) = (128, 128) and (64, 64) at any power-of-two
+ * page_size; other shapes take the generic kernel. */
 int gqa_decode(const gla_decode_params* p, const void* key_cache, const int64_t key_stride[3]);
 
 /* For callers that cannot allocate device memory or obtain a workspace (code

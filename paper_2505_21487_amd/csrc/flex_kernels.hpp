@@ -117,7 +117,11 @@ struct FlexTraits {
   static_assert(kVB % 32 == 0 && kKB % 32 == 0 && kRB % 32 == 0, "a tile is a whole number of load instructions");
 };
 
-template <int DN, int DR, int DV, bool SEPK, int GPW = 1>
+// LANE: pages of fewer than 32 tokens.  The rows of a tile then lie in up to 32 pages, so every lane forms
+// the address of the row it fetches in each load from that row's page id (taken with a cross-lane read
+// from the 64 page ids the wave holds, one per lane); with larger pages a tile lies inside one page and
+// has one base address.
+template <int DN, int DR, int DV, bool SEPK, int GPW = 1, bool LANE = false>
 __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
   using FT = FlexTraits<DN, DR, DV, SEPK, GPW>;
   constexpr int NST = FT::kNST, STAGE = FT::kStage, LPT = FT::kLPT;
@@ -189,6 +193,20 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
   lane_offsets(std::integral_constant<int, VB>{}, goff_v);
   if constexpr (SEPK) lane_offsets(std::integral_constant<int, KB>{}, goff_k);
   if constexpr (DR > 0) lane_offsets(std::integral_constant<int, RB>{}, goff_r);
+  // LANE: the same offsets split into the row of the tile and the byte offset inside that row
+  int row_v[NLV] = {}, row_k[NLK > 0 ? NLK : 1] = {}, row_r[NLR > 0 ? NLR : 1] = {};
+  if constexpr (LANE) {
+#pragma unroll
+    for (int i = 0; i < NLV; ++i) row_v[i] = (int)(goff_v[i] / VB), goff_v[i] -= (unsigned)row_v[i] * VB;
+    if constexpr (SEPK) {
+#pragma unroll
+      for (int i = 0; i < NLK; ++i) row_k[i] = (int)(goff_k[i] / KB), goff_k[i] -= (unsigned)row_k[i] * KB;
+    }
+    if constexpr (DR > 0) {
+#pragma unroll
+      for (int i = 0; i < NLR; ++i) row_r[i] = (int)(goff_r[i] / RB), goff_r[i] -= (unsigned)row_r[i] * RB;
+    }
+  }
   const unsigned char* const state_b = (const unsigned char*)(p.state + g0 * p.st_s[1]);
   const unsigned char* const key_b = SEPK ? (const unsigned char*)(p.kstate + g0 * p.k_s[1]) : nullptr;
   const unsigned char* const rope_b = (const unsigned char*)p.rope;
@@ -198,14 +216,29 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
   TileCursor cur = locate_tile<32>(p, 1, pos0, lane, L_first, incl0);
   TileCursor pre = cur;
   int pre_left = left;
-  const int lgP = p.lg_page;             // page size is a power of two of at least 32 tokens
+  const int lgP = p.lg_page;             // page size is a power of two (of at least 32 tokens unless LANE)
   const int tpp_lg = lgP - 5;            // log2(tiles per page)
   int pt_b = -1, pt_base = 0, pt_vec = 0;  // 64 page ids of sequence pt_b from page pt_base on, one per lane
   const unsigned char *src_v = state_b, *src_k = key_b, *src_r = rope_b;
+  int ln_tok0 = 0, ln_last = 0;          // LANE: first token of the tile being fetched, last page its sequence holds
   // fetch the tile at `pre` into a stage and step `pre`; past the end of the chunk: the last tile again
   // (keeps the count of loads in flight the same in every iteration)
   auto issue_next = [&](int stage) {
-    if (pre_left > 0) {
+    if constexpr (LANE) {
+      if (pre_left > 0) {
+        // Rows past the end of the sequence take its last page (valid memory, masked later), never an
+        // unused table entry.  A tile's pages, at most 32, must lie in the 64 the wave holds.
+        ln_tok0 = pre.j << 5;
+        ln_last = (pre.L - 1) >> lgP;
+        const int pg0 = ln_tok0 >> lgP, pg1 = min((ln_tok0 + 31) >> lgP, ln_last);
+        if (pre.b != pt_b || pg0 < pt_base || pg1 >= pt_base + 64) {
+          pt_b = pre.b;
+          pt_base = pg0;
+          pt_vec = load_i32_sync(p.page_table + (int64_t)pre.b * p.max_pages + min(pg0 + lane, ln_last));
+        }
+        if (--pre_left > 0) advance<32>(p, 1, pre);
+      }
+    } else if (pre_left > 0) {
       const int pg = pre.j >> tpp_lg;
       if (pre.b != pt_b || pg < pt_base || pg >= pt_base + 64) {
         pt_b = pre.b;
@@ -220,23 +253,39 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
       if (--pre_left > 0) advance<32>(p, 1, pre);
     }
     unsigned char* dst = smem + wave * (NST * STAGE) + stage * STAGE;
+    // LANE: element offset of tile row `row` in a pool with pages of `page_stride` elements and rows of `dims`
+    auto row_at = [&](int row, int64_t page_stride, int dims) -> int64_t {
+      const int t = ln_tok0 + row;
+      const int e = min(t >> lgP, ln_last);
+      const int64_t id = __builtin_amdgcn_ds_bpermute((e - pt_base) << 2, pt_vec);
+      return id * page_stride + (int64_t)(t & ((1 << lgP) - 1)) * dims;
+    };
     auto loads = [&](auto hint) {
       constexpr int aux = decltype(hint)::value;
 #pragma unroll
-      for (int j = 0; j < GPW; ++j)
+      for (int i = 0; i < NLV; ++i) {
+        const unsigned char* src = src_v;
+        if constexpr (LANE) src = state_b + row_at(row_v[i], p.st_s[0], DV) * 2;
 #pragma unroll
-        for (int i = 0; i < NLV; ++i)
-          __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_v + j * p.st_s[1] * 2 + goff_v[i]),
+        for (int j = 0; j < GPW; ++j)
+          __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src + j * p.st_s[1] * 2 + goff_v[i]),
                                            (lds_void_t*)(dst + j * 32 * VB + i * 1024), 16, 0, aux);
+      }
       if constexpr (SEPK) {
 #pragma unroll
-        for (int j = 0; j < NLK; ++j)
-          __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_k + goff_k[j]), (lds_void_t*)(dst + OFF_K + j * 1024), 16, 0, aux);
+        for (int j = 0; j < NLK; ++j) {
+          const unsigned char* src = src_k;
+          if constexpr (LANE) src = key_b + row_at(row_k[j], p.k_s[0], DN) * 2;
+          __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src + goff_k[j]), (lds_void_t*)(dst + OFF_K + j * 1024), 16, 0, aux);
+        }
       }
       if constexpr (DR > 0) {
 #pragma unroll
-        for (int j = 0; j < NLR; ++j)
-          __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src_r + goff_r[j]), (lds_void_t*)(dst + OFF_R + j * 1024), 16, 0, 0);  // (shared by the strands: left cacheable)
+        for (int j = 0; j < NLR; ++j) {  // (shared by the strands: left cacheable)
+          const unsigned char* src = src_r;
+          if constexpr (LANE) src = rope_b + row_at(row_r[j], p.rp_s[0], DR) * 2;
+          __builtin_amdgcn_global_load_lds((global_cvoid_t*)(src + goff_r[j]), (lds_void_t*)(dst + OFF_R + j * 1024), 16, 0, 0);
+        }
       }
     };
     if (stream_hint) loads(std::integral_constant<int, 2>{});

@@ -62,6 +62,7 @@ struct FlexPlan {
   int strands;      // (group block, row block) pairs: each walks the whole tile list
   int chunks;       // chunks of the tile list (one wave per chunk and strand)
   int chunk_tiles;  // > 0: fixed tiles per chunk; 0: ceil(total / chunks), worked out on the device
+  bool lane;        // pages of fewer than 32 tokens: the kernel variant that forms one address per row and lane
 };
 
 int flex_variant(const gla_decode_params* p, int mode) {
@@ -83,7 +84,8 @@ bool flex_plan(const gla_decode_params* p, int mode, const KeyCache* kc, FlexPla
   plan->id = flex_variant(p, mode);
   if (plan->id < 0) return false;
   const int ps = p->page_size;
-  if (ps < 32 || (ps & (ps - 1))) return false;  // a tile of 32 tokens lies inside one page
+  if (ps < 1 || (ps & (ps - 1))) return false;
+  plan->lane = ps < 32;  // (else a tile of 32 tokens lies inside one page)
   if (!(p->softmax_scale > 0.f)) return false;
   // layout the kernel assumes: contiguous rows, 16-byte aligned rows and bases
   if (p->state_stride[2] != p->d_v || p->state_stride[0] % 8 || p->state_stride[1] % 8) return false;
@@ -170,6 +172,12 @@ int check_pointers(const gla_decode_params* p) {
   return GLA_OK;
 }
 
+template <int DN, int DR, int DV, bool SEPK, int GPW>
+void launch_flex_main(bool lane, dim3 grid, dim3 block, hipStream_t st, const DevParams& d) {
+  if (lane) hipLaunchKernelGGL((flex_main_kernel<DN, DR, DV, SEPK, GPW, true>), grid, block, 0, st, d);
+  else hipLaunchKernelGGL((flex_main_kernel<DN, DR, DV, SEPK, GPW, false>), grid, block, 0, st, d);
+}
+
 int launch_flex(const gla_decode_params* p, const FlexPlan& plan, DevParams& d, hipStream_t st, hipEvent_t* ev) {
   d.num_chunks = plan.chunks;
   d.chunk_tiles = plan.chunk_tiles;
@@ -190,16 +198,14 @@ int launch_flex(const gla_decode_params* p, const FlexPlan& plan, DevParams& d, 
   const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
   if (ev) (void)hipEventRecord(ev[0], st);
   switch (plan.id) {
-    case 0: hipLaunchKernelGGL((flex_main_kernel<128, 0, 128, true>), grid, block, 0, st, d); break;
-    case 1: hipLaunchKernelGGL((flex_main_kernel<64, 0, 64, true>), grid, block, 0, st, d); break;
+    case 0: launch_flex_main<128, 0, 128, true, 1>(plan.lane, grid, block, st, d); break;
+    case 1: launch_flex_main<64, 0, 64, true, 1>(plan.lane, grid, block, st, d); break;
     case 2:
-      if (plan.gpw == 2)
-        hipLaunchKernelGGL((flex_main_kernel<32, 32, 64, false, 2>), grid, block, 0, st, d);
-      else
-        hipLaunchKernelGGL((flex_main_kernel<32, 32, 64, false>), grid, block, 0, st, d);
+      if (plan.gpw == 2) launch_flex_main<32, 32, 64, false, 2>(plan.lane, grid, block, st, d);
+      else launch_flex_main<32, 32, 64, false, 1>(plan.lane, grid, block, st, d);
       break;
-    case 3: hipLaunchKernelGGL((flex_main_kernel<48, 48, 96, false>), grid, block, 0, st, d); break;
-    case 4: hipLaunchKernelGGL((flex_main_kernel<128, 32, 128, false>), grid, block, 0, st, d); break;
+    case 3: launch_flex_main<48, 48, 96, false, 1>(plan.lane, grid, block, st, d); break;
+    case 4: launch_flex_main<128, 32, 128, false, 1>(plan.lane, grid, block, st, d); break;
     default: return GLA_ERR_UNSUPPORTED_SHAPE;
   }
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;

@@ -48,6 +48,20 @@ def test_small_head_shapes(shape, page_size, T):
         check_problem(p, impl=impl, what=f"{shape} page {page_size} T={T} impl={impl}")
 
 
+@pytest.mark.parametrize("page_size", [16, 8, 2, 1])
+@pytest.mark.parametrize("shape", list(SHAPES))
+def test_small_pages(shape, page_size):
+    """Pages of fewer than 32 tokens: a tile spans 2 to 32 pages, every lane forms
+    the address of its row from that row's page id; sequences long enough to move
+    the wave's 64 held page ids many times, with the automatic split and as one
+    chunk per sequence, T = 1 and 3."""
+    for T, splits in ((1, 0), (3, 1), (2, 5)):
+        p = make_problem(f"flex_sp_{shape}", seq_lens=LENS + [4100], T=T, page_size=page_size, num_pages=16384,
+                         seed=1900 + 11 * T + page_size, poison_tail=True, extra_table_cols=2, **SHAPES[shape])
+        assert mfma_kernel_selected(p)
+        check_problem(p, impl=TUNED, num_splits=splits, what=f"{shape} page {page_size} T={T} splits={splits}")
+
+
 @pytest.mark.parametrize("splits", [1, 3, 50])
 @pytest.mark.parametrize("shape", list(SHAPES))
 def test_key_ranges_do_not_change_the_result(shape, splits):
@@ -128,10 +142,10 @@ def test_seeded_random_shapes(case):
     B = int(rng.choice([1, 2, 5, 17, 70, 130]))
     lens = [int(x) for x in rng.choice([0, 0, 1, 2, 31, 32, 33, 64, 65, 127, 300, 900], size=B)]
     lens[int(rng.integers(B))] = int(rng.integers(1, 4000))
-    page = int(rng.choice([32, 64]))
+    page = int(rng.choice([32, 64, 64, 16, 4, 1]))
     kw = dict(d_r=d_r) if kind != "gqa" else {}
     p = make_problem(f"flex_rand{case}", kind=kind, seq_lens=lens, T=T, h_q=h_c * g_q, h_c=h_c, d_v=d_v, page_size=page,
-                     num_pages=8192, seed=9600 + case, causal=int(rng.integers(0, 2)), poison_tail=True,
+                     num_pages=max(8192, 2 * sum(-(-n // page) for n in lens) + 64), seed=9600 + case, causal=int(rng.integers(0, 2)), poison_tail=True,
                      extra_table_cols=int(rng.integers(0, 3)), **kw)
     assert mfma_kernel_selected(p)
     check_problem(p, impl=TUNED, num_splits=int(rng.choice([0, 0, 1, 2, 7, 40])),

@@ -434,8 +434,8 @@ def test_seeded_random_problems_over_every_mfma_shape(seed):
     kernel, every page size, q_len 1-4, RoPE dims, split counts, causal or not,
     peaky softmax (query gain up to 4) and five length mixes (short, long, around
     tile and page edges, a handful of keys, one long among short), with the MFMA
-    kernels forced wherever the shape and page size have one (no fallback to the
-    generic kernel can pass for them), bf16 and fp32 output each."""
+    kernels forced (no fallback to the generic kernel can pass for them), bf16
+    and fp32 output each."""
     rng = np.random.default_rng(seed)
     for it in range(60):
         kind, h_c, d_v, heads, ropes = RANDOM_SHAPES[int(rng.integers(0, len(RANDOM_SHAPES)))]
@@ -462,9 +462,7 @@ def test_seeded_random_problems_over_every_mfma_shape(seed):
         p = make_problem(f"rnd{seed}_{it}", kind=kind, seq_lens=lens, T=T, h_q=h_q, h_c=h_c, d_v=d_v, d_r=d_r,
                          page_size=ps, num_pages=max(1024, 2 * pages + 64), seed=5000 * seed + 7 * it,
                          poison_tail=True, extra_table_cols=int(rng.integers(0, 3)), q_gain=gain, causal=causal)
-        # (the second MFMA kernel takes pages of 64 and 32 tokens; smaller pages of its shapes run the generic kernel)
-        mfma = (kind, d_v) in TUNED_SHAPES or ps >= 32
-        check_problem(p, impl=TUNED if mfma else AUTO, num_splits=splits,
+        check_problem(p, impl=TUNED, num_splits=splits,
                       what=f"seed {seed} case {it}: {kind} h_c={h_c} d_v={d_v} d_r={d_r} h_q={h_q} T={T} page {ps} "
                            f"splits {splits} gain {gain} causal {causal} lens {lens}")
 
