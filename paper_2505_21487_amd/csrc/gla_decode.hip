@@ -363,6 +363,7 @@ int run_noalloc(const gla_decode_params* p, int is_gta) {
 // ---- projections around the attention ------------------------------------------
 struct ProjPlan {
   int mt;          // 32-row blocks of query rows per workgroup (1 or 2)
+  int nt;          // 32-row blocks of output features per wave (1 or 2)
   int ksplit;      // ranges the input features of a group are cut into
   int k_per_split;
   bool direct;     // no partials: the kernel writes the result itself
@@ -378,23 +379,42 @@ int proj_plan(const gla_proj_params* p, int sum_groups, ProjPlan* plan) {
   if (p->a_row_stride % 8 || p->a_group_stride % 8 || p->c_row_stride % 4 || p->c_group_stride % 4)
     return GLA_ERR_UNSUPPORTED_SHAPE;
   plan->mt = p->rows <= 32 ? 1 : 2;
-  const int64_t tiles = (int64_t)((p->n + 127) / 128) * ((p->rows + 32 * plan->mt - 1) / (32 * plan->mt));
-  // Ranges per group: one workgroup is resident per compute unit (its LDS ring), so the grid runs in
-  // rounds of as many workgroups as there are compute units.  Among the cuts into ranges of at least
-  // 512 features pick the one with the least estimated time: rounds x (steps per range + a fixed cost
-  // per workgroup of about four steps: start-up latency, partial store).
+  const int cus = device_cu_count();
+  const int64_t row_tiles = (p->rows + 32 * plan->mt - 1) / (32 * plan->mt);
+  // Long sums (the output projection): 64 output features per wave, i.e. 256 per workgroup, and as many
+  // ranges per group as give one workgroup per compute unit in a single round (its ring of three 40 KB
+  // stages fills the LDS).  Against 32 features per wave that halves the re-reads of the query rows (every
+  // workgroup fetches its range of them: rows x k x 2 bytes per 128 or 256 output features) and needs
+  // fewer partial results (output projection of the benchmark shape: 240 workgroups, 93 -> 74 us).
+  // Taken when such a grid covers at least three quarters of the compute units; ranges of at least 512
+  // features, of ceil(steps / ranges) steps of 64 each, the last one shorter.
   int ks = 1;
+  plan->nt = 1;
+  plan->k_per_split = p->k;
   {
-    const int cus = device_cu_count();
+    const int64_t base = (int64_t)((p->n + 255) / 256) * row_tiles * p->groups;
+    const int64_t want = std::min<int64_t>(std::max(1, p->k / 512), cus / std::max<int64_t>(1, base));
+    if (want >= 1 && base * want * 4 >= (int64_t)cus * 3) {
+      const int steps = p->k / 64, per = (int)((steps + want - 1) / want);
+      plan->nt = 2;
+      ks = (steps + per - 1) / per;  // (no empty range)
+      plan->k_per_split = per * 64;
+    }
+  }
+  if (plan->nt == 1) {
+    const int64_t tiles = (int64_t)((p->n + 127) / 128) * row_tiles;
+    // Ranges per group: the grid runs in rounds of as many workgroups as there are compute units.  Among
+    // the cuts into ranges of at least 512 features pick the one with the least estimated time: rounds x
+    // (steps per range + a fixed cost per workgroup of about four steps: start-up latency, partial store).
     double best = 1e30;
     for (int c = 1; c <= 64 && p->k / c >= 512 && (p->k / c) % 64 == 0; c *= 2) {
       const int64_t wgs = tiles * p->groups * c;
       const double t = (double)((wgs + cus - 1) / cus) * (p->k / c / 64 + 4);
       if (t < best * 0.999) { best = t; ks = c; }
     }
+    plan->k_per_split = p->k / ks;
   }
   plan->ksplit = ks;
-  plan->k_per_split = p->k / ks;
   plan->direct = ks == 1 && (!sum_groups || p->groups == 1);
   plan->part_bytes = plan->direct ? 0 : (size_t)p->groups * ks * p->rows * p->n * sizeof(float);
   return GLA_OK;
@@ -428,11 +448,17 @@ int run_proj(const gla_proj_params* p, int sum_groups) {
   d.c_fp32 = p->c_dtype == GLA_OUT_FP32;
   d.direct = plan.direct ? 1 : 0;
   hipStream_t st = (hipStream_t)p->stream;
-  const dim3 grid((unsigned)((p->n + 127) / 128), (unsigned)((p->rows + 32 * plan.mt - 1) / (32 * plan.mt)),
+  const int wg_n = 128 * plan.nt;
+  const dim3 grid((unsigned)((p->n + wg_n - 1) / wg_n), (unsigned)((p->rows + 32 * plan.mt - 1) / (32 * plan.mt)),
                   (unsigned)(p->groups * plan.ksplit));
   if (grid.y > 65535u || grid.z > 65535u) return GLA_ERR_UNSUPPORTED_SHAPE;
-  if (plan.mt == 1) hipLaunchKernelGGL(proj_kernel<1>, grid, dim3(256), 0, st, d);
-  else hipLaunchKernelGGL(proj_kernel<2>, grid, dim3(256), 0, st, d);
+  if (plan.nt == 2) {
+    if (plan.mt == 1) hipLaunchKernelGGL((proj_kernel<1, 2>), grid, dim3(256), 0, st, d);
+    else hipLaunchKernelGGL((proj_kernel<2, 2>), grid, dim3(256), 0, st, d);
+  } else {
+    if (plan.mt == 1) hipLaunchKernelGGL((proj_kernel<1, 1>), grid, dim3(256), 0, st, d);
+    else hipLaunchKernelGGL((proj_kernel<2, 1>), grid, dim3(256), 0, st, d);
+  }
   if (hipGetLastError() != hipSuccess) return GLA_ERR_LAUNCH;
   if (!plan.direct) {
     const int64_t outs = (int64_t)p->rows * (sum_groups ? 1 : p->groups) * (p->n / 4);

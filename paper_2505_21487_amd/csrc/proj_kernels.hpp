@@ -6,7 +6,7 @@
 //
 // m runs over the few query rows of a decode step (batch x q_len), so the
 // work is reading W once: the kernel is bound by HBM, and the weights are the
-// operand that streams.  Transposed form C^T = W . A^T: a wave owns 32 output
+// operand that streams.  Transposed form C^T = W . A^T: a wave owns 32*NT output
 // features (rows of W, the MFMA A operand) and all 32*MT query rows of its
 // workgroup (columns, the B operand).
 //
@@ -15,7 +15,7 @@
 // cache lines per instruction, each line touched by exactly one instruction
 // (register-direct loads in MFMA operand order touch every line four times and
 // run at a quarter of the rate).  The workgroup keeps one ring of NST stages in
-// LDS; a stage holds 64 input features of each wave's 32 weight rows (fetched
+// LDS; a stage holds 64 input features of each wave's 32*NT weight rows (fetched
 // and read by that wave alone) and of the 32*MT query rows, which all four waves
 // read and each fetches a quarter of (fetched once per wave they cost three
 // times the weights' bytes in L2 traffic).  One barrier per stage; NST - 1
@@ -57,12 +57,11 @@ struct ProjParams {
   int32_t sum_groups, c_fp32, direct;
 };
 
-template <int MT>
+template <int MT, int NT>
 __global__ __launch_bounds__(256) void proj_kernel(ProjParams p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 31, h = lane >> 5;
-  const int n0 = blockIdx.x * 128 + wave * 32;
-  const bool n_valid = n0 < p.N;  // (N is a multiple of 32: a wave's 32 output features exist or do not)
+  const int n0 = blockIdx.x * (128 * NT) + wave * (32 * NT);  // (N is a multiple of 32: a block of 32 output features exists or does not)
   const int m0 = blockIdx.y * (32 * MT);
   const int g = (int)blockIdx.z / p.ksplit, ks = (int)blockIdx.z % p.ksplit;
   const int k_begin = ks * p.k_per_split;
@@ -70,10 +69,12 @@ __global__ __launch_bounds__(256) void proj_kernel(ProjParams p) {
 
   // One ring of NST stages per workgroup; a stage holds, for 64 input features, the 32 weight rows of each
   // of the four waves (private to the wave) and the 32*MT query rows (shared: each wave fetches a quarter).
-  // (three or four stages, 72-80 KB: two workgroups per compute unit, one streaming while the other starts up
-  // or stores; deeper rings with one resident workgroup measured 10 % slower on the output projection)
-  constexpr int NST = MT == 1 ? 4 : 3;
-  constexpr int kStage = (4 + MT) * 4096;
+  // (NT = 1: three or four stages, 72-80 KB: two workgroups per compute unit, one streaming while the other
+  // starts up or stores.  NT = 2: three stages of up to 40 KB, one workgroup per compute unit; the host
+  // then launches about one workgroup per compute unit.  Two and four stages measured 5 % and 1 % slower.)
+  constexpr int NST = NT > 1 ? 3 : (MT == 1 ? 4 : 3);
+  constexpr int kStage = (4 * NT + MT) * 4096;
+  constexpr int kAOff = 4 * NT * 4096;  // the query rows follow the weights in a stage
   __shared__ __attribute__((aligned(1024))) unsigned char smem[NST * kStage];
   static_assert(sizeof(smem) <= 160 * 1024, "LDS capacity");
   const unsigned smem_addr = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -81,38 +82,40 @@ __global__ __launch_bounds__(256) void proj_kernel(ProjParams p) {
   // load side: lane l of an instruction moves row l / 8 of its block of 8 rows; its LDS slot l % 8 is home to
   // chunk (l % 8) ^ (row % 8)
   const int lr = lane >> 3, lc = (lane & 7) ^ (lane >> 3);
-  const unsigned char* wsrc[4];
+  const unsigned char* wsrc[4 * NT];
   const unsigned char* asrc[MT];
 #pragma unroll
-  for (int j = 0; j < 4; ++j)  // (waves past the last output feature fetch the last rows again and store nothing)
+  for (int j = 0; j < 4 * NT; ++j)  // (waves past the last output feature fetch the last rows again and store nothing)
     wsrc[j] = (const unsigned char*)(p.w + ((int64_t)g * p.N + min(n0 + 8 * j + lr, p.N - 1)) * p.K) + lc * 16;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {  // query rows 32 * mt + 8 * wave .. + 7 (rows past the end repeat the last one)
     const int m = min(m0 + mt * 32 + 8 * wave + lr, p.M - 1);
     asrc[mt] = (const unsigned char*)(p.a + m * p.a_row + g * p.a_group) + lc * 16;
   }
-  auto issue = [&](int k, int stage) {  // 4 + MT loads
+  auto issue = [&](int k, int stage) {  // 4 * NT + MT loads
     unsigned char* dst = smem + stage * kStage;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(wsrc[j] + (int64_t)k * 2), (lds_void_t*)(dst + wave * 4096 + j * 1024), 16, 0, 0);
+    for (int j = 0; j < 4 * NT; ++j)
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(wsrc[j] + (int64_t)k * 2), (lds_void_t*)(dst + wave * (NT * 4096) + j * 1024), 16, 0, 0);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
-      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(asrc[mt] + (int64_t)k * 2), (lds_void_t*)(dst + (4 + mt) * 4096 + wave * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((global_cvoid_t*)(asrc[mt] + (int64_t)k * 2), (lds_void_t*)(dst + kAOff + mt * 4096 + wave * 1024), 16, 0, 0);
   };
   // operand side: row r, chunk 4h + s at slot (4h + s) ^ (r % 8)
   unsigned rd[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s) rd[s] = smem_addr + (unsigned)(r * 128 + (((4 * h + s) ^ (r & 7)) << 4));
-  const unsigned w_off = (unsigned)wave * 4096u;
+  const unsigned w_off = (unsigned)wave * (unsigned)(NT * 4096);
 
-  proj_f32x16_t acc[MT];
+  proj_f32x16_t acc[NT][MT];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
+  for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[nt][mt][i] = 0.f;
 
-  constexpr int LPS = 4 + MT;  // loads per wave and stage
+  constexpr int LPS = 4 * NT + MT;  // loads per wave and stage
   static_assert(LPS * (NST - 2) <= 63, "vmcnt range");
   const int k_last = k_end - 64;
 #pragma unroll
@@ -126,24 +129,30 @@ __global__ __launch_bounds__(256) void proj_kernel(ProjParams p) {
         wait_vmcnt<LPS * (NST - 2)>();
         bare_barrier();
         issue(min(k + 64 * (st + NST - 1), k_last), (st + NST - 1) % NST);
-        u32x4_t wf[4], af[MT][4];
+        u32x4_t wf[NT][4], af[MT][4];
         static_for<0, 4>([&](auto sc) {
           constexpr int s = decltype(sc)::value;
           // (the stage offset goes into the address register: the instruction's offset field has 16 bits)
-          lds_read_b128<0>(wf[s], rd[s] + (w_off + (unsigned)(st * kStage)));
+          static_for<0, NT>([&](auto nc) {
+            lds_read_b128<decltype(nc)::value * 4096>(wf[decltype(nc)::value][s], rd[s] + (w_off + (unsigned)(st * kStage)));
+          });
           static_for<0, MT>([&](auto mc) {
-            lds_read_b128<(4 + decltype(mc)::value) * 4096>(af[decltype(mc)::value][s], rd[s] + (unsigned)(st * kStage));
+            lds_read_b128<kAOff + decltype(mc)::value * 4096>(af[decltype(mc)::value][s], rd[s] + (unsigned)(st * kStage));
           });
         });
         static_for<0, 4>([&](auto sc) {
           constexpr int s = decltype(sc)::value;
-          constexpr int left = (3 - s) * (1 + MT);  // reads of later steps may still be in flight
-          lds_wait<left>(wf[s]);
-          static_for<0, MT>([&](auto mc) {
-            constexpr int mt = decltype(mc)::value;
-            asm volatile("" : "+v"(af[mt][s]));  // (covered by the wait above: LDS returns in order)
-            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(proj_bf16x8_t, wf[s]),
-                                                               __builtin_bit_cast(proj_bf16x8_t, af[mt][s]), acc[mt], 0, 0, 0);
+          constexpr int left = (3 - s) * (NT + MT);  // reads of later steps may still be in flight
+          lds_wait<left>(wf[0][s]);
+          static_for<0, NT>([&](auto nc) {
+            constexpr int nt = decltype(nc)::value;
+            asm volatile("" : "+v"(wf[nt][s]));  // (covered by the wait above: LDS returns in order)
+            static_for<0, MT>([&](auto mc) {
+              constexpr int mt = decltype(mc)::value;
+              asm volatile("" : "+v"(af[mt][s]));
+              acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(proj_bf16x8_t, wf[nt][s]),
+                                                                     __builtin_bit_cast(proj_bf16x8_t, af[mt][s]), acc[nt][mt], 0, 0, 0);
+            });
           });
         });
       }
@@ -151,15 +160,16 @@ __global__ __launch_bounds__(256) void proj_kernel(ProjParams p) {
   }
 
   wait_vmcnt<0>();  // (re-fetched steps past the end of the range: let them land before the wave leaves)
-  // accumulator element i of lane (r, h): output feature n0 + 8 * (i / 4) + 4 * h + i % 4, query row m0 + 32 * mt + r
+  // accumulator element i of lane (r, h): output feature n0 + 32 * nt + 8 * (i / 4) + 4 * h + i % 4, query row m0 + 32 * mt + r
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
+  for (int nm = 0; nm < NT * MT; ++nm) {
+    const int nt = nm / MT, mt = nm % MT;
     const int m = m0 + mt * 32 + r;
-    if (m >= p.M || !n_valid) continue;
+    if (m >= p.M || n0 + 32 * nt >= p.N) continue;
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
-      const int n = n0 + 8 * q4 + 4 * h;
-      const proj_f32x4_t v = {acc[mt][4 * q4], acc[mt][4 * q4 + 1], acc[mt][4 * q4 + 2], acc[mt][4 * q4 + 3]};
+      const int n = n0 + 32 * nt + 8 * q4 + 4 * h;
+      const proj_f32x4_t v = {acc[nt][mt][4 * q4], acc[nt][mt][4 * q4 + 1], acc[nt][mt][4 * q4 + 2], acc[nt][mt][4 * q4 + 3]};
       if (!p.direct) {
         *reinterpret_cast<proj_f32x4_t*>(p.part + ((int64_t)blockIdx.z * p.M + m) * p.N + n) = v;
       } else {

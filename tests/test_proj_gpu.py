@@ -27,10 +27,13 @@ def check_projection(c, ref, abs_prod, *, bf16_out, what):
     assert rel <= (4e-3 if bf16_out else 1e-5), f"{what}: rel-L2 {rel:.3e}"
 
 
-@pytest.mark.parametrize("M,G,N,K", [(1, 3, 32, 64), (33, 5, 96, 192), (64, 128, 256, 128), (128, 16, 512, 128), (70, 1, 4096, 1024)])
+@pytest.mark.parametrize("M,G,N,K", [(1, 3, 32, 64), (33, 5, 96, 192), (64, 128, 256, 128), (128, 16, 512, 128), (70, 1, 4096, 1024),
+                                     (64, 8, 1056, 6208)])
 def test_absorb_query_against_oracle(M, G, N, K):
     """(64, 128, 256, 128) is the benchmark workload's shape: 64 rows, 128 heads, d_c 256, d_h 128;
-    (70, 1, 4096, 1024): one merged weight from a hidden vector, input features cut into ranges."""
+    (70, 1, 4096, 1024): one merged weight from a hidden vector, input features cut into ranges;
+    (64, 8, 1056, 6208): long sums per group, which take the variant with 64 output features per wave
+    (the last wave's second block of 32 does not exist) and ranges of unequal length."""
     g = torch.Generator().manual_seed(700 + M)
     a = torch.randn(M, G, K, generator=g).to(torch.bfloat16)
     w = (torch.randn(G, N, K, generator=g) / K ** 0.5).to(torch.bfloat16)
@@ -47,9 +50,12 @@ def test_absorb_query_against_oracle(M, G, N, K):
         check_projection(c.double().cpu().numpy(), ref, abs_prod, bf16_out=dt == torch.bfloat16, what=f"absorb {M}x{G}x{N}x{K} {dt}")
 
 
-@pytest.mark.parametrize("M,G,N,K", [(1, 2, 64, 256), (64, 2, 5120, 16384), (37, 4, 160, 8192), (128, 1, 1024, 32768)])
+@pytest.mark.parametrize("M,G,N,K", [(1, 2, 64, 256), (64, 2, 5120, 16384), (37, 4, 160, 8192), (128, 1, 1024, 32768),
+                                     (64, 3, 1632, 12352)])
 def test_output_proj_against_oracle(M, G, N, K):
-    """(64, 2, 5120, 16384): the benchmark workload's shape (two latent heads, 64 heads x 256 dims each, model dim 5120)."""
+    """(64, 2, 5120, 16384): the benchmark workload's shape (two latent heads, 64 heads x 256 dims each, model dim 5120);
+    it, (128, 1, 1024, 32768) and (64, 3, 1632, 12352) take the variant with 64 output features per wave, the last
+    with a number of 32-feature blocks and of 64-feature steps that divide by nothing the plan uses."""
     g = torch.Generator().manual_seed(800 + M)
     a = (torch.randn(M, G, K, generator=g) * 0.05).to(torch.bfloat16)     # attention outputs are small
     w = projection_weights(G, N, K, seed=801 + M)
