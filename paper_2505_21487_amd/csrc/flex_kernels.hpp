@@ -118,9 +118,10 @@ struct FlexTraits {
 };
 
 // LANE: pages of fewer than 32 tokens.  The rows of a tile then lie in up to 32 pages, so every lane forms
-// the address of the row it fetches in each load from that row's page id (taken with a cross-lane read
-// from the 64 page ids the wave holds, one per lane); with larger pages a tile lies inside one page and
-// has one base address.
+// the address of the row it fetches in each load from that row's page id, taken with a cross-lane read
+// from the page ids the wave holds: an aligned window of 256 table entries in four registers, one entry
+// per lane each (a tile's pages lie in one aligned block of 32 entries, hence in one of the registers).
+// With larger pages a tile lies inside one page and has one base address.
 template <int DN, int DR, int DV, bool SEPK, int GPW = 1, bool LANE = false>
 __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
   using FT = FlexTraits<DN, DR, DV, SEPK, GPW>;
@@ -221,21 +222,27 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
   int pt_b = -1, pt_base = 0, pt_vec = 0;  // 64 page ids of sequence pt_b from page pt_base on, one per lane
   const unsigned char *src_v = state_b, *src_k = key_b, *src_r = rope_b;
   int ln_tok0 = 0, ln_last = 0;          // LANE: first token of the tile being fetched, last page its sequence holds
+  int pt_w0 = 0, pt_w1 = 0, pt_w2 = 0, pt_w3 = 0;  // LANE: entries [256 * pt_base, +256) of the page-table row of sequence pt_b
   // fetch the tile at `pre` into a stage and step `pre`; past the end of the chunk: the last tile again
   // (keeps the count of loads in flight the same in every iteration)
   auto issue_next = [&](int stage) {
     if constexpr (LANE) {
       if (pre_left > 0) {
-        // Rows past the end of the sequence take its last page (valid memory, masked later), never an
-        // unused table entry.  A tile's pages, at most 32, must lie in the 64 the wave holds.
+        // Rows past the end of the sequence take its last page (valid memory, masked later; at or after the
+        // tile's first page, so inside the same block of entries), never an unused table entry.
         ln_tok0 = pre.j << 5;
         ln_last = (pre.L - 1) >> lgP;
-        const int pg0 = ln_tok0 >> lgP, pg1 = min((ln_tok0 + 31) >> lgP, ln_last);
-        if (pre.b != pt_b || pg0 < pt_base || pg1 >= pt_base + 64) {
+        const int pg0 = ln_tok0 >> lgP;
+        if (pre.b != pt_b || (pg0 >> 8) != pt_base) {  // (every eighth tile at one token per page; the wave waits for it)
           pt_b = pre.b;
-          pt_base = pg0;
-          pt_vec = load_i32_sync(p.page_table + (int64_t)pre.b * p.max_pages + min(pg0 + lane, ln_last));
+          pt_base = pg0 >> 8;
+          const int32_t* row = p.page_table + (int64_t)pre.b * p.max_pages;
+          const int e0 = pt_base * 256 + lane;
+          load_i32x4_sync(pt_w0, pt_w1, pt_w2, pt_w3, row + min(e0, ln_last), row + min(e0 + 64, ln_last),
+                          row + min(e0 + 128, ln_last), row + min(e0 + 192, ln_last));
         }
+        const int reg = (pg0 >> 6) & 3;  // (uniform)
+        pt_vec = reg == 0 ? pt_w0 : reg == 1 ? pt_w1 : reg == 2 ? pt_w2 : pt_w3;
         if (--pre_left > 0) advance<32>(p, 1, pre);
       }
     } else if (pre_left > 0) {
@@ -257,7 +264,7 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
     auto row_at = [&](int row, int64_t page_stride, int dims) -> int64_t {
       const int t = ln_tok0 + row;
       const int e = min(t >> lgP, ln_last);
-      const int64_t id = __builtin_amdgcn_ds_bpermute((e - pt_base) << 2, pt_vec);
+      const int64_t id = __builtin_amdgcn_ds_bpermute((e & 63) << 2, pt_vec);
       return id * page_stride + (int64_t)(t & ((1 << lgP) - 1)) * dims;
     };
     auto loads = [&](auto hint) {

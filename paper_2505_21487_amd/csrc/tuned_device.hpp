@@ -204,6 +204,17 @@ __device__ __forceinline__ int load_i32_sync(const int32_t* ptr) {
   return v;
 }
 
+// Four such loads in flight together, complete when the statement ends.
+__device__ __forceinline__ void load_i32x4_sync(int& v0, int& v1, int& v2, int& v3, const int32_t* p0, const int32_t* p1,
+                                                const int32_t* p2, const int32_t* p3) {
+  asm volatile(
+      "global_load_dword %0, %4, off\n\tglobal_load_dword %1, %5, off\n\tglobal_load_dword %2, %6, off\n\t"
+      "global_load_dword %3, %7, off\n\ts_waitcnt vmcnt(0)"
+      : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
+      : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+      : "memory");
+}
+
 // Register-class pins (no instruction is emitted).  MFMA accumulators and the
 // query fragments, which are only ever MFMA operands inside the tile loop, are
 // kept in the accumulation half of the unified register file; everything the
