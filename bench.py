@@ -10,7 +10,8 @@ Timing protocol.  The first K calls of the process are timed as they come
 (`first_calls_us`: cold clocks, then the 10-35 % slower transient of the first
 ~15 ms of load).  Then an untimed pre-heat (`preheat`, default 150 ms of calls),
 the W warm-up calls, and the K timed calls that give `value`; `settled_us` is
-the same over at least 1000 further calls.
+the same over at least 1000 further calls, `per_call_us` the median and the
+10th / 90th percentile of 200 single calls (events between consecutive calls).
 
     python bench.py [--steps K] [--warmup W] [--config 1] [--q-len T]
 
@@ -398,6 +399,21 @@ def main() -> int:
     settled_n = max(args.steps, args.settled_steps) if args.settled_steps > 0 else 0
     settled_us = timed(settled_n) if settled_n > 0 else us_per_call
 
+    # (5) spread of single calls: an event between every two of 200 back-to-back calls (the gaps between
+    #     consecutive events: a call's duration in a full queue, event record included)
+    spread = None
+    if settled_n > 0:
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(201)]
+        torch.cuda.synchronize()
+        marks[0].record()
+        for i in range(200):
+            one_call(i)
+            marks[i + 1].record()
+        torch.cuda.synchronize()
+        gaps = sorted(marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(200))
+        spread = {"n": 200, "median": gaps[100], "p10": gaps[20], "p90": gaps[180],
+                  "how": "HIP events between consecutive calls of a back-to-back run"}
+
     # per-kernel durations from HIP events recorded by the library on its launch stream
     main_us = comb_us = 0.0
     if is_gqa:
@@ -454,6 +470,7 @@ def main() -> int:
         "preheat": {"calls": preheat_calls, "ms": preheat_ms},
         "settled_us": settled_us,
         "settled_steps": settled_n,
+        "per_call_us": spread,
         "cache_bytes": cache_b,
         "cache_GBps": cache_b / (us_per_call * 1e-6) / 1e9,
         "hbm_frac_of_peak": cache_b / (us_per_call * 1e-6) / 1e9 / HBM_PEAK_GBPS,
