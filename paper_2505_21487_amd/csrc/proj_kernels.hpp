@@ -200,7 +200,17 @@ __global__ __launch_bounds__(256) void proj_reduce_kernel(ProjParams p) {
   const int m = (int)(idx / ((int64_t)n4 * outs));
   const int z0 = p.sum_groups ? 0 : g * p.ksplit, z1 = p.sum_groups ? p.G * p.ksplit : (g + 1) * p.ksplit;
   proj_f32x4_t v = {0.f, 0.f, 0.f, 0.f};
-  for (int z = z0; z < z1; ++z) v += *reinterpret_cast<const proj_f32x4_t*>(p.part + ((int64_t)z * p.M + m) * p.N + n);
+  const float* src = p.part + ((int64_t)z0 * p.M + m) * p.N + n;
+  const int64_t step = (int64_t)p.M * p.N;
+  int z = z0;
+  for (; z + 4 <= z1; z += 4, src += 4 * step) {  // four slices in flight, added in index order
+    const proj_f32x4_t a0 = *reinterpret_cast<const proj_f32x4_t*>(src);
+    const proj_f32x4_t a1 = *reinterpret_cast<const proj_f32x4_t*>(src + step);
+    const proj_f32x4_t a2 = *reinterpret_cast<const proj_f32x4_t*>(src + 2 * step);
+    const proj_f32x4_t a3 = *reinterpret_cast<const proj_f32x4_t*>(src + 3 * step);
+    v = (((v + a0) + a1) + a2) + a3;
+  }
+  for (; z < z1; ++z, src += step) v += *reinterpret_cast<const proj_f32x4_t*>(src);
   const int64_t off = m * p.c_row + (p.sum_groups ? 0 : g * p.c_group) + n;
   if (p.c_fp32) {
     *reinterpret_cast<proj_f32x4_t*>((float*)p.c + off) = v;
