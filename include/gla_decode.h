@@ -25,8 +25,8 @@
  *
  * The cache is paged: token j of sequence b lives in physical page
  * page_table[b][j / page_size] at slot j % page_size.  Table entries at or
- * beyond ceil(L_b / page_size) are never read (they may hold anything, -1
- * included); slots at or beyond L_b inside a page the table does hold may be
+ * beyond ceil(L_b / page_size) are never used as page ids (they may hold
+ * anything, -1 included; a kernel may load them along with their row); slots at or beyond L_b inside a page the table does hold may be
  * fetched but never reach a result, whatever they contain (NaN included).
  * The main MFMA kernel runs for every power-of-two page_size from 64 down to 1
  * (paper Section 4.2 for the small ones), state dims (d_v, d_nope) = (256, 256),

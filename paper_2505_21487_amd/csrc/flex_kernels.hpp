@@ -219,7 +219,9 @@ __global__ __launch_bounds__(256) void flex_main_kernel(DevParams p) {
   int pre_left = left;
   const int lgP = p.lg_page;             // page size is a power of two (of at least 32 tokens unless LANE)
   const int tpp_lg = lgP - 5;            // log2(tiles per page)
-  int pt_b = -1, pt_base = 0, pt_vec = 0;  // 64 page ids of sequence pt_b from page pt_base on, one per lane
+  // 64 page ids of sequence pt_b, one per lane: from page pt_base on (LANE: the register of the window below
+  // that serves the tile being fetched; pt_base is then the window's index)
+  int pt_b = -1, pt_base = 0, pt_vec = 0;
   const unsigned char *src_v = state_b, *src_k = key_b, *src_r = rope_b;
   int ln_tok0 = 0, ln_last = 0;          // LANE: first token of the tile being fetched, last page its sequence holds
   int pt_w0 = 0, pt_w1 = 0, pt_w2 = 0, pt_w3 = 0;  // LANE: entries [256 * pt_base, +256) of the page-table row of sequence pt_b
