@@ -467,6 +467,32 @@ def test_seeded_random_problems_over_every_mfma_shape(seed):
                            f"splits {splits} gain {gain} causal {causal} lens {lens}")
 
 
+LONG_SHAPES = {
+    "gla2": dict(kind="gla", h_q=128, h_c=2, d_v=256, d_r=64),
+    "mla": dict(kind="gla", h_q=128, h_c=1, d_v=512, d_r=64),
+    "mla_few": dict(kind="gla", h_q=16, h_c=1, d_v=512, d_r=64),
+    "gta128": dict(kind="gta", h_q=32, h_c=4, d_v=128, d_r=64),
+    "gta64": dict(kind="gta", h_q=32, h_c=4, d_v=64, d_r=32),
+    "gta96": dict(kind="gta", h_q=24, h_c=4, d_v=96, d_r=48),
+    "gqa128": dict(kind="gqa", h_q=32, h_c=4, d_v=128),
+    "gla128": dict(kind="gla", h_q=32, h_c=2, d_v=128, d_r=32),
+}
+
+
+@pytest.mark.parametrize("page_size,lens,T", [(1, [131072 + 77, 300], 1), (2, [70001, 131072 - 3], 2)])
+@pytest.mark.parametrize("shape", list(LONG_SHAPES))
+def test_very_long_sequences_at_tiny_pages(shape, page_size, lens, T):
+    """Page-table rows of 65 000 to 131 000 entries on every MFMA path (LDS and
+    register page-id windows of the first kernel, the per-lane addresses of the
+    second): hundreds of windows per sequence, sampled rows against the oracle."""
+    pages = sum(-(-n // page_size) for n in lens)
+    p = make_problem(f"long_{shape}_{page_size}", seq_lens=lens, T=T, page_size=page_size, num_pages=pages + 1000,
+                     seed=7000 + page_size + len(shape), poison_tail=True, extra_table_cols=1, **LONG_SHAPES[shape])
+    rng = np.random.default_rng(page_size * 100 + len(shape))
+    sel = [(int(rng.integers(0, p.B)), int(rng.integers(0, p.T)), int(rng.integers(0, p.h_q))) for _ in range(12)]
+    check_problem(p, sel=sel, impl=TUNED, what=f"{shape} page {page_size} lens {lens} T={T}")
+
+
 def test_batch_of_empty_sequences():
     """No key anywhere: every output row is zero and every lse is -inf, on both kernels."""
     p = make_problem("all_empty", seq_lens=[0, 0, 0], T=2, h_q=128, h_c=2, d_v=256, seed=520, num_pages=64)
