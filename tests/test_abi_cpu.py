@@ -195,3 +195,16 @@ def test_register_page_windows_keep_their_registers():
 
     found = build.check_register_windows(verbose=False)
     assert len(found) == 2
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: `bench.py --gpus N` with N above 1 (or a WORLD_SIZE above 1) exits with a message that says
+    so, before anything touches a GPU."""
+    import subprocess
+    import sys
+
+    for argv, env in ((["--gpus", "2"], {}), ([], {"WORLD_SIZE": "4"})):
+        r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")] + argv, capture_output=True, text=True,
+                           env=dict(os.environ, **env), timeout=120)
+        assert r.returncode != 0
+        assert "one GPU only" in (r.stdout + r.stderr)
